@@ -1,0 +1,103 @@
+// Internal declarations shared by the translation units of libpoplar.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <stdarg.h>
+#include <vector>
+#include "../../include/poplar.h"
+
+typedef __hip_bfloat16 bf16;
+
+int poplar_fail(int code, const char* fmt, ...);
+
+#define POPLAR_CHECK_HIP(expr)                                                         \
+  do {                                                                                 \
+    hipError_t e_ = (expr);                                                            \
+    if (e_ != hipSuccess)                                                              \
+      return poplar_fail(POPLAR_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));      \
+  } while (0)
+
+#define POPLAR_TRY(expr)            \
+  do {                              \
+    int s_ = (expr);                \
+    if (s_ != POPLAR_OK) return s_; \
+  } while (0)
+
+#define POPLAR_LAUNCH_CHECK() POPLAR_CHECK_HIP(hipGetLastError())
+
+struct poplar_ctx {
+  poplar_model_cfg cfg;
+  hipStream_t stream;
+  poplar_state st;
+  bool bound;
+  std::vector<hipEvent_t> events;  // pool reused by every profiled step
+};
+
+static inline int64_t elt_size(int dtype) { return dtype == POPLAR_BF16 ? 2 : 4; }
+static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// layout.cpp
+struct LayerOffsets {  // element offsets inside one layer block; -1 = absent
+  int64_t g1, b1, wqkv, bqkv, wo, bo, g2, b2, w1, bm1, w2, bm2, count;
+};
+LayerOffsets layer_offsets(const poplar_model_cfg& c);
+struct ModelOffsets {
+  int64_t wte, wpe, layer0, gf, bf, whead, count, layer_count;
+};
+ModelOffsets model_offsets(const poplar_model_cfg& c);
+int validate_cfg(const poplar_model_cfg* cfg);
+
+// ---- kernel launchers (each returns a poplar_status) ------------------------
+// GEMM: C[M,N] = epilogue(sum_k A(m,k) * B(k,n)).
+enum GemmLayout { GEMM_NT = 0, GEMM_NN = 1, GEMM_TN = 2 };
+// NT: A[M,K] row-major (lda), B stored [N,K] row-major (ldb)   -> y = x W^T
+// NN: A[M,K] row-major (lda), B stored [K,N] row-major (ldb)   -> dx = dy W
+// TN: A stored [K,M] row-major (lda), B stored [K,N] (ldb)     -> dW = dy^T x
+enum GemmAct { ACT_NONE = 0, ACT_GELU = 1, ACT_GELU_BWD = 2 };
+struct GemmArgs {
+  int layout;
+  int64_t M, N, K;
+  const void* A; int64_t lda;
+  const void* B; int64_t ldb;
+  void* C; int64_t ldc;
+  int c_float;            // 1: C is float regardless of the input dtype
+  float beta;             // C = acc + beta * C_old  (float C only; 0 or 1)
+  const void* bias;       // lowp [N] or null, added per column
+  const void* residual;   // lowp [M,N] (ldc) or null, added after activation
+  int act;                // ACT_GELU: aux <- pre-activation, C <- gelu;  ACT_GELU_BWD: C <- acc * gelu'(aux)
+  void* aux; int64_t ldaux;
+};
+int gemm_simple(hipStream_t s, int dtype, const GemmArgs& a);
+int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a);
+int gemm(hipStream_t s, int dtype, const GemmArgs& a);
+
+// attention on the fused qkv activation [B*S, 3H]; o [B*S, H]; lse float [B, nh, S]
+int attn_fwd_simple(hipStream_t s, int dtype, int B, int S, int nh, int d, int causal, const void* qkv, void* o, float* lse);
+int attn_bwd_simple(hipStream_t s, int dtype, int B, int S, int nh, int d, int causal, const void* qkv, const void* o,
+                    const void* dout, const float* lse, void* dqkv, float* delta);
+int attn_fwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const void* qkv, void* o, float* lse);
+int attn_bwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const void* qkv, const void* o,
+                   const void* dout, const float* lse, void* dqkv, float* delta);
+
+// row-wise / elementwise kernels (elementwise.hip)
+int layernorm_fwd(hipStream_t s, int dtype, int64_t T, int H, const void* x, const void* g, const void* b, void* y, float* stats, int rms);
+// dx = (dres ? dres : 0) + norm_bwd(dy); partial dgamma/dbeta to `partials` (float [nblk, 2, H]); then reduced into dg/db
+int layernorm_bwd(hipStream_t s, int dtype, int64_t T, int H, const void* dy, const void* x, const void* g, const float* stats,
+                  const void* dres, void* dx, float* dg, float* db, int accumulate, float* partials, int64_t partials_elems, int rms);
+int colsum(hipStream_t s, int dtype, int64_t T, int64_t N, const void* x, int64_t ldx, float* out, int accumulate,
+           float* partials, int64_t partials_elems);
+int swiglu_fwd(hipStream_t s, int dtype, int64_t T, int F, const void* hgu, void* g);
+int swiglu_bwd(hipStream_t s, int dtype, int64_t T, int F, const void* dg, const void* hgu, void* dhgu);
+int rope_inplace(hipStream_t s, int dtype, int B, int S, int nh, int d, void* qkv, int64_t ld, float sign);
+int embed_fwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok, int64_t tok_ld, const void* wte, const void* wpe, void* x);
+int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok, int64_t tok_ld, const void* dx, float* dwte, float* dwpe, int accumulate);
+int xent_fwd_bwd(hipStream_t s, int dtype, int64_t T, int V, int64_t ld, void* logits, const int32_t* targets, int64_t tgt_ld, int S,
+                 float loss_scale, float* loss, float* row_loss);
+int adam_shard(hipStream_t s, int lowp_dtype, float* p, float* m, float* v, const float* g, void* p_lowp, int64_t n,
+               int step_t, float lr, float b1, float b2, float eps);
+int zero2_reduce_local(hipStream_t s, float* gshard, const float* g_unit, int64_t unit_lo, int64_t unit_hi, int64_t shard_off, int64_t shard_len);
+int zero3_gather_local(hipStream_t s, int dtype, void* out, const void* own, const void* peers, int64_t lo, int64_t hi, int64_t shard_off, int64_t shard_len);
+int fill_zero(hipStream_t s, void* p, int64_t bytes);
+int cast_f32_to_lowp(hipStream_t s, int dtype, const float* in, void* out, int64_t n);

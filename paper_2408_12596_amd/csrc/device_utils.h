@@ -1,0 +1,103 @@
+// Device-side helpers: 16-byte vector access for float / bfloat16 rows and
+// 64-lane wavefront reductions.
+#pragma once
+#include "common.h"
+
+#define WAVE 64
+
+template <typename T> struct Vec;  // 16 bytes of T
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  float4 raw;
+  __device__ void load(const float* p) { raw = *reinterpret_cast<const float4*>(p); }
+  __device__ void store(float* p) const { *reinterpret_cast<float4*>(p) = raw; }
+  __device__ void unpack(float* f) const { f[0] = raw.x; f[1] = raw.y; f[2] = raw.z; f[3] = raw.w; }
+  __device__ void pack(const float* f) { raw = make_float4(f[0], f[1], f[2], f[3]); }
+};
+
+__device__ inline float bf16_bits_to_float(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
+// round-to-nearest-even float -> bfloat16 bits (NaN kept quiet)
+__device__ inline uint32_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <> struct Vec<bf16> {
+  static constexpr int N = 8;
+  uint4 raw;
+  __device__ void load(const bf16* p) { raw = *reinterpret_cast<const uint4*>(p); }
+  __device__ void store(bf16* p) const { *reinterpret_cast<uint4*>(p) = raw; }
+  __device__ void unpack(float* f) const {
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  __device__ void pack(const float* f) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = float_to_bf16_bits(f[2 * i]) | (float_to_bf16_bits(f[2 * i + 1]) << 16);
+    raw = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+template <typename T> __device__ inline float to_float(T v);
+template <> __device__ inline float to_float<float>(float v) { return v; }
+template <> __device__ inline float to_float<bf16>(bf16 v) {
+  return bf16_bits_to_float(*reinterpret_cast<const uint16_t*>(&v));
+}
+template <typename T> __device__ inline T from_float(float f);
+template <> __device__ inline float from_float<float>(float f) { return f; }
+template <> __device__ inline bf16 from_float<bf16>(float f) {
+  uint16_t b = (uint16_t)float_to_bf16_bits(f);
+  return *reinterpret_cast<bf16*>(&b);
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+  return v;
+}
+
+// make LDS writes of this wavefront visible to its other lanes
+__device__ inline void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// tanh-form GeLU and its derivative (the form GPT-2 uses)
+__device__ inline float gelu_tanh(float h) {
+  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
+  float t = tanhf(k0 * (h + k1 * h * h * h));
+  return 0.5f * h * (1.0f + t);
+}
+__device__ inline float gelu_tanh_grad(float h) {
+  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
+  float t = tanhf(k0 * (h + k1 * h * h * h));
+  float dt = (1.0f - t * t) * k0 * (1.0f + 3.0f * k1 * h * h);
+  return 0.5f * (1.0f + t) + 0.5f * h * dt;
+}
+
+// streaming (non-temporal) 16-byte / 8-byte accesses: index i counts vectors
+typedef float nt_f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t nt_u2 __attribute__((ext_vector_type(2)));
+__device__ inline float4 nt_load4(const float* base, int64_t i) {
+  nt_f4 v = __builtin_nontemporal_load(reinterpret_cast<const nt_f4*>(base) + i);
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ inline void nt_store4(float* base, int64_t i, float4 v) {
+  nt_f4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<nt_f4*>(base) + i);
+}
+__device__ inline void nt_store2(uint32_t* base, int64_t i, uint2 v) {
+  nt_u2 t = {v.x, v.y};
+  __builtin_nontemporal_store(t, reinterpret_cast<nt_u2*>(base) + i);
+}

@@ -1,0 +1,736 @@
+// HBM-bound kernels of the training step: Adam on a shard, the single-rank
+// share of the ZeRO-2 / ZeRO-3 collectives, LayerNorm / RMSNorm forward and
+// backward, column sums (bias gradients), SwiGLU, RoPE, embedding, and the
+// softmax cross-entropy.  All use 16-byte accesses per lane and 64-lane
+// wavefront reductions; math is float whatever the storage type.
+#include "device_utils.h"
+
+#define DISPATCH_DTYPE(dtype, ...)                                         \
+  do {                                                                      \
+    if ((dtype) == POPLAR_BF16) { typedef bf16 T; __VA_ARGS__; }            \
+    else { typedef float T; __VA_ARGS__; }                                  \
+  } while (0)
+
+static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+static inline int grid_for(int64_t work_items, int block, int max_blocks = 256 * 16) {
+  int64_t g = cdiv(work_items, block);
+  if (g < 1) g = 1;
+  if (g > max_blocks) g = max_blocks;
+  return (int)g;
+}
+
+// ---------------------------------------------------------------------------
+// fill
+// ---------------------------------------------------------------------------
+__global__ void fill_zero_kernel(uint32_t* p, int64_t n_words) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n_words; i += stride) p[i] = 0u;
+}
+int fill_zero(hipStream_t s, void* p, int64_t bytes) {
+  if (bytes == 0) return POPLAR_OK;
+  if (bytes % 4 || ((uintptr_t)p & 3)) return poplar_fail(POPLAR_ERR_INVALID, "fill_zero needs 4-byte granularity");
+  int64_t n = bytes / 4;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, (uint32_t*)p, n);
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+template <typename T>
+__global__ void cast_kernel(const float* __restrict__ in, T* __restrict__ out, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) out[i] = from_float<T>(in[i]);
+}
+int cast_f32_to_lowp(hipStream_t s, int dtype, const float* in, void* out, int64_t n) {
+  if (n == 0) return POPLAR_OK;
+  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(cast_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, s, in, (T*)out, n));
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Adam on a shard.  Per element: read g, p, m, v (16 B), write p, m, v (12 B)
+// and the rounded low-precision copy (2 B for bf16).
+// ---------------------------------------------------------------------------
+struct AdamConst { float lr, b1, b2, eps, omb1, omb2, inv_bc1, inv_bc2; };
+
+__device__ inline void adam_one(float g, float& p, float& m, float& v, const AdamConst& c) {
+  // explicit roundings: every element sees the same operations whichever
+  // kernel (vector body, scalar tail) or shard it falls in
+  m = __fmaf_rn(c.b1, m, __fmul_rn(c.omb1, g));
+  v = __fmaf_rn(c.b2, v, __fmul_rn(__fmul_rn(c.omb2, g), g));
+  float mhat = __fmul_rn(m, c.inv_bc1);
+  float vhat = __fmul_rn(v, c.inv_bc2);
+  p = __fsub_rn(p, __fdiv_rn(__fmul_rn(c.lr, mhat), __fadd_rn(__fsqrt_rn(vhat), c.eps)));
+}
+
+template <typename L, bool HAS_LOWP>
+__global__ void __launch_bounds__(256) adam_vec_kernel(float* __restrict__ p, float* __restrict__ m, float* __restrict__ v,
+                                                        const float* __restrict__ g, L* __restrict__ lowp, int64_t n4, AdamConst c) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n4; i += stride) {
+    float4 gg = nt_load4(g, i);
+    float4 pp = nt_load4(p, i);
+    float4 mm = nt_load4(m, i);
+    float4 vv = nt_load4(v, i);
+    adam_one(gg.x, pp.x, mm.x, vv.x, c);
+    adam_one(gg.y, pp.y, mm.y, vv.y, c);
+    adam_one(gg.z, pp.z, mm.z, vv.z, c);
+    adam_one(gg.w, pp.w, mm.w, vv.w, c);
+    nt_store4(p, i, pp);
+    nt_store4(m, i, mm);
+    nt_store4(v, i, vv);
+    if (HAS_LOWP) {
+      if (sizeof(L) == 2) {
+        uint2 w;
+        w.x = float_to_bf16_bits(pp.x) | (float_to_bf16_bits(pp.y) << 16);
+        w.y = float_to_bf16_bits(pp.z) | (float_to_bf16_bits(pp.w) << 16);
+        nt_store2(reinterpret_cast<uint32_t*>(lowp), i, w);
+      } else {
+        nt_store4(reinterpret_cast<float*>(lowp), i, pp);
+      }
+    }
+  }
+}
+
+template <typename L, bool HAS_LOWP>
+__global__ void adam_scalar_kernel(float* __restrict__ p, float* __restrict__ m, float* __restrict__ v,
+                                   const float* __restrict__ g, L* __restrict__ lowp, int64_t begin, int64_t n, AdamConst c) {
+  int64_t i = begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    float pp = p[i], mm = m[i], vv = v[i];
+    adam_one(g[i], pp, mm, vv, c);
+    p[i] = pp; m[i] = mm; v[i] = vv;
+    if (HAS_LOWP) lowp[i] = from_float<L>(pp);
+  }
+}
+
+template <typename L, bool HAS_LOWP>
+static int adam_launch(hipStream_t s, float* p, float* m, float* v, const float* g, L* lowp, int64_t n, const AdamConst& c) {
+  bool vec = aligned16(p) && aligned16(m) && aligned16(v) && aligned16(g) && (!HAS_LOWP || ((uintptr_t)lowp & 15) == 0);
+  int64_t n4 = vec ? n / 4 : 0;
+  if (n4 > 0) {
+    hipLaunchKernelGGL((adam_vec_kernel<L, HAS_LOWP>), dim3(grid_for(n4, 256, 256 * 32)), dim3(256), 0, s, p, m, v, g, lowp, n4, c);
+    POPLAR_LAUNCH_CHECK();
+  }
+  if (n4 * 4 < n) {
+    hipLaunchKernelGGL((adam_scalar_kernel<L, HAS_LOWP>), dim3(grid_for(n - n4 * 4, 256)), dim3(256), 0, s, p, m, v, g, lowp, n4 * 4, n, c);
+    POPLAR_LAUNCH_CHECK();
+  }
+  return POPLAR_OK;
+}
+
+int adam_shard(hipStream_t s, int lowp_dtype, float* p, float* m, float* v, const float* g, void* p_lowp, int64_t n,
+               int step_t, float lr, float b1, float b2, float eps) {
+  if (n == 0) return POPLAR_OK;
+  AdamConst c;
+  c.lr = lr; c.b1 = b1; c.b2 = b2; c.eps = eps;
+  c.omb1 = 1.0f - b1; c.omb2 = 1.0f - b2;
+  c.inv_bc1 = (float)(1.0 / (1.0 - pow((double)b1, (double)step_t)));
+  c.inv_bc2 = (float)(1.0 / (1.0 - pow((double)b2, (double)step_t)));
+  if (!p_lowp) return adam_launch<float, false>(s, p, m, v, g, (float*)nullptr, n, c);
+  if (lowp_dtype == POPLAR_BF16) return adam_launch<bf16, true>(s, p, m, v, g, (bf16*)p_lowp, n, c);
+  return adam_launch<float, true>(s, p, m, v, g, (float*)p_lowp, n, c);
+}
+
+// ---------------------------------------------------------------------------
+// ZeRO-2 local reduce and ZeRO-3 local gather
+// ---------------------------------------------------------------------------
+__global__ void axpy_vec_kernel(float* __restrict__ dst, const float* __restrict__ src, int64_t n4) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n4; i += stride) {
+    float4 a = reinterpret_cast<float4*>(dst)[i];
+    float4 b = nt_load4(src, i);
+    a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    reinterpret_cast<float4*>(dst)[i] = a;
+  }
+}
+__global__ void axpy_scalar_kernel(float* __restrict__ dst, const float* __restrict__ src, int64_t begin, int64_t n) {
+  int64_t i = begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] += src[i];
+}
+
+int zero2_reduce_local(hipStream_t s, float* gshard, const float* g_unit, int64_t unit_lo, int64_t unit_hi,
+                       int64_t shard_off, int64_t shard_len) {
+  int64_t lo = unit_lo > shard_off ? unit_lo : shard_off;
+  int64_t hi = unit_hi < shard_off + shard_len ? unit_hi : shard_off + shard_len;
+  if (hi <= lo) return POPLAR_OK;
+  float* dst = gshard + (lo - shard_off);
+  const float* src = g_unit + (lo - unit_lo);
+  int64_t n = hi - lo;
+  int64_t n4 = (aligned16(dst) && aligned16(src)) ? n / 4 : 0;
+  if (n4 > 0) {
+    hipLaunchKernelGGL(axpy_vec_kernel, dim3(grid_for(n4, 256, 256 * 32)), dim3(256), 0, s, dst, src, n4);
+    POPLAR_LAUNCH_CHECK();
+  }
+  if (n4 * 4 < n) {
+    hipLaunchKernelGGL(axpy_scalar_kernel, dim3(grid_for(n - n4 * 4, 256, 256 * 32)), dim3(256), 0, s, dst, src, n4 * 4, n);
+    POPLAR_LAUNCH_CHECK();
+  }
+  return POPLAR_OK;
+}
+
+// out[i - lo] = (i in own shard) ? own[i - shard_off] : peers[i]; W = words of 16 or 2/4 bytes
+template <typename W>
+__global__ void gather_kernel(W* __restrict__ out, const W* __restrict__ own, const W* __restrict__ peers,
+                              int64_t lo, int64_t n, int64_t own_lo, int64_t own_hi) {
+  // all indices in units of W; own_lo/own_hi are the shard bounds in the same units
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    int64_t f = lo + i;
+    out[i] = (f >= own_lo && f < own_hi) ? own[f - own_lo] : peers[f];
+  }
+}
+
+int zero3_gather_local(hipStream_t s, int dtype, void* out, const void* own, const void* peers, int64_t lo, int64_t hi,
+                       int64_t shard_off, int64_t shard_len) {
+  if (hi <= lo) return POPLAR_OK;
+  const int64_t es = elt_size(dtype);
+  const int64_t per = 16 / es;  // elements per 16-byte word
+  int64_t n = hi - lo;
+  bool vec = aligned16(out) && aligned16(own) && aligned16(peers) && lo % per == 0 && n % per == 0 &&
+             shard_off % per == 0 && shard_len % per == 0;
+  if (vec) {
+    hipLaunchKernelGGL(gather_kernel<uint4>, dim3(grid_for(n / per, 256, 256 * 32)), dim3(256), 0, s, (uint4*)out, (const uint4*)own,
+                       (const uint4*)peers, lo / per, n / per, shard_off / per, (shard_off + shard_len) / per);
+  } else if (es == 2) {
+    hipLaunchKernelGGL(gather_kernel<uint16_t>, dim3(grid_for(n, 256, 256 * 32)), dim3(256), 0, s, (uint16_t*)out, (const uint16_t*)own,
+                       (const uint16_t*)peers, lo, n, shard_off, shard_off + shard_len);
+  } else {
+    hipLaunchKernelGGL(gather_kernel<uint32_t>, dim3(grid_for(n, 256, 256 * 32)), dim3(256), 0, s, (uint32_t*)out, (const uint32_t*)own,
+                       (const uint32_t*)peers, lo, n, shard_off, shard_off + shard_len);
+  }
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// LayerNorm / RMSNorm.  One wavefront per row, the row held in registers
+// (NV 16-byte vectors per lane), so x is read from HBM once.
+// stats: float [T, 2] = (mean, rstd); RMSNorm stores mean = 0.
+// ---------------------------------------------------------------------------
+template <typename T, int NV, bool RMS>
+__global__ void __launch_bounds__(256) norm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ g, const T* __restrict__ b,
+                                                        T* __restrict__ y, float* __restrict__ stats, int64_t rows, int H) {
+  constexpr int VN = Vec<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  for (int64_t r = wave; r < rows; r += nwaves) {
+    const T* xr = x + r * H;
+    float f[NV][VN];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      int c = (i * 64 + lane) * VN;
+      if (c < H) {
+        Vec<T> v; v.load(xr + c); v.unpack(f[i]);
+#pragma unroll
+        for (int k = 0; k < VN; ++k) sum += RMS ? f[i][k] * f[i][k] : f[i][k];
+      }
+    }
+    sum = wave_sum(sum);
+    float mean = 0.f, var;
+    if (RMS) {
+      var = sum / H;
+    } else {
+      mean = sum / H;
+      float sq = 0.f;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        int c = (i * 64 + lane) * VN;
+        if (c < H) {
+#pragma unroll
+          for (int k = 0; k < VN; ++k) { float d = f[i][k] - mean; sq += d * d; }
+        }
+      }
+      var = wave_sum(sq) / H;
+    }
+    float rstd = 1.0f / sqrtf(var + 1e-5f);
+    if (lane == 0) { stats[2 * r] = mean; stats[2 * r + 1] = rstd; }
+    T* yr = y + r * H;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      int c = (i * 64 + lane) * VN;
+      if (c < H) {
+        float gg[VN], bb[VN], o[VN];
+        Vec<T> v; v.load(g + c); v.unpack(gg);
+        if (!RMS) { v.load(b + c); v.unpack(bb); }
+#pragma unroll
+        for (int k = 0; k < VN; ++k) o[k] = (f[i][k] - mean) * rstd * gg[k] + (RMS ? 0.f : bb[k]);
+        v.pack(o); v.store(yr + c);
+      }
+    }
+  }
+}
+
+template <typename T, bool RMS>
+static int norm_fwd_launch(hipStream_t s, int64_t rows, int H, const T* x, const T* g, const T* b, T* y, float* stats) {
+  constexpr int VN = Vec<T>::N;
+  int need = (int)cdiv(H, 64 * VN);
+  int grid = grid_for(rows, 4, 256 * 8);
+#define NORM_FWD_CASE(NVV) \
+  hipLaunchKernelGGL((norm_fwd_kernel<T, NVV, RMS>), dim3(grid), dim3(256), 0, s, x, g, b, y, stats, rows, H)
+  if (need <= 1) NORM_FWD_CASE(1);
+  else if (need <= 2) NORM_FWD_CASE(2);
+  else if (need <= 4) NORM_FWD_CASE(4);
+  else if (need <= 8) NORM_FWD_CASE(8);
+  else if (need <= 16) NORM_FWD_CASE(16);
+  else return poplar_fail(POPLAR_ERR_INVALID, "hidden %d too large for the norm kernel", H);
+#undef NORM_FWD_CASE
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+int layernorm_fwd(hipStream_t s, int dtype, int64_t T_, int H, const void* x, const void* g, const void* b, void* y, float* stats, int rms) {
+  if (T_ == 0) return POPLAR_OK;
+  DISPATCH_DTYPE(dtype, {
+    if (rms) return norm_fwd_launch<T, true>(s, T_, H, (const T*)x, (const T*)g, (const T*)b, (T*)y, stats);
+    return norm_fwd_launch<T, false>(s, T_, H, (const T*)x, (const T*)g, (const T*)b, (T*)y, stats);
+  });
+  return POPLAR_OK;
+}
+
+// Backward: dx = dres + rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)),  dxhat = dy * gamma
+// (RMSNorm drops the mean(dxhat) term).  Each wave walks rows r = wave, wave + nwaves, ...
+// and keeps per-column partial sums of dy*xhat (dgamma) and dy (dbeta) in
+// registers; the four waves of a block are added through LDS and the block
+// writes one row of `partials` [nblocks, 2, H].
+template <typename T, int NV, bool RMS>
+__global__ void __launch_bounds__(256) norm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, const T* __restrict__ g,
+                                                        const float* __restrict__ stats, const T* __restrict__ dres,
+                                                        T* __restrict__ dx, float* __restrict__ partials, int64_t rows, int H) {
+  constexpr int VN = Vec<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int wv = threadIdx.x >> 6;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + wv;
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  float accg[NV][VN], accb[NV][VN], gam[NV][VN];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int c = (i * 64 + lane) * VN;
+#pragma unroll
+    for (int k = 0; k < VN; ++k) { accg[i][k] = 0.f; accb[i][k] = 0.f; gam[i][k] = 0.f; }
+    if (c < H) { Vec<T> v; v.load(g + c); v.unpack(gam[i]); }
+  }
+  for (int64_t r = wave; r < rows; r += nwaves) {
+    const float mean = stats[2 * r], rstd = stats[2 * r + 1];
+    float xh[NV][VN], dxh[NV][VN];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      int c = (i * 64 + lane) * VN;
+      if (c < H) {
+        float xv[VN], dv[VN];
+        Vec<T> v; v.load(x + r * H + c); v.unpack(xv);
+        v.load(dy + r * H + c); v.unpack(dv);
+#pragma unroll
+        for (int k = 0; k < VN; ++k) {
+          xh[i][k] = (xv[k] - mean) * rstd;
+          dxh[i][k] = dv[k] * gam[i][k];
+          accg[i][k] += dv[k] * xh[i][k];
+          accb[i][k] += dv[k];
+          s1 += dxh[i][k];
+          s2 += dxh[i][k] * xh[i][k];
+        }
+      }
+    }
+    s1 = RMS ? 0.f : wave_sum(s1) / H;
+    s2 = wave_sum(s2) / H;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      int c = (i * 64 + lane) * VN;
+      if (c < H) {
+        float o[VN], rs[VN];
+        Vec<T> v;
+        if (dres) { v.load(dres + r * H + c); v.unpack(rs); }
+#pragma unroll
+        for (int k = 0; k < VN; ++k) o[k] = rstd * (dxh[i][k] - s1 - xh[i][k] * s2) + (dres ? rs[k] : 0.f);
+        v.pack(o); v.store(dx + r * H + c);
+      }
+    }
+  }
+  // block reduction of the per-wave column sums
+  extern __shared__ float lds[];  // [4][2][H]
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int c = (i * 64 + lane) * VN;
+    if (c < H) {
+#pragma unroll
+      for (int k = 0; k < VN; ++k) {
+        lds[(wv * 2 + 0) * H + c + k] = accg[i][k];
+        lds[(wv * 2 + 1) * H + c + k] = accb[i][k];
+      }
+    }
+  }
+  __syncthreads();
+  float* outp = partials + (int64_t)blockIdx.x * 2 * H;
+  for (int j = threadIdx.x; j < 2 * H; j += 256)
+    outp[j] = lds[j] + lds[2 * H + j] + lds[4 * H + j] + lds[6 * H + j];
+}
+
+// out[j] (+)= sum_c partials[c * stride + j]
+__global__ void reduce_partials_kernel(const float* __restrict__ partials, int nchunks, int64_t stride, float* __restrict__ out,
+                                       int64_t n, int accumulate) {
+  int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  float acc = 0.f;
+  for (int c = 0; c < nchunks; ++c) acc += partials[c * stride + j];
+  out[j] = accumulate ? out[j] + acc : acc;
+}
+
+static int norm_bwd_blocks(int64_t rows) {
+  int64_t b = cdiv(rows, 16);  // at least 4 rows per wave
+  if (b > 512) b = 512;
+  if (b < 1) b = 1;
+  return (int)b;
+}
+
+template <typename T, bool RMS>
+static int norm_bwd_launch(hipStream_t s, int64_t rows, int H, const T* dy, const T* x, const T* g, const float* stats, const T* dres,
+                           T* dx, float* partials, int grid) {
+  constexpr int VN = Vec<T>::N;
+  int need = (int)cdiv(H, 64 * VN);
+  size_t lds = (size_t)8 * H * sizeof(float);
+#define NORM_BWD_CASE(NVV) \
+  hipLaunchKernelGGL((norm_bwd_kernel<T, NVV, RMS>), dim3(grid), dim3(256), lds, s, dy, x, g, stats, dres, dx, partials, rows, H)
+  if (need <= 1) NORM_BWD_CASE(1);
+  else if (need <= 2) NORM_BWD_CASE(2);
+  else if (need <= 4) NORM_BWD_CASE(4);
+  else if (need <= 8) NORM_BWD_CASE(8);
+  else return poplar_fail(POPLAR_ERR_INVALID, "hidden %d too large for the norm backward kernel", H);
+#undef NORM_BWD_CASE
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+int layernorm_bwd(hipStream_t s, int dtype, int64_t T_, int H, const void* dy, const void* x, const void* g, const float* stats,
+                  const void* dres, void* dx, float* dg, float* db, int accumulate, float* partials, int64_t partials_elems, int rms) {
+  if (T_ == 0) return POPLAR_OK;
+  int grid = norm_bwd_blocks(T_);
+  if ((int64_t)grid * 2 * H > partials_elems) return poplar_fail(POPLAR_ERR_OOM, "norm backward scratch too small");
+  if ((size_t)8 * H * sizeof(float) > 160 * 1024) return poplar_fail(POPLAR_ERR_INVALID, "hidden %d too large for the norm backward kernel", H);
+  DISPATCH_DTYPE(dtype, {
+    if (rms) POPLAR_TRY((norm_bwd_launch<T, true>(s, T_, H, (const T*)dy, (const T*)x, (const T*)g, stats, (const T*)dres, (T*)dx, partials, grid)));
+    else POPLAR_TRY((norm_bwd_launch<T, false>(s, T_, H, (const T*)dy, (const T*)x, (const T*)g, stats, (const T*)dres, (T*)dx, partials, grid)));
+  });
+  // dgamma = partials[:, 0, :], dbeta = partials[:, 1, :]
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((int)cdiv(H, 256)), dim3(256), 0, s, partials, grid, (int64_t)2 * H, dg, (int64_t)H, accumulate);
+  POPLAR_LAUNCH_CHECK();
+  if (!rms) {
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((int)cdiv(H, 256)), dim3(256), 0, s, partials + H, grid, (int64_t)2 * H, db, (int64_t)H, accumulate);
+    POPLAR_LAUNCH_CHECK();
+  }
+  return POPLAR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Column sums (bias gradients): out[n] (+)= sum_t x[t, n].
+// grid = (column strips of 64*VN, row chunks); 4 waves split the chunk's rows.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) colsum_kernel(const T* __restrict__ x, int64_t ldx, int64_t rows, int64_t N, int rows_per_chunk,
+                                                      float* __restrict__ partials) {
+  constexpr int VN = Vec<T>::N;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * VN;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_chunk;
+  int64_t r1 = r0 + rows_per_chunk;
+  if (r1 > rows) r1 = rows;
+  float acc[VN];
+#pragma unroll
+  for (int k = 0; k < VN; ++k) acc[k] = 0.f;
+  if (c < N) {
+    for (int64_t r = r0 + wv; r < r1; r += 4) {
+      float f[VN];
+      Vec<T> v; v.load(x + r * ldx + c); v.unpack(f);
+#pragma unroll
+      for (int k = 0; k < VN; ++k) acc[k] += f[k];
+    }
+  }
+  __shared__ float lds[4][64 * VN];
+#pragma unroll
+  for (int k = 0; k < VN; ++k) lds[wv][lane * VN + k] = acc[k];
+  __syncthreads();
+  for (int j = threadIdx.x; j < 64 * VN; j += 256) {
+    int64_t col = (int64_t)blockIdx.x * 64 * VN + j;
+    if (col < N) partials[(int64_t)blockIdx.y * N + col] = lds[0][j] + lds[1][j] + lds[2][j] + lds[3][j];
+  }
+}
+
+int colsum(hipStream_t s, int dtype, int64_t T_, int64_t N, const void* x, int64_t ldx, float* out, int accumulate,
+           float* partials, int64_t partials_elems) {
+  if (T_ == 0 || N == 0) return POPLAR_OK;
+  const int VN = dtype == POPLAR_BF16 ? 8 : 4;
+  if (N % VN) return poplar_fail(POPLAR_ERR_INVALID, "colsum needs N %% %d == 0", VN);
+  int strips = (int)cdiv(N, 64 * VN);
+  int chunks = (int)cdiv(2048, strips);
+  if (chunks > cdiv(T_, 32)) chunks = (int)cdiv(T_, 32);
+  if (chunks < 1) chunks = 1;
+  int rpc = (int)cdiv(T_, chunks);
+  chunks = (int)cdiv(T_, rpc);
+  if ((int64_t)chunks * N > partials_elems) return poplar_fail(POPLAR_ERR_OOM, "colsum scratch too small");
+  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(colsum_kernel<T>, dim3(strips, chunks), dim3(256), 0, s, (const T*)x, ldx, T_, N, rpc, partials));
+  POPLAR_LAUNCH_CHECK();
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((int)cdiv(N, 256)), dim3(256), 0, s, partials, chunks, N, out, N, accumulate);
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// SwiGLU on the fused [T, 2F] gate|up activation: g = silu(hg) * hu
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void swiglu_fwd_kernel(const T* __restrict__ hgu, T* __restrict__ g, int64_t rows, int F) {
+  constexpr int VN = Vec<T>::N;
+  const int64_t per_row = F / VN;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < rows * per_row; i += stride) {
+    int64_t r = i / per_row, c = (i % per_row) * VN;
+    float a[VN], b[VN], o[VN];
+    Vec<T> v; v.load(hgu + r * 2 * F + c); v.unpack(a);
+    v.load(hgu + r * 2 * F + F + c); v.unpack(b);
+#pragma unroll
+    for (int k = 0; k < VN; ++k) o[k] = a[k] / (1.0f + __expf(-a[k])) * b[k];
+    v.pack(o); v.store(g + r * F + c);
+  }
+}
+template <typename T>
+__global__ void swiglu_bwd_kernel(const T* __restrict__ dg, const T* __restrict__ hgu, T* __restrict__ dhgu, int64_t rows, int F) {
+  constexpr int VN = Vec<T>::N;
+  const int64_t per_row = F / VN;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < rows * per_row; i += stride) {
+    int64_t r = i / per_row, c = (i % per_row) * VN;
+    float a[VN], b[VN], d[VN], oa[VN], ob[VN];
+    Vec<T> v; v.load(hgu + r * 2 * F + c); v.unpack(a);
+    v.load(hgu + r * 2 * F + F + c); v.unpack(b);
+    v.load(dg + r * F + c); v.unpack(d);
+#pragma unroll
+    for (int k = 0; k < VN; ++k) {
+      float sg = 1.0f / (1.0f + __expf(-a[k]));
+      oa[k] = d[k] * b[k] * (sg + a[k] * sg * (1.0f - sg));
+      ob[k] = d[k] * a[k] * sg;
+    }
+    v.pack(oa); v.store(dhgu + r * 2 * F + c);
+    v.pack(ob); v.store(dhgu + r * 2 * F + F + c);
+  }
+}
+int swiglu_fwd(hipStream_t s, int dtype, int64_t T_, int F, const void* hgu, void* g) {
+  if (T_ == 0) return POPLAR_OK;
+  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(swiglu_fwd_kernel<T>, dim3(grid_for(T_ * F / Vec<T>::N, 256)), dim3(256), 0, s, (const T*)hgu, (T*)g, T_, F));
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+int swiglu_bwd(hipStream_t s, int dtype, int64_t T_, int F, const void* dg, const void* hgu, void* dhgu) {
+  if (T_ == 0) return POPLAR_OK;
+  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(swiglu_bwd_kernel<T>, dim3(grid_for(T_ * F / Vec<T>::N, 256)), dim3(256), 0, s, (const T*)dg, (const T*)hgu, (T*)dhgu, T_, F));
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// RoPE in place on the q and k thirds of qkv [B*S, ld]: element i of a head is
+// paired with i + d/2 and rotated by pos * 10000^(-2i/d).  One thread owns one
+// (token, i) pair, evaluates the angle once in double and walks all heads.
+// sign = -1 applies the inverse rotation (the backward pass).
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void rope_kernel(T* __restrict__ qkv, int64_t ld, int64_t tokens, int S, int nh, int d, float sign) {
+  const int half = d / 2;
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= tokens * half) return;
+  const int64_t t = idx / half;
+  const int i = (int)(idx % half);
+  const int pos = (int)(t % S);
+  const double ang = (double)pos * pow(10000.0, -2.0 * (double)i / (double)d);
+  double sd, cd;
+  sincos(ang, &sd, &cd);
+  const float c = (float)cd, sn = sign * (float)sd;
+  const int H = nh * d;
+  T* row = qkv + t * ld;
+  for (int part = 0; part < 2; ++part) {
+    for (int h = 0; h < nh; ++h) {
+      T* p = row + part * H + h * d + i;
+      float x1 = to_float<T>(p[0]), x2 = to_float<T>(p[half]);
+      p[0] = from_float<T>(x1 * c - x2 * sn);
+      p[half] = from_float<T>(x2 * c + x1 * sn);
+    }
+  }
+}
+int rope_inplace(hipStream_t s, int dtype, int B, int S, int nh, int d, void* qkv, int64_t ld, float sign) {
+  int64_t work = (int64_t)B * S * (d / 2);
+  if (work == 0) return POPLAR_OK;
+  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, s, (T*)qkv, ld, (int64_t)B * S, S, nh, d, sign));
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Embedding
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void embed_fwd_kernel(const int32_t* __restrict__ tok, int64_t tok_ld, const T* __restrict__ wte, const T* __restrict__ wpe,
+                                 T* __restrict__ x, int64_t tokens, int S, int H) {
+  constexpr int VN = Vec<T>::N;
+  const int per_row = H / VN;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < tokens * per_row; i += stride) {
+    int64_t t = i / per_row;
+    int c = (int)(i % per_row) * VN;
+    int64_t b = t / S, sp = t % S;
+    int id = tok[b * tok_ld + sp];
+    float a[VN], p[VN];
+    Vec<T> v; v.load(wte + (int64_t)id * H + c); v.unpack(a);
+    if (wpe) {
+      v.load(wpe + sp * H + c); v.unpack(p);
+#pragma unroll
+      for (int k = 0; k < VN; ++k) a[k] += p[k];
+    }
+    v.pack(a); v.store(x + t * H + c);
+  }
+}
+int embed_fwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok, int64_t tok_ld, const void* wte, const void* wpe, void* x) {
+  int64_t tokens = (int64_t)B * S;
+  if (tokens == 0) return POPLAR_OK;
+  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(embed_fwd_kernel<T>, dim3(grid_for(tokens * H / Vec<T>::N, 256)), dim3(256), 0, s, tok, tok_ld,
+                                           (const T*)wte, (const T*)wpe, (T*)x, tokens, S, H));
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+template <typename T>
+__global__ void embed_bwd_wte_kernel(const int32_t* __restrict__ tok, int64_t tok_ld, const T* __restrict__ dx, float* __restrict__ dwte,
+                                     int64_t tokens, int S, int H) {
+  constexpr int VN = Vec<T>::N;
+  const int per_row = H / VN;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < tokens * per_row; i += stride) {
+    int64_t t = i / per_row;
+    int c = (int)(i % per_row) * VN;
+    int id = tok[(t / S) * tok_ld + (t % S)];
+    float a[VN];
+    Vec<T> v; v.load(dx + t * H + c); v.unpack(a);
+#pragma unroll
+    for (int k = 0; k < VN; ++k) unsafeAtomicAdd(dwte + (int64_t)id * H + c + k, a[k]);
+  }
+}
+template <typename T>
+__global__ void embed_bwd_wpe_kernel(const T* __restrict__ dx, float* __restrict__ dwpe, int B, int S, int H, int accumulate) {
+  constexpr int VN = Vec<T>::N;
+  const int per_row = H / VN;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)S * per_row) return;
+  int64_t sp = i / per_row;
+  int c = (int)(i % per_row) * VN;
+  float acc[VN];
+#pragma unroll
+  for (int k = 0; k < VN; ++k) acc[k] = 0.f;
+  for (int b = 0; b < B; ++b) {
+    float a[VN];
+    Vec<T> v; v.load(dx + ((int64_t)b * S + sp) * H + c); v.unpack(a);
+#pragma unroll
+    for (int k = 0; k < VN; ++k) acc[k] += a[k];
+  }
+  float* o = dwpe + sp * H + c;
+#pragma unroll
+  for (int k = 0; k < VN; ++k) o[k] = accumulate ? o[k] + acc[k] : acc[k];
+}
+int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok, int64_t tok_ld, const void* dx, float* dwte, float* dwpe, int accumulate) {
+  int64_t tokens = (int64_t)B * S;
+  if (tokens == 0) return POPLAR_OK;
+  DISPATCH_DTYPE(dtype, {
+    hipLaunchKernelGGL(embed_bwd_wte_kernel<T>, dim3(grid_for(tokens * H / Vec<T>::N, 256)), dim3(256), 0, s, tok, tok_ld, (const T*)dx, dwte, tokens, S, H);
+    POPLAR_LAUNCH_CHECK();
+    if (dwpe) {
+      hipLaunchKernelGGL(embed_bwd_wpe_kernel<T>, dim3((unsigned)cdiv((int64_t)S * H / Vec<T>::N, 256)), dim3(256), 0, s, (const T*)dx, dwpe, B, S, H, accumulate);
+      POPLAR_LAUNCH_CHECK();
+    }
+  });
+  return POPLAR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Softmax cross-entropy over logits [T, ld] (V valid columns), in place:
+// logits <- loss_scale * (softmax - onehot(target)), columns V..ld-1 <- 0;
+// row_loss[t] = logsumexp - logit[target].  One block per row, two passes over
+// the row (online max / sum first, gradient second).
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) xent_kernel(T* __restrict__ logits, int64_t ld, int V, const int32_t* __restrict__ targets,
+                                                    int64_t tgt_ld, int S, float loss_scale, float* __restrict__ row_loss) {
+  constexpr int VN = Vec<T>::N;
+  const int64_t t = blockIdx.x;
+  T* row = logits + t * ld;
+  const int nvec = (int)(ld / VN);
+  float mx = -INFINITY, sum = 0.f;
+  for (int i = threadIdx.x; i < nvec; i += 256) {
+    float f[VN];
+    Vec<T> v; v.load(row + i * VN); v.unpack(f);
+    float lm = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < VN; ++k) if (i * VN + k < V) lm = fmaxf(lm, f[k]);
+    if (lm > mx) { sum *= __expf(mx - lm); mx = lm; }
+#pragma unroll
+    for (int k = 0; k < VN; ++k) if (i * VN + k < V) sum += __expf(f[k] - mx);
+  }
+  __shared__ float smx[4], ssum[4];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  float wm = wave_max(mx);
+  sum = (mx == -INFINITY) ? 0.f : sum * __expf(mx - wm);
+  sum = wave_sum(sum);
+  if (lane == 0) { smx[wv] = wm; ssum[wv] = sum; }
+  __syncthreads();
+  float bm = fmaxf(fmaxf(smx[0], smx[1]), fmaxf(smx[2], smx[3]));
+  float bs = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) bs += (smx[w] == -INFINITY) ? 0.f : ssum[w] * __expf(smx[w] - bm);
+  const float lse = bm + logf(bs);
+  const int tgt = targets[(t / S) * tgt_ld + (t % S)];
+  if (threadIdx.x == 0) row_loss[t] = lse - to_float<T>(row[tgt]);
+  __syncthreads();  // the target logit is read before anyone overwrites it
+  for (int i = threadIdx.x; i < nvec; i += 256) {
+    float f[VN];
+    Vec<T> v; v.load(row + i * VN); v.unpack(f);
+#pragma unroll
+    for (int k = 0; k < VN; ++k) {
+      int col = i * VN + k;
+      float p = col < V ? __expf(f[k] - lse) : 0.f;
+      if (col == tgt) p -= 1.0f;
+      f[k] = p * loss_scale;
+    }
+    v.pack(f); v.store(row + i * VN);
+  }
+}
+
+__global__ void __launch_bounds__(256) loss_sum_kernel(const float* __restrict__ row_loss, int64_t n, float scale, float* __restrict__ loss) {
+  float acc = 0.f;
+  for (int64_t i = threadIdx.x; i < n; i += 256) acc += row_loss[i];
+  __shared__ float sw[4];
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) sw[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) *loss = (sw[0] + sw[1] + sw[2] + sw[3]) * scale;
+}
+
+int xent_fwd_bwd(hipStream_t s, int dtype, int64_t T_, int V, int64_t ld, void* logits, const int32_t* targets, int64_t tgt_ld, int S,
+                 float loss_scale, float* loss, float* row_loss) {
+  if (T_ == 0) return POPLAR_OK;
+  const int VN = dtype == POPLAR_BF16 ? 8 : 4;
+  if (ld % VN || ld < V) return poplar_fail(POPLAR_ERR_INVALID, "logit row stride %lld invalid for V=%d", (long long)ld, V);
+  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(xent_kernel<T>, dim3((unsigned)T_), dim3(256), 0, s, (T*)logits, ld, V, targets, tgt_ld, S, loss_scale, row_loss));
+  POPLAR_LAUNCH_CHECK();
+  hipLaunchKernelGGL(loss_sum_kernel, dim3(1), dim3(256), 0, s, row_loss, T_, loss_scale, loss);
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}

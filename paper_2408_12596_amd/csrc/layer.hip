@@ -1,0 +1,349 @@
+// Entry points for one decoder layer, the embedding, the head + loss, the
+// sharded optimizer and the single-rank share of the ZeRO collectives.
+// Host orchestration only: every arithmetic step is a kernel launch.
+#include "layer_plan.h"
+
+int gemm(hipStream_t s, int dtype, const GemmArgs& a) {
+  if (dtype == POPLAR_BF16) return gemm_bf16_mfma(s, a);
+  return gemm_simple(s, dtype, a);
+}
+
+static int attn_fwd(hipStream_t s, const poplar_model_cfg& c, int B, const void* qkv, void* o, float* lse) {
+  const int d = c.hidden / c.n_head;
+  if (c.dtype == POPLAR_BF16) return attn_fwd_flash(s, B, c.seq, c.n_head, d, c.causal, qkv, o, lse);
+  return attn_fwd_simple(s, c.dtype, B, c.seq, c.n_head, d, c.causal, qkv, o, lse);
+}
+static int attn_bwd(hipStream_t s, const poplar_model_cfg& c, int B, const void* qkv, const void* o, const void* dout,
+                    const float* lse, void* dqkv, float* delta) {
+  const int d = c.hidden / c.n_head;
+  if (c.dtype == POPLAR_BF16) return attn_bwd_flash(s, B, c.seq, c.n_head, d, c.causal, qkv, o, dout, lse, dqkv, delta);
+  return attn_bwd_simple(s, c.dtype, B, c.seq, c.n_head, d, c.causal, qkv, o, dout, lse, dqkv, delta);
+}
+
+static GemmArgs gemm_args(int layout, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb,
+                          void* C, int64_t ldc) {
+  GemmArgs g;
+  g.layout = layout; g.M = M; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
+  g.c_float = 0; g.beta = 0.f; g.bias = nullptr; g.residual = nullptr; g.act = ACT_NONE; g.aux = nullptr; g.ldaux = 0;
+  return g;
+}
+
+SavedPlan saved_plan(const poplar_model_cfg& c, int B) {
+  const int64_t T = (int64_t)B * c.seq, H = c.hidden, F = c.ffn, es = elt_size(c.dtype);
+  const int64_t hw = c.arch == POPLAR_ARCH_LLAMA ? 2 * F : F;
+  SavedPlan p;
+  int64_t at = 0;
+  auto take = [&](int64_t bytes) { int64_t r = at; at += round_up(bytes, 256); return r; };
+  p.stats1 = take(T * 2 * 4);
+  p.a = take(T * H * es);
+  p.qkv = take(T * 3 * H * es);
+  p.o = take(T * H * es);
+  p.lse = take((int64_t)B * c.n_head * c.seq * 4);
+  p.x1 = take(T * H * es);
+  p.stats2 = take(T * 2 * 4);
+  p.m = take(T * H * es);
+  p.h = take(T * hw * es);
+  p.g = take(T * F * es);
+  p.bytes = at;
+  return p;
+}
+
+int64_t scratch_floats(const poplar_model_cfg& c) {
+  // norm backward: <= 512 blocks x 2 x H; column sums: <= (2048/strips + 1) chunks x N
+  const int64_t H = c.hidden, F = c.ffn;
+  const int64_t maxN = std::max<int64_t>(3 * H, 2 * F);
+  const int64_t a = 512 * 2 * H;
+  const int64_t b = 2048 * 64 * 8 + 2 * maxN;
+  return std::max(a, b);
+}
+
+BwdPlan bwd_plan(const poplar_model_cfg& c, int B) {
+  const int64_t T = (int64_t)B * c.seq, H = c.hidden, F = c.ffn, es = elt_size(c.dtype);
+  const bool llama = c.arch == POPLAR_ARCH_LLAMA;
+  BwdPlan p;
+  int64_t at = 0;
+  auto take = [&](int64_t bytes) { int64_t r = at; at += round_up(bytes, 256); return r; };
+  p.dh = take(T * (llama ? 2 * F : F) * es);
+  p.dg = llama ? take(T * F * es) : -1;
+  p.dm = take(T * H * es);
+  p.dx1 = take(T * H * es);
+  p.dob = take(T * H * es);
+  p.dqkv = take(T * 3 * H * es);
+  p.da = take(T * H * es);
+  p.delta = take((int64_t)B * c.n_head * c.seq * 4);
+  p.scratch = take(scratch_floats(c) * 4);
+  p.bytes = at;
+  return p;
+}
+
+extern "C" int poplar_layer_saved_bytes(const poplar_model_cfg* cfg, int32_t B, int64_t* bytes) {
+  POPLAR_TRY(validate_cfg(cfg));
+  if (B < 1 || !bytes) return poplar_fail(POPLAR_ERR_INVALID, "batch must be >= 1 and bytes non-null");
+  *bytes = saved_plan(*cfg, B).bytes;
+  return POPLAR_OK;
+}
+
+extern "C" int poplar_layer_workspace_bytes(const poplar_model_cfg* cfg, int32_t B, int64_t* bytes) {
+  POPLAR_TRY(validate_cfg(cfg));
+  if (B < 1 || !bytes) return poplar_fail(POPLAR_ERR_INVALID, "batch must be >= 1 and bytes non-null");
+  *bytes = bwd_plan(*cfg, B).bytes;
+  return POPLAR_OK;
+}
+
+static inline const char* at(const void* base, int64_t elems, int64_t es) { return (const char*)base + elems * es; }
+
+int layer_fwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* params, void* x_out, void* saved) {
+  const poplar_model_cfg& c = ctx->cfg;
+  hipStream_t s = ctx->stream;
+  const int64_t T = (int64_t)B * c.seq, H = c.hidden, F = c.ffn, es = elt_size(c.dtype);
+  const bool llama = c.arch == POPLAR_ARCH_LLAMA;
+  const LayerOffsets lo = layer_offsets(c);
+  const SavedPlan sp = saved_plan(c, B);
+  char* sv = (char*)saved;
+  auto P = [&](int64_t off) -> const void* { return off < 0 ? nullptr : at(params, off, es); };
+  float* stats1 = (float*)(sv + sp.stats1);
+  float* stats2 = (float*)(sv + sp.stats2);
+  float* lse = (float*)(sv + sp.lse);
+  void *a = sv + sp.a, *qkv = sv + sp.qkv, *o = sv + sp.o, *x1 = sv + sp.x1, *m = sv + sp.m, *h = sv + sp.h, *g = sv + sp.g;
+
+  POPLAR_TRY(layernorm_fwd(s, c.dtype, T, (int)H, x_in, P(lo.g1), P(lo.b1), a, stats1, llama));
+  GemmArgs ga = gemm_args(GEMM_NT, T, 3 * H, H, a, H, P(lo.wqkv), H, qkv, 3 * H);
+  ga.bias = P(lo.bqkv);
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  if (llama) POPLAR_TRY(rope_inplace(s, c.dtype, B, c.seq, c.n_head, (int)(H / c.n_head), qkv, 3 * H, 1.0f));
+  POPLAR_TRY(attn_fwd(s, c, B, qkv, o, lse));
+  ga = gemm_args(GEMM_NT, T, H, H, o, H, P(lo.wo), H, x1, H);
+  ga.bias = P(lo.bo); ga.residual = x_in;
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(layernorm_fwd(s, c.dtype, T, (int)H, x1, P(lo.g2), P(lo.b2), m, stats2, llama));
+  if (llama) {
+    ga = gemm_args(GEMM_NT, T, 2 * F, H, m, H, P(lo.w1), H, h, 2 * F);
+    POPLAR_TRY(gemm(s, c.dtype, ga));
+    POPLAR_TRY(swiglu_fwd(s, c.dtype, T, (int)F, h, g));
+  } else {
+    ga = gemm_args(GEMM_NT, T, F, H, m, H, P(lo.w1), H, g, F);
+    ga.bias = P(lo.bm1); ga.act = ACT_GELU; ga.aux = h; ga.ldaux = F;
+    POPLAR_TRY(gemm(s, c.dtype, ga));
+  }
+  ga = gemm_args(GEMM_NT, T, H, F, g, F, P(lo.w2), F, x_out, H);
+  ga.bias = P(lo.bm2); ga.residual = x1;
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  return POPLAR_OK;
+}
+
+int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, const void* params, const void* saved, void* dx,
+                   float* grads, int accumulate, void* workspace) {
+  const poplar_model_cfg& c = ctx->cfg;
+  hipStream_t s = ctx->stream;
+  const int64_t T = (int64_t)B * c.seq, H = c.hidden, F = c.ffn, es = elt_size(c.dtype);
+  const bool llama = c.arch == POPLAR_ARCH_LLAMA;
+  const int64_t hw = llama ? 2 * F : F;
+  const LayerOffsets lo = layer_offsets(c);
+  const SavedPlan sp = saved_plan(c, B);
+  const BwdPlan bp = bwd_plan(c, B);
+  const char* sv = (const char*)saved;
+  char* ws = (char*)workspace;
+  auto P = [&](int64_t off) -> const void* { return off < 0 ? nullptr : at(params, off, es); };
+  auto G = [&](int64_t off) -> float* { return off < 0 ? nullptr : grads + off; };
+  const float* stats1 = (const float*)(sv + sp.stats1);
+  const float* stats2 = (const float*)(sv + sp.stats2);
+  const float* lse = (const float*)(sv + sp.lse);
+  const void *a = sv + sp.a, *qkv = sv + sp.qkv, *o = sv + sp.o, *x1 = sv + sp.x1, *m = sv + sp.m, *h = sv + sp.h, *g = sv + sp.g;
+  void *dh = ws + bp.dh, *dm = ws + bp.dm, *dx1 = ws + bp.dx1, *dob = ws + bp.dob, *dqkv = ws + bp.dqkv, *da = ws + bp.da;
+  float* delta = (float*)(ws + bp.delta);
+  float* scratch = (float*)(ws + bp.scratch);
+  const int64_t scratch_n = scratch_floats(c);
+  const float beta = accumulate ? 1.f : 0.f;
+  GemmArgs ga;
+
+  // MLP down projection: out = x1 + g W2^T + bm2
+  if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, H, dy, H, G(lo.bm2), accumulate, scratch, scratch_n));
+  ga = gemm_args(GEMM_TN, H, F, T, dy, H, g, F, G(lo.w2), F);
+  ga.c_float = 1; ga.beta = beta;
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  if (llama) {
+    void* dg = ws + bp.dg;
+    ga = gemm_args(GEMM_NN, T, F, H, dy, H, P(lo.w2), F, dg, F);
+    POPLAR_TRY(gemm(s, c.dtype, ga));
+    POPLAR_TRY(swiglu_bwd(s, c.dtype, T, (int)F, dg, h, dh));
+  } else {
+    ga = gemm_args(GEMM_NN, T, F, H, dy, H, P(lo.w2), F, dh, F);
+    ga.act = ACT_GELU_BWD; ga.aux = const_cast<void*>(h); ga.ldaux = F;
+    POPLAR_TRY(gemm(s, c.dtype, ga));
+    POPLAR_TRY(colsum(s, c.dtype, T, F, dh, F, G(lo.bm1), accumulate, scratch, scratch_n));
+  }
+  // MLP up projection
+  ga = gemm_args(GEMM_TN, hw, H, T, dh, hw, m, H, G(lo.w1), H);
+  ga.c_float = 1; ga.beta = beta;
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  ga = gemm_args(GEMM_NN, T, H, hw, dh, hw, P(lo.w1), H, dm, H);
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  // second norm; dx1 = dy + norm_bwd(dm)
+  POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, dm, x1, P(lo.g2), stats2, dy, dx1, G(lo.g2), G(lo.b2), accumulate, scratch, scratch_n, llama));
+  // attention output projection: x1 = x + o Wo^T + bo
+  if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, H, dx1, H, G(lo.bo), accumulate, scratch, scratch_n));
+  ga = gemm_args(GEMM_TN, H, H, T, dx1, H, o, H, G(lo.wo), H);
+  ga.c_float = 1; ga.beta = beta;
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  ga = gemm_args(GEMM_NN, T, H, H, dx1, H, P(lo.wo), H, dob, H);
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  // attention
+  POPLAR_TRY(attn_bwd(s, c, B, qkv, o, dob, lse, dqkv, delta));
+  if (llama) POPLAR_TRY(rope_inplace(s, c.dtype, B, c.seq, c.n_head, (int)(H / c.n_head), dqkv, 3 * H, -1.0f));
+  // QKV projection
+  if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, 3 * H, dqkv, 3 * H, G(lo.bqkv), accumulate, scratch, scratch_n));
+  ga = gemm_args(GEMM_TN, 3 * H, H, T, dqkv, 3 * H, a, H, G(lo.wqkv), H);
+  ga.c_float = 1; ga.beta = beta;
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  ga = gemm_args(GEMM_NN, T, H, 3 * H, dqkv, 3 * H, P(lo.wqkv), H, da, H);
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  // first norm; dx = dx1 + norm_bwd(da)
+  POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, da, x_in, P(lo.g1), stats1, dx1, dx, G(lo.g1), G(lo.b1), accumulate, scratch, scratch_n, llama));
+  return POPLAR_OK;
+}
+
+static int check_ctx_batch(poplar_ctx* ctx, int B) {
+  if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
+  if (B < 1) return poplar_fail(POPLAR_ERR_INVALID, "batch must be >= 1, got %d", B);
+  if ((int64_t)B * ctx->cfg.seq > (int64_t)1 << 24) return poplar_fail(POPLAR_ERR_INVALID, "batch * seq above 2^24 tokens");
+  return POPLAR_OK;
+}
+
+extern "C" int poplar_layer_fwd(poplar_ctx* ctx, int32_t B, const void* x_in, const void* params, void* x_out, void* saved,
+                                void* workspace, int64_t workspace_bytes) {
+  POPLAR_TRY(check_ctx_batch(ctx, B));
+  if (!x_in || !params || !x_out || !saved) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
+  if (x_in == x_out) return poplar_fail(POPLAR_ERR_INVALID, "x_in and x_out may not alias");
+  (void)workspace; (void)workspace_bytes;  // the forward pass keeps everything it writes in `saved`
+  return layer_fwd_impl(ctx, B, x_in, params, x_out, saved);
+}
+
+extern "C" int poplar_layer_bwd(poplar_ctx* ctx, int32_t B, const void* x_in, const void* dy, const void* params, const void* saved,
+                                void* dx, float* grads, int32_t accumulate, void* workspace, int64_t workspace_bytes) {
+  POPLAR_TRY(check_ctx_batch(ctx, B));
+  if (!x_in || !dy || !params || !saved || !dx || !grads || !workspace) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
+  if (workspace_bytes < bwd_plan(ctx->cfg, B).bytes)
+    return poplar_fail(POPLAR_ERR_OOM, "layer backward workspace: have %lld bytes, need %lld", (long long)workspace_bytes, (long long)bwd_plan(ctx->cfg, B).bytes);
+  return layer_bwd_impl(ctx, B, x_in, dy, params, saved, dx, grads, accumulate, workspace);
+}
+
+// ---- embedding -------------------------------------------------------------
+extern "C" int poplar_embed_fwd(poplar_ctx* ctx, int32_t B, const int32_t* tokens, const void* wte, const void* wpe, void* x) {
+  POPLAR_TRY(check_ctx_batch(ctx, B));
+  const poplar_model_cfg& c = ctx->cfg;
+  if (!tokens || !wte || !x) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
+  if (c.arch == POPLAR_ARCH_GPT && !wpe) return poplar_fail(POPLAR_ERR_INVALID, "GPT needs wpe");
+  return embed_fwd(ctx->stream, c.dtype, B, c.seq, c.hidden, tokens, c.seq, wte, c.arch == POPLAR_ARCH_GPT ? wpe : nullptr, x);
+}
+
+extern "C" int poplar_embed_bwd(poplar_ctx* ctx, int32_t B, const int32_t* tokens, const void* dx, float* dwte, float* dwpe, int32_t accumulate) {
+  POPLAR_TRY(check_ctx_batch(ctx, B));
+  const poplar_model_cfg& c = ctx->cfg;
+  if (!tokens || !dx || !dwte) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
+  if (c.arch == POPLAR_ARCH_GPT && !dwpe) return poplar_fail(POPLAR_ERR_INVALID, "GPT needs dwpe");
+  return embed_bwd(ctx->stream, c.dtype, B, c.seq, c.hidden, tokens, c.seq, dx, dwte, c.arch == POPLAR_ARCH_GPT ? dwpe : nullptr, accumulate);
+}
+
+// ---- head + loss -----------------------------------------------------------
+HeadPlan head_plan(const poplar_model_cfg& c, int B) {
+  const int64_t T = (int64_t)B * c.seq, H = c.hidden, es = elt_size(c.dtype);
+  HeadPlan p;
+  p.ldl = round_up(c.vocab, 128);
+  int64_t at = 0;
+  auto take = [&](int64_t bytes) { int64_t r = at; at += round_up(bytes, 256); return r; };
+  p.hf = take(T * H * es);
+  p.stats = take(T * 2 * 4);
+  p.logits = take(T * p.ldl * es);
+  p.row_loss = take(T * 4);
+  p.dhf = take(T * H * es);
+  p.scratch = take(scratch_floats(c) * 4);
+  p.bytes = at;
+  return p;
+}
+
+extern "C" int poplar_head_workspace_bytes(const poplar_model_cfg* cfg, int32_t B, int64_t* bytes) {
+  POPLAR_TRY(validate_cfg(cfg));
+  if (B < 1 || !bytes) return poplar_fail(POPLAR_ERR_INVALID, "batch must be >= 1 and bytes non-null");
+  *bytes = head_plan(*cfg, B).bytes;
+  return POPLAR_OK;
+}
+
+int head_fwd_part(poplar_ctx* ctx, int B, const void* x, const int32_t* targets, int64_t tgt_ld, const void* gf, const void* bf,
+                  const void* whead, float loss_scale, float* loss, void* workspace) {
+  const poplar_model_cfg& c = ctx->cfg;
+  hipStream_t s = ctx->stream;
+  const int64_t T = (int64_t)B * c.seq, H = c.hidden, V = c.vocab;
+  const bool llama = c.arch == POPLAR_ARCH_LLAMA;
+  const HeadPlan hp = head_plan(c, B);
+  char* ws = (char*)workspace;
+  void *hf = ws + hp.hf, *logits = ws + hp.logits;
+  float *stats = (float*)(ws + hp.stats), *row_loss = (float*)(ws + hp.row_loss);
+  POPLAR_TRY(layernorm_fwd(s, c.dtype, T, (int)H, x, gf, bf, hf, stats, llama));
+  GemmArgs ga = gemm_args(GEMM_NT, T, V, H, hf, H, whead, H, logits, hp.ldl);
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  // the gradient of the logits replaces them in place; it belongs to the
+  // forward half because it is one pass over the same rows
+  POPLAR_TRY(xent_fwd_bwd(s, c.dtype, T, (int)V, hp.ldl, logits, targets, tgt_ld, c.seq, loss_scale, loss, row_loss));
+  return POPLAR_OK;
+}
+
+int head_bwd_part(poplar_ctx* ctx, int B, const void* x, const void* gf, const void* whead, void* dx, float* d_gf, float* d_bf,
+                  float* d_whead, int accumulate, void* workspace) {
+  const poplar_model_cfg& c = ctx->cfg;
+  hipStream_t s = ctx->stream;
+  const int64_t T = (int64_t)B * c.seq, H = c.hidden, V = c.vocab;
+  const bool llama = c.arch == POPLAR_ARCH_LLAMA;
+  const HeadPlan hp = head_plan(c, B);
+  char* ws = (char*)workspace;
+  void *hf = ws + hp.hf, *logits = ws + hp.logits, *dhf = ws + hp.dhf;
+  float *stats = (float*)(ws + hp.stats), *scratch = (float*)(ws + hp.scratch);
+  GemmArgs ga = gemm_args(GEMM_TN, V, H, T, logits, hp.ldl, hf, H, d_whead, H);
+  ga.c_float = 1; ga.beta = accumulate ? 1.f : 0.f;
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  ga = gemm_args(GEMM_NN, T, H, V, logits, hp.ldl, whead, H, dhf, H);
+  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, dhf, x, gf, stats, nullptr, dx, d_gf, d_bf, accumulate, scratch, scratch_floats(c), llama));
+  return POPLAR_OK;
+}
+
+extern "C" int poplar_head_loss_fwd_bwd(poplar_ctx* ctx, int32_t B, const void* x, const int32_t* targets, const void* gf, const void* bf,
+                                        const void* whead, float loss_scale, float* loss, void* dx, float* d_gf, float* d_bf,
+                                        float* d_whead, int32_t accumulate, void* workspace, int64_t workspace_bytes) {
+  POPLAR_TRY(check_ctx_batch(ctx, B));
+  const poplar_model_cfg& c = ctx->cfg;
+  if (!x || !targets || !gf || !whead || !loss || !dx || !d_gf || !d_whead || !workspace) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
+  if (c.arch == POPLAR_ARCH_GPT && (!bf || !d_bf)) return poplar_fail(POPLAR_ERR_INVALID, "GPT needs bf and d_bf");
+  if (workspace_bytes < head_plan(c, B).bytes)
+    return poplar_fail(POPLAR_ERR_OOM, "head workspace: have %lld bytes, need %lld", (long long)workspace_bytes, (long long)head_plan(c, B).bytes);
+  POPLAR_TRY(head_fwd_part(ctx, B, x, targets, c.seq, gf, bf, whead, loss_scale, loss, workspace));
+  return head_bwd_part(ctx, B, x, gf, whead, dx, d_gf, d_bf, d_whead, accumulate, workspace);
+}
+
+// ---- optimizer and collectives' local share ---------------------------------
+extern "C" int poplar_adam_shard(poplar_ctx* ctx, float* p32, float* m, float* v, const float* g, void* p_lowp, int64_t len,
+                                 int32_t step_t, float lr, float b1, float b2, float eps) {
+  if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
+  if (len < 0 || step_t < 1) return poplar_fail(POPLAR_ERR_INVALID, "len must be >= 0 and step_t >= 1");
+  if (len > 0 && (!p32 || !m || !v || !g)) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
+  if (!(b1 >= 0.f && b1 < 1.f && b2 >= 0.f && b2 < 1.f)) return poplar_fail(POPLAR_ERR_INVALID, "betas must be in [0, 1)");
+  return adam_shard(ctx->stream, ctx->cfg.dtype, p32, m, v, g, p_lowp, len, step_t, lr, b1, b2, eps);
+}
+
+extern "C" int poplar_zero2_reduce_local(poplar_ctx* ctx, float* gshard, const float* g_unit, int64_t unit_lo, int64_t unit_hi,
+                                         int64_t shard_off, int64_t shard_len) {
+  if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
+  if (unit_lo < 0 || unit_hi < unit_lo || shard_off < 0 || shard_len < 0) return poplar_fail(POPLAR_ERR_INVALID, "bad ranges");
+  if (unit_hi == unit_lo || shard_len == 0) return POPLAR_OK;
+  if (!gshard || !g_unit) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
+  return zero2_reduce_local(ctx->stream, gshard, g_unit, unit_lo, unit_hi, shard_off, shard_len);
+}
+
+extern "C" int poplar_zero3_gather_local(poplar_ctx* ctx, void* out, const void* own_shard, const void* peers, int64_t lo, int64_t hi,
+                                         int64_t shard_off, int64_t shard_len) {
+  if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
+  if (lo < 0 || hi < lo || shard_off < 0 || shard_len < 0) return poplar_fail(POPLAR_ERR_INVALID, "bad ranges");
+  if (hi == lo) return POPLAR_OK;
+  if (!out || !own_shard || !peers) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
+  return zero3_gather_local(ctx->stream, ctx->cfg.dtype, out, own_shard, peers, lo, hi, shard_off, shard_len);
+}

@@ -1,0 +1,155 @@
+"""GPU parity: one decoder layer forward + backward, embedding, head + loss,
+against the fp64 oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import transformer as otr
+from paper_2408_12596_amd import binding as pb
+from paper_2408_12596_amd import synth
+from gpu_util import DEV, quantize, rel_l2, scratch, to_dev, to_np, sync, tdtype
+
+pytestmark = pytest.mark.gpu
+
+# relative-L2 bars: bf16 activations and gradients 2e-2; the fp32 path accumulates
+# in float over K <= 1024 terms, so 2e-5 leaves a wide margin over sqrt(K) * 6e-8
+TOL = {"bf16": 2e-2, "f32": 2e-5}
+
+LAYER_CASES = [
+    # the small parity configuration: pre-LN GPT layer, hidden 256, 4 heads, MLP 1024, seq 128, batch 2
+    dict(arch="gpt", L=1, H=256, nh=4, F=1024, S=128, V=1, B=2),
+    dict(arch="llama", L=1, H=128, nh=2, F=192, S=96, V=1, B=3),
+    # ragged: tokens and widths that are not multiples of the GEMM tiles
+    dict(arch="gpt", L=1, H=192, nh=3, F=328, S=77, V=1, B=3),
+    dict(arch="llama", L=1, H=256, nh=2, F=1000, S=130, V=1, B=1),
+]
+
+
+def layer_inputs(case, dtype, seed=0):
+    spec = [(f"l0.{n}", s) for n, s in otr.layer_spec(case["arch"], case["H"], case["F"])]
+    flat = synth.init_params(spec, seed=seed, jitter=True)
+    x = synth.activations((case["B"], case["S"], case["H"]), seed=seed)
+    dy = synth.activations((case["B"], case["S"], case["H"]), seed=seed + 1)
+    return spec, flat, x, dy
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", LAYER_CASES, ids=lambda c: f"{c['arch']}-H{c['H']}-S{c['S']}-B{c['B']}")
+def test_layer_fwd_bwd_matches_oracle(case, dtype):
+    if dtype == "bf16" and case["H"] // case["nh"] not in (64, 128):
+        pytest.skip("bf16 attention supports head_dim 64 and 128")
+    B, S, H, nh = case["B"], case["S"], case["H"], case["nh"]
+    cfg = pb.make_cfg(**{k: case[k] for k in ("arch", "L", "H", "nh", "F", "S", "V")}, dtype=dtype)
+    ctx = pb.Context(cfg)
+    spec, flat, x, dy = layer_inputs(case, dtype)
+    n = len(flat)
+    assert n == pb.layer_param_count(cfg)
+    d_params, d_x, d_dy = to_dev(flat, dtype), to_dev(x, dtype), to_dev(dy, dtype)
+    d_out = torch.empty_like(d_x)
+    d_dx = torch.empty_like(d_x)
+    saved = scratch(pb.layer_saved_bytes(cfg, B))
+    wsb = pb.layer_workspace_bytes(cfg, B)
+    ws = scratch(wsb)
+    grads = torch.full((n,), float("nan"), device=DEV)
+    ctx.layer_fwd(B, d_x, d_params, d_out, saved)
+    ctx.layer_bwd(B, d_x, d_dy, d_params, saved, d_dx, grads, 0, ws, wsb)
+    sync()
+
+    p = {k[3:]: v for k, v in otr.unpack(quantize(flat, dtype), spec).items()}
+    ref_out, cache = otr.layer_fwd(case["arch"], p, quantize(x, dtype), nh)
+    ref_dx, ref_g = otr.layer_bwd(case["arch"], p, quantize(dy, dtype), cache, nh)
+    tol = TOL[dtype]
+    assert rel_l2(to_np(d_out), ref_out) <= tol
+    assert rel_l2(to_np(d_dx), ref_dx) <= tol
+    table, _ = otr.offsets(spec)
+    got = to_np(grads)
+    assert np.isfinite(got).all()
+    for name, (off, shape) in table.items():
+        k = int(np.prod(shape))
+        assert rel_l2(got[off:off + k], ref_g[name[3:]]) <= tol, name
+
+    # accumulate = 1 adds the same gradient again
+    ctx.layer_bwd(B, d_x, d_dy, d_params, saved, d_dx, grads, 1, ws, wsb)
+    sync()
+    assert rel_l2(to_np(grads), 2 * got) <= 1e-6
+
+
+def test_layer_bwd_rejects_small_workspace():
+    case = LAYER_CASES[0]
+    cfg = pb.make_cfg(**{k: case[k] for k in ("arch", "L", "H", "nh", "F", "S", "V")}, dtype="f32")
+    ctx = pb.Context(cfg)
+    t = torch.zeros(16, device=DEV)
+    with pytest.raises(pb.OutOfMemory):
+        ctx.layer_bwd(2, t, t, t, t, t, t, 0, t, 64)
+    with pytest.raises(pb.PoplarError):
+        ctx.layer_fwd(0, t, t, t, t)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("arch", ["gpt", "llama"])
+def test_embedding_fwd_bwd(arch, dtype):
+    B, S, H, V = 3, 40, 64, 97
+    cfg = pb.make_cfg(arch=arch, L=1, H=H, nh=1, F=64, S=S, V=V, dtype=dtype)
+    ctx = pb.Context(cfg)
+    rng = np.random.default_rng(0)
+    wte = (rng.standard_normal((V, H)) * 0.5).astype(np.float32)
+    wpe = (rng.standard_normal((S, H)) * 0.5).astype(np.float32)
+    tok, _ = synth.tokens(B, S, V, seed=0)
+    tok[0, :5] = tok[1, 0]          # repeated ids exercise the scatter-add
+    dx = synth.activations((B, S, H), seed=3)
+    d_tok = to_dev(tok)
+    d_x = torch.empty((B, S, H), dtype=tdtype(dtype), device=DEV)
+    ctx.embed_fwd(B, d_tok, to_dev(wte, dtype), to_dev(wpe, dtype) if arch == "gpt" else None, d_x)
+    dwte = torch.zeros((V, H), device=DEV)
+    dwpe = torch.full((S, H), float("nan"), device=DEV) if arch == "gpt" else None
+    ctx.embed_bwd(B, d_tok, to_dev(dx, dtype), dwte, dwpe, 0)
+    sync()
+    ref_x = otr.embed_fwd(arch, quantize(wte, dtype), quantize(wpe, dtype), tok)
+    assert rel_l2(to_np(d_x), ref_x) <= (4e-3 if dtype == "bf16" else 1e-7)
+    r_dwte, r_dwpe = otr.embed_bwd(arch, quantize(dx, dtype), tok, V, S)
+    assert rel_l2(to_np(dwte), r_dwte) <= 1e-6
+    if arch == "gpt":
+        assert rel_l2(to_np(dwpe), r_dwpe) <= 1e-6
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("arch,V", [("gpt", 211), ("llama", 256), ("gpt", 1031)])
+def test_head_loss_fwd_bwd(arch, V, dtype):
+    B, S, H = 2, 48, 128
+    cfg = pb.make_cfg(arch=arch, L=1, H=H, nh=2, F=128, S=S, V=V, dtype=dtype)
+    ctx = pb.Context(cfg)
+    rng = np.random.default_rng(1)
+    x = synth.activations((B, S, H), seed=5)
+    gf = (1 + 0.1 * rng.standard_normal(H)).astype(np.float32)
+    bf = (0.1 * rng.standard_normal(H)).astype(np.float32)
+    wh = (rng.standard_normal((V, H)) * 0.1).astype(np.float32)
+    _, tgt = synth.tokens(B, S, V, seed=2)
+    scale = 1.0 / (B * S)
+    loss = torch.zeros(1, device=DEV)
+    d_dx = torch.empty((B, S, H), dtype=tdtype(dtype), device=DEV)
+    d_gf, d_bf = torch.full((H,), float("nan"), device=DEV), torch.full((H,), float("nan"), device=DEV)
+    d_wh = torch.full((V, H), float("nan"), device=DEV)
+    wsb = pb.head_workspace_bytes(cfg, B)
+    ws = scratch(wsb)
+    ctx.head_loss_fwd_bwd(B, to_dev(x, dtype), to_dev(tgt.reshape(-1)), to_dev(gf, dtype), to_dev(bf, dtype) if arch == "gpt" else None,
+                          to_dev(wh, dtype), scale, loss, d_dx, d_gf, d_bf if arch == "gpt" else None, d_wh, 0, ws, wsb)
+    sync()
+    xq, gq, bq, wq = quantize(x, dtype), quantize(gf, dtype), quantize(bf, dtype), quantize(wh, dtype)
+    if arch == "gpt":
+        hf, nc = otr.layernorm_fwd(xq, gq, bq)
+    else:
+        hf, nc = otr.rmsnorm_fwd(xq, gq)
+    logits = hf.reshape(-1, H) @ wq.T
+    r_loss, dlog = otr.xent_fwd_bwd(logits, tgt.reshape(-1), scale)
+    r_dwh = dlog.T @ hf.reshape(-1, H)
+    dhf = (dlog @ wq).reshape(hf.shape)
+    tol = TOL[dtype]
+    assert abs(loss.item() - r_loss) <= (5e-3 if dtype == "bf16" else 1e-5) * abs(r_loss)
+    if arch == "gpt":
+        r_dx, r_dg, r_db = otr.layernorm_bwd(dhf, gq, nc)
+        assert rel_l2(to_np(d_bf), r_db) <= tol
+    else:
+        r_dx, r_dg = otr.rmsnorm_bwd(dhf, gq, nc)
+    assert rel_l2(to_np(d_dx), r_dx) <= tol
+    assert rel_l2(to_np(d_gf), r_dg) <= tol
+    assert rel_l2(to_np(d_wh), r_dwh) <= tol

@@ -1,0 +1,182 @@
+"""GPU parity: one rank's whole step at every ZeRO stage (profile_step), the
+max-batch search under an emulated cap, and the allocator on measured curves."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import allocate as oal
+from oracle import optimizer as oopt
+from oracle import profiling as opf
+from oracle import transformer as otr
+from paper_2408_12596_amd import binding as pb
+from paper_2408_12596_amd import synth
+from gpu_util import DEV, quantize, rel_l2, scratch, to_dev, to_np, sync, tdtype
+
+pytestmark = pytest.mark.gpu
+TOL = {"bf16": 2e-2, "f32": 5e-5}
+# the C ABI takes float hyper-parameters: the oracle gets the same float values
+HP = {k: float(np.float32(x)) for k, x in dict(lr=1e-3, b1=0.9, b2=0.999, eps=1e-8).items()}
+
+MODELS = {
+    "gpt": dict(arch="gpt", L=2, H=128, nh=2, F=256, S=64, V=211),
+    "llama": dict(arch="llama", L=2, H=128, nh=2, F=200, S=64, V=157),
+}
+
+
+class Rank:
+    """Device state of one simulated rank, built from the same flat fp32 vector the oracle sees."""
+
+    def __init__(self, model, dtype, stage, world, rank, max_batch, cap_bytes=0, seed=0):
+        self.model, self.dtype, self.stage = model, dtype, stage
+        self.cfg = pb.make_cfg(**model, dtype=dtype, world=world, rank=rank, zero_stage=stage, cap_bytes=cap_bytes)
+        self.ctx = pb.Context(self.cfg)
+        self.spec = otr.model_spec(model)
+        self.flat = synth.init_params(self.spec, seed=seed, jitter=True)
+        self.P = len(self.flat)
+        assert self.P == pb.model_param_count(self.cfg)
+        if stage == 0:
+            self.off, self.len, self.valid = 0, self.P, self.P
+        else:
+            self.off, self.len, self.valid = pb.shard_range(self.P, world, rank)
+        padded = np.zeros(max(self.off + self.len, self.P), np.float32)
+        padded[:self.P] = self.flat
+        self.params = to_dev(self.flat, dtype)
+        self.master = to_dev(padded[self.off:self.off + self.len])
+        self.own = to_dev(padded[self.off:self.off + self.len], dtype) if stage == 3 else None
+        if stage == 3:   # the rank's own range must come from its shard, not from the stand-in
+            self.params[self.off:self.off + self.valid] = float("nan")
+        self.m = torch.zeros(self.len, device=DEV)
+        self.v = torch.zeros(self.len, device=DEV)
+        self.grads = torch.full((self.P if stage < 2 else self.len,), float("nan"), device=DEV)
+        tok, tgt = synth.tokens(max_batch, model["S"], model["V"], seed=seed)
+        self.tok, self.tgt = tok, tgt
+        both = np.concatenate([tok, tgt[:, -1:]], axis=1).astype(np.int32)
+        self.tokens = to_dev(both)
+        self.wsb = pb.step_workspace_bytes(self.cfg, stage, max_batch)
+        self.ws = scratch(self.wsb)
+        self.loss = torch.zeros(1, device=DEV)
+        self.ctx.bind_state(self.params, self.master, self.m, self.v, self.grads, self.tokens, max_batch, self.ws, self.wsb,
+                            self.loss, own_shard=self.own, adam_t=1, lr=HP["lr"], beta1=HP["b1"], beta2=HP["b2"], eps=HP["eps"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("stage", [0, 1, 2, 3])
+@pytest.mark.parametrize("arch", ["gpt", "llama"])
+def test_profile_step_matches_oracle(arch, stage, dtype):
+    model, B, world, rank = MODELS[arch], 3, 4, 1
+    rk = Rank(model, dtype, stage, world, rank, max_batch=4)
+    prof = rk.ctx.profile_step(stage, B)
+    sync()
+    fq = quantize(rk.flat, dtype)
+    loss, grad, _ = otr.model_fwd_bwd(model, fq, rk.tok[:B], rk.tgt[:B], 1.0 / (B * model["S"]))
+    tol = TOL[dtype]
+    assert abs(prof["loss"] - loss) <= (5e-3 if dtype == "bf16" else 1e-5) * abs(loss)
+    got = to_np(rk.grads)
+    sl = slice(rk.off, rk.off + rk.valid)
+    if stage < 2:
+        table, _ = otr.offsets(rk.spec)
+        for name, (off, shape) in table.items():
+            k = int(np.prod(shape))
+            assert rel_l2(got[off:off + k], grad[off:off + k]) <= tol, name
+        g_used = got[sl]
+    else:
+        assert rel_l2(got[:rk.valid], grad[sl]) <= tol
+        assert np.all(got[rk.valid:] == 0)
+        g_used = got[:rk.valid]
+    # Adam on the shard: the oracle applied to the gradient the device produced (1e-6), and end to end
+    p0 = rk.flat[sl].astype(np.float64)
+    z = np.zeros_like(p0)
+    rp, rm, rv = oopt.adam_step(p0, z, z, g_used, 1, **HP)
+    assert rel_l2(to_np(rk.master)[:rk.valid], rp) <= 1e-6
+    assert rel_l2(to_np(rk.m)[:rk.valid], rm) <= 1e-6
+    assert rel_l2(to_np(rk.v)[:rk.valid], rv) <= 1e-6
+    low = rk.own[:rk.valid] if stage == 3 else rk.params[sl]
+    np.testing.assert_array_equal(low.to(torch.float32).cpu().numpy(),
+                                  oopt.bf16_round(rk.master[:rk.valid].cpu().numpy()) if dtype == "bf16" else rk.master[:rk.valid].cpu().numpy())
+    # what a profile sample means, per stage
+    ref_t = opf.time_consumed(stage, prof["t_fwd"], prof["t_bwd"], prof["t_gather_fwd"], prof["t_gather_bwd"], prof["t_reduce_bwd"])
+    assert abs(prof["t_consumed"] - ref_t) <= 1e-12
+    assert prof["t_fwd"] > 0 and prof["t_bwd"] > 0 and prof["t_adam"] > 0
+    assert (prof["t_reduce_bwd"] > 0) == (stage >= 2) and (prof["t_gather_fwd"] > 0) == (stage == 3)
+    assert prof["accounted_bytes"] == pb.step_accounted_bytes(rk.cfg, stage, B)
+    S, H, F, V, L = (model[k] for k in "SHFVL")
+    mlp = 3 if arch == "llama" else 2
+    assert prof["flops"] == B * (L * (6 * S * (4 * H * H + mlp * H * F) + 7 * S * S * H) + 6 * S * H * V)
+
+
+def test_all_ranks_together_equal_the_unsharded_update():
+    """ZeRO world of 4 simulated by shard offsets: the four shards' updates tile the full update."""
+    model, B, world = MODELS["gpt"], 2, 4
+    full = Rank(model, "f32", 0, 1, 0, max_batch=B)
+    full.ctx.profile_step(0, B)
+    sync()
+    ref = to_np(full.master)
+    for stage in (1, 2):
+        parts = []
+        for r in range(world):
+            rk = Rank(model, "f32", stage, world, r, max_batch=B)
+            rk.ctx.profile_step(stage, B)
+            sync()
+            parts.append(to_np(rk.master)[:rk.valid])
+        got = np.concatenate(parts)
+        # same kernels, same inputs: only the scatter-add order of the embedding gradient may differ
+        assert rel_l2(got, ref) <= 1e-7
+
+
+def test_profile_step_errors_leave_state_untouched():
+    model = MODELS["gpt"]
+    rk = Rank(model, "f32", 1, 4, 0, max_batch=2, cap_bytes=1)
+    before = rk.master.clone()
+    with pytest.raises(pb.OutOfMemory):
+        rk.ctx.profile_step(1, 1)
+    with pytest.raises(pb.PoplarError):
+        rk.ctx.profile_step(1, 3)          # above the bound token buffer
+    with pytest.raises(pb.PoplarError):
+        rk.ctx.profile_step(3, 1)          # stage 3 needs own_shard
+    with pytest.raises(pb.PoplarError):
+        pb.Context(rk.cfg).profile_step(1, 1)   # nothing bound
+    sync()
+    assert torch.equal(before, rk.master)
+
+
+@pytest.mark.parametrize("stage", [1, 2, 3])
+def test_search_mbs_under_an_emulated_cap(stage):
+    model, world = MODELS["gpt"], 4
+    probe = pb.make_cfg(**model, dtype="bf16", world=world, zero_stage=stage)
+    want = 11
+    cap = pb.step_accounted_bytes(probe, stage, want) + 100    # room for 11 samples, not 12
+    rk = Rank(model, "bf16", stage, world, 0, max_batch=16, cap_bytes=cap)
+    mbs, samples = rk.ctx.search_mbs(stage)
+    brute = max(b for b in range(0, 17) if pb.step_accounted_bytes(rk.cfg, stage, b) <= cap)
+    assert mbs == brute == want
+    # the oracle's search on the same memory model visits the same batches in the same order
+    calls = []
+
+    def step(b):
+        calls.append(b)
+        if pb.step_accounted_bytes(rk.cfg, stage, b) > cap:
+            raise opf.OutOfMemory()
+        return 1.0
+    now = [pb.step_accounted_bytes(rk.cfg, stage, 0, True)]
+
+    def forward(b):
+        now[0] = pb.step_accounted_bytes(rk.cfg, stage, b, True)
+    o_mbs, o_samples = opf.search_mbs(lambda: now[0], forward, step, cap)
+    assert o_mbs == mbs
+    assert [s["batch"] for s in samples] == [b for b, _ in o_samples]
+    assert all(s["t_consumed"] > 0 for s in samples)
+    # curves from the measured samples, scaled for a 4-device mix 1 : 1.5 : 2 : 3, go through Algorithm 2
+    bs = [s["batch"] for s in samples]
+    ts = [s["t_consumed"] for s in samples]
+    curves = [(bs, [t * k for t in ts], mbs) for k in (1.0, 1 / 1.5, 1 / 2.0, 1 / 3.0)]
+    got = pb.allocate(stage, 64, curves, 0.0)
+    ref = oal.allocate(stage, 64, curves, 0.0)
+    assert got["gmbs"] == ref["gmbs"] and got["b"] == ref["b"] and got["lbs"] == ref["lbs"]
+    assert sum(got["gmbs"]) == 64
+
+
+def test_search_mbs_returns_zero_when_nothing_fits():
+    model = MODELS["gpt"]
+    rk = Rank(model, "bf16", 1, 4, 0, max_batch=4, cap_bytes=1000)
+    mbs, samples = rk.ctx.search_mbs(1)
+    assert mbs == 0 and samples == []
