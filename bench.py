@@ -1,0 +1,148 @@
+"""Benchmark: one rank's ZeRO-1 training step of the GPT-2-small-shaped workload
+on one MI355X, through libpoplar's C ABI.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B]
+
+A step is poplar_profile_step(stage 1, B): embedding, 12 layers forward, head
+and loss, backward, Adam on the rank's 1/8 shard, all on synthetic inputs that
+already sit in HBM.  Prints ONE JSON line ("Measurement").
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+WORKLOAD = dict(arch="gpt", L=12, H=768, nh=12, F=3072, S=1024, V=50257)
+WORLD, RANK, STAGE = 8, 0, 1
+SWEEP = (1, 2, 4, 8, 16)
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(model, flat, tok, tgt):
+    """The oracle as it stands, timed on this host: forward + backward of ONE sample
+    through all layers and the head, then Adam on the 1/8 shard."""
+    from oracle import optimizer as oopt
+    from oracle import transformer as otr
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    f64 = flat.astype(np.float64)
+    t0 = time.perf_counter()
+    loss, grad, _ = otr.model_fwd_bwd(model, f64, tok[:1], tgt[:1], 1.0 / model["S"])
+    off, ln, valid = oopt.shard_range(len(f64), WORLD, RANK)
+    sl = slice(off, off + valid)
+    z = np.zeros(valid)
+    oopt.adam_step(f64[sl], z, z, grad[sl], 1, 1e-3, 0.9, 0.999, 1e-8)
+    dt = time.perf_counter() - t0
+    return {"value": 1.0 / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": "1 sample (1024 tokens) through the full 12-layer model fwd+bwd + Adam on the 1/8 shard, fp64 NumPy",
+            "seconds": dt, "loss": float(loss)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--batch", type=int, default=16, help="local batch of the headline number")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one rank on ONE GPU (the ZeRO world is simulated by shard offsets); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2408_12596_amd import binding as pb
+    from paper_2408_12596_amd import synth
+
+    pb.lib()   # fails loudly if the HIP library has not been built
+    dev = "cuda:0"
+    model = WORKLOAD
+    cfg = pb.make_cfg(**model, dtype="bf16", world=WORLD, rank=RANK, zero_stage=STAGE)
+    P = pb.model_param_count(cfg)
+    off, ln, valid = pb.shard_range(P, WORLD, RANK)
+    spec = [(name, shape) for name, shape, _ in pb.model_spec(cfg)]   # the library's own flat layout
+    assert sum(int(np.prod(s)) for _, s in spec) == P
+    flat = synth.init_params(spec, seed=0)
+    max_b = max(max(SWEEP), args.batch)
+    tok, tgt = synth.tokens(max_b, model["S"], model["V"], seed=0)
+    both = np.concatenate([tok, tgt[:, -1:]], axis=1).astype(np.int32)
+
+    params = torch.from_numpy(flat).to(dev).to(torch.bfloat16)
+    master = torch.from_numpy(flat[off:off + ln].copy()).to(dev)
+    m = torch.zeros(ln, device=dev)
+    v = torch.zeros(ln, device=dev)
+    grads = torch.zeros(P, device=dev)
+    tokens = torch.from_numpy(both).to(dev)
+    wsb = pb.step_workspace_bytes(cfg, STAGE, max_b)
+    ws = torch.empty(wsb + 256, dtype=torch.uint8, device=dev)
+    loss = torch.zeros(1, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    ctx = pb.Context(cfg, stream)
+    ctx.bind_state(params, master, m, v, grads, tokens, max_b, ws, wsb, loss, adam_t=1, lr=1e-4)
+
+    def run(B, steps, warmup, timing):
+        ctx.set_kernel_timing(False)
+        for _ in range(warmup):
+            ctx.profile_step(STAGE, B)
+        ctx.set_kernel_timing(timing)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        profs = [ctx.profile_step(STAGE, B) for _ in range(steps)]
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps, profs
+
+    B = args.batch
+    dt, profs = run(B, args.steps, args.warmup, True)
+    mean = lambda k: float(np.mean([p[k] for p in profs]))
+    flops = profs[0]["flops"]
+    t_gemm, f_gemm, n_gemm = mean("t_gemm"), profs[0]["gemm_flops"], profs[0]["n_gemm"]
+    t_attn, f_attn = mean("t_attn"), profs[0]["attn_flops"]
+    gemm_tflops = f_gemm / t_gemm / 1e12 if t_gemm > 0 else 0.0
+    adam_gbs = 30.0 * valid / mean("t_adam") / 1e9
+    out = {
+        "metric": "samples/sec", "value": B / dt, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "GPT-2-small-shaped decoder (12 layers, hidden 768, 12 heads, MLP 3072 GeLU, seq 1024, vocab 50257), "
+                               "bf16 compute, fp32 master; ZeRO-1 step of rank 0 of a simulated world of 8: fwd + bwd + Adam on the 1/8 shard",
+                   "local_batch": B, "zero_stage": STAGE, "world": WORLD, "params": P, "shard_elems": valid},
+        "tflops": flops / dt / 1e12,
+        "frac_mfma_peak_step": flops / dt / 1e12 / PEAK_BF16_TFLOPS,
+        "samples_per_s_time_consumed": B / mean("t_consumed"),
+        "step_breakdown_ms": {k: mean(k) * 1e3 for k in ("t_fwd", "t_bwd", "t_adam", "t_gemm", "t_attn")},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16 (all GEMM launches of the step)", "achieved": gemm_tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches_per_step": n_gemm, "avg_launch_ms": t_gemm / max(n_gemm, 1) * 1e3,
+                     "flop_per_launch": f_gemm / max(n_gemm, 1)},
+        "attention": {"achieved": f_attn / t_attn / 1e12 if t_attn > 0 else 0.0, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS,
+                      "frac": (f_attn / t_attn / 1e12 / PEAK_BF16_TFLOPS) if t_attn > 0 else 0.0},
+        "adam": {"achieved": adam_gbs, "unit": "GB/s", "peak": PEAK_HBM_GBS, "frac": adam_gbs / PEAK_HBM_GBS,
+                 "bytes_per_elem": 30, "elems": valid},
+        "loss": profs[-1]["loss"],
+    }
+    if not args.no_sweep:
+        sweep = []
+        for b in SWEEP:
+            d, pr = run(b, 3, 1, False)
+            sweep.append({"local_batch": b, "samples_per_s": b / d, "ms_per_step": d * 1e3, "tflops": pr[0]["flops"] / d / 1e12,
+                          "frac_mfma_peak": pr[0]["flops"] / d / 1e12 / PEAK_BF16_TFLOPS,
+                          "t_consumed_ms": float(np.mean([p["t_consumed"] for p in pr])) * 1e3})
+        out["sweep"] = sweep
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(model, flat, tok, tgt)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -227,7 +227,18 @@ typedef struct poplar_profile {
   int64_t accounted_bytes;      /* poplar_step_accounted_bytes(stage, batch) */
   double flops;                 /* algorithmic flop of forward + backward */
   float loss;
+  /* filled only with poplar_set_kernel_timing(ctx, 1): every GEMM / attention
+   * launch of the step bracketed by two events on the context's stream */
+  double t_gemm, gemm_flops;    /* summed launch durations (s) and algorithmic flop 2*M*N*K of the GEMM launches */
+  double t_attn, attn_flops;    /* same for the attention kernels: 2 S^2 H fwd, 5 S^2 H bwd per sample (causal) */
+  int32_t n_gemm, n_attn;       /* launches counted */
 } poplar_profile;
+
+/* Kernel-level timing inside poplar_profile_step (off by default).  The paper
+ * records wall time per step because no single operation explains it (Section
+ * "Time Consumed Estimation"); this switch adds the per-kernel view needed to
+ * place the GEMM and attention kernels against the matrix-core roofline. */
+int poplar_set_kernel_timing(poplar_ctx* ctx, int32_t on);
 
 /* model.step(local_batch) of Algorithm 1 at a ZeRO stage, timed:
  * embedding, L layers, head and loss, backward, (stage 2/3) local gradient

@@ -47,7 +47,8 @@ class Profile(C.Structure):
     _fields_ = [("stage", C.c_int32), ("batch", C.c_int32), ("t_fwd", C.c_double), ("t_bwd", C.c_double),
                 ("t_gather_fwd", C.c_double), ("t_gather_bwd", C.c_double), ("t_reduce_bwd", C.c_double),
                 ("t_adam", C.c_double), ("t_consumed", C.c_double), ("accounted_bytes", C.c_int64),
-                ("flops", C.c_double), ("loss", C.c_float)]
+                ("flops", C.c_double), ("loss", C.c_float), ("t_gemm", C.c_double), ("gemm_flops", C.c_double),
+                ("t_attn", C.c_double), ("attn_flops", C.c_double), ("n_gemm", C.c_int32), ("n_attn", C.c_int32)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -68,7 +69,7 @@ EXPORTS = [
     "poplar_layer_fwd", "poplar_layer_bwd", "poplar_embed_fwd", "poplar_embed_bwd", "poplar_head_workspace_bytes",
     "poplar_head_loss_fwd_bwd", "poplar_adam_shard", "poplar_zero2_reduce_local", "poplar_zero3_gather_local",
     "poplar_bind_state", "poplar_step_workspace_bytes", "poplar_step_accounted_bytes", "poplar_profile_step",
-    "poplar_search_mbs", "poplar_speed_curve", "poplar_allocate",
+    "poplar_search_mbs", "poplar_speed_curve", "poplar_allocate", "poplar_set_kernel_timing",
 ]
 
 _lib = None
@@ -112,6 +113,7 @@ def _declare(L):
         "poplar_step_accounted_bytes": [cfgp, i32, i32, i32, p64],
         "poplar_profile_step": [vp, i32, i32, C.POINTER(Profile)],
         "poplar_search_mbs": [vp, i32, C.POINTER(i32), C.POINTER(Profile), i32, C.POINTER(i32)],
+        "poplar_set_kernel_timing": [vp, i32],
         "poplar_speed_curve": [C.POINTER(Curve), C.POINTER(f64)],
         "poplar_allocate": [i32, i32, C.POINTER(Curve), i64, f64, f64, C.POINTER(Alloc)],
     }
@@ -307,6 +309,9 @@ class Context:
                    _ptr(workspace), workspace_bytes, _ptr(loss), adam_t, lr, beta1, beta2, eps)
         _check(lib().poplar_bind_state(self._h, C.byref(st)))
         self._state_refs = (params, master, m, v, grads, tokens, workspace, loss, own_shard)  # keep the tensors alive
+
+    def set_kernel_timing(self, on):
+        _check(lib().poplar_set_kernel_timing(self._h, int(on)))
 
     def profile_step(self, stage, local_batch):
         out = Profile()

@@ -26,13 +26,22 @@ int poplar_fail(int code, const char* fmt, ...);
 
 #define POPLAR_LAUNCH_CHECK() POPLAR_CHECK_HIP(hipGetLastError())
 
+enum LaunchKind { KIND_GEMM = 0, KIND_ATTN = 1, KIND_COUNT = 2 };
+struct TimedLaunch { int kind; hipEvent_t a, b; double flops; };
+
 struct poplar_ctx {
   poplar_model_cfg cfg;
   hipStream_t stream;
   poplar_state st;
   bool bound;
   std::vector<hipEvent_t> events;  // pool reused by every profiled step
+  size_t ev_next;                  // next unused event of the pool in the running step
+  bool kernel_timing;              // bracket every GEMM / attention launch with events
+  bool in_step;                    // a profiled step is being enqueued
+  std::vector<TimedLaunch> launches;
 };
+// record the next pooled event on the context's stream
+int ctx_mark(poplar_ctx* ctx, hipEvent_t* e);
 
 static inline int64_t elt_size(int dtype) { return dtype == POPLAR_BF16 ? 2 : 4; }
 static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }

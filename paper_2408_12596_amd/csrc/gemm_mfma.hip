@@ -1,3 +1,264 @@
-// bring-up placeholder: replaced by the MFMA kernel
-#include "common.h"
-int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a) { return gemm_simple(s, POPLAR_BF16, a); }
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), float
+// accumulation, for the projections of the decoder layer in forward and
+// backward:  NT  y = x W^T,   NN  dx = dy W,   TN  dW = dy^T x.
+//
+// Design
+//  * 256 threads = 4 wavefronts in a 2x2 grid; each wavefront owns TM x TN
+//    MFMA tiles of 32x32 (block tile 64*TM x 64*TN), K step 64.
+//  * Both operands sit in LDS as rows of 64 k-contiguous bf16 (128 B), the
+//    16-byte chunks XOR-swizzled with the row index so that the 16-byte
+//    fragment reads of 8 consecutive rows cover all banks.
+//  * An operand whose reduction index is not the contiguous one in memory (B in
+//    NN, both in TN) is loaded as 8x8 blocks with 16-byte global loads and
+//    transposed in registers before it goes to LDS, so the compute loop is the
+//    same for the three layouts.
+//  * Global loads of step i+1 are issued before the MFMAs of step i (register
+//    prefetch); two blocks per CU overlap one block's LDS phase with the
+//    other's MFMA phase.
+//  * Blocks are renumbered so that each XCD (one L2 each, blocks are dealt
+//    round-robin over 8 of them) works on a compact band of tiles.
+//  * Gradient GEMMs with few output tiles split K over blockIdx.y and add
+//    their partial sums into the float output with hardware atomics.
+#include "device_utils.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+struct MfmaGemmParams {
+  const bf16* A; const bf16* B; void* C;
+  const bf16* bias; const bf16* residual; bf16* aux;
+  int64_t M, N, K, lda, ldb, ldc, ldaux;
+  int64_t a_ext, b_ext;   // readable extent (multiple of 8) of each operand's contiguous dimension
+  int c_float, act, atomic;
+  float beta;
+  int tiles_m, tiles_n, k_per_split;
+};
+
+#define BK 64
+
+__device__ inline int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+
+// ---- operand tile, reduction index contiguous in memory: elem(r, k) = p[(r0+r)*ld + k] ----
+template <int R>
+struct DirectTile {
+  static constexpr int N = R / 32;
+  uint4 v[N];
+  __device__ void load(const bf16* __restrict__ p, int64_t ld, int64_t r0, int64_t rlim, int64_t k0, int64_t kend) {
+    const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
+    const int64_t k = k0 + c * 8;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int64_t r = r0 + rr + i * 32;
+      if (r < rlim && k < kend) v[i] = *reinterpret_cast<const uint4*>(p + r * ld + k);
+      else v[i] = make_uint4(0, 0, 0, 0);
+    }
+  }
+  __device__ void store(char* lds) const {
+    const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
+#pragma unroll
+    for (int i = 0; i < N; ++i) *reinterpret_cast<uint4*>(lds + lds_off(rr + i * 32, c)) = v[i];
+  }
+};
+
+// ---- operand tile, reduction index strided in memory: elem(r, k) = p[k*ld + r0 + r] ----
+// A thread owns 8(k) x 8(r) blocks: 8 global loads of 16 bytes, transposed in registers.
+template <int R>
+struct TransTile {
+  static constexpr int NB = R >= 256 ? R / 256 : 1;
+  uint4 v[NB][8];
+  __device__ void load(const bf16* __restrict__ p, int64_t ld, int64_t r0, int64_t rext, int64_t k0, int64_t kend) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const int blk = threadIdx.x + b * 256;
+      const int xc = blk % (R / 8), kg = blk / (R / 8);
+      const int64_t r = r0 + xc * 8;
+      const bool live = blk < R && r < rext;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int64_t k = k0 + kg * 8 + i;
+        if (live && k < kend) v[b][i] = *reinterpret_cast<const uint4*>(p + k * ld + r);
+        else v[b][i] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  }
+  __device__ void store(char* lds) const {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const int blk = threadIdx.x + b * 256;
+      if (blk >= R) continue;
+      const int xc = blk % (R / 8), kg = blk / (R / 8);
+      const uint32_t* w = reinterpret_cast<const uint32_t*>(&v[b][0]);  // w[k*4 + word]
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        uint32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t lo = w[(2 * j) * 4 + (x >> 1)], hi = w[(2 * j + 1) * 4 + (x >> 1)];
+          o[j] = (x & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+        }
+        *reinterpret_cast<uint4*>(lds + lds_off(xc * 8 + x, kg)) = make_uint4(o[0], o[1], o[2], o[3]);
+      }
+    }
+  }
+};
+
+template <int LAYOUT, int R> struct ATile { typedef DirectTile<R> type; };
+template <int R> struct ATile<GEMM_TN, R> { typedef TransTile<R> type; };
+template <int LAYOUT, int R> struct BTile { typedef TransTile<R> type; };
+template <int R> struct BTile<GEMM_NT, R> { typedef DirectTile<R> type; };
+
+template <int LAYOUT, int TM, int TN>
+__global__ void __launch_bounds__(256, (TM * TN > 4 ? 1 : 2)) gemm_mfma_kernel(MfmaGemmParams p) {
+  constexpr int BM = TM * 64, BN = TN * 64;
+  __shared__ __attribute__((aligned(16))) char lds_a[BM * 128];
+  __shared__ __attribute__((aligned(16))) char lds_b[BN * 128];
+
+  // XCD-aware renumbering, then bands of 8 tile rows with the column index fastest inside a band
+  const int nt = p.tiles_m * p.tiles_n;
+  int id = blockIdx.x;
+  {
+    const int per = nt / 8;
+    if (id < per * 8) id = (id & 7) * per + (id >> 3);
+  }
+  const int band = 8 * p.tiles_n;
+  const int band_id = id / band;
+  const int rows_in_band = min(8, p.tiles_m - band_id * 8);
+  const int in_band = id - band_id * band;
+  const int tile_m = band_id * 8 + in_band % rows_in_band;
+  const int tile_n = in_band / rows_in_band;
+  const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+  const int64_t kbeg = (int64_t)blockIdx.y * p.k_per_split;
+  const int64_t kend = min(p.K, kbeg + p.k_per_split);
+  // reading limits: rows/cols past M, N give zeros; along k the contiguous operand may read its zero padding
+  const int64_t ka_end = LAYOUT == GEMM_TN ? kend : min(kend, p.a_ext);
+  const int64_t kb_end = LAYOUT == GEMM_NT ? min(kend, p.b_ext) : kend;
+  const int64_t ra_lim = LAYOUT == GEMM_TN ? p.a_ext : p.M;
+  const int64_t rb_lim = LAYOUT == GEMM_NT ? p.N : p.b_ext;
+
+  typename ATile<LAYOUT, BM>::type ta;
+  typename BTile<LAYOUT, BN>::type tb;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = (wave >> 1) * (TM * 32), wn = (wave & 1) * (TN * 32);
+  const int lr = lane & 31, lk = lane >> 5;
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+  ta.load(p.A, p.lda, m0, ra_lim, kbeg, ka_end);
+  tb.load(p.B, p.ldb, n0, rb_lim, kbeg, kb_end);
+  for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
+    ta.store(lds_a);
+    tb.store(lds_b);
+    __syncthreads();
+    if (k0 + BK < kend) {
+      ta.load(p.A, p.lda, m0, ra_lim, k0 + BK, ka_end);
+      tb.load(p.B, p.ldb, n0, rb_lim, k0 + BK, kb_end);
+    }
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(lds_a + lds_off(wm + i * 32 + lr, kk * 2 + lk));
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(lds_b + lds_off(wn + j * 32 + lr, kk * 2 + lk));
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // epilogue: accumulator q of a 32x32 tile is row (q/4)*8 + (lane/32)*4 + q%4, column lane%32
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int64_t n = n0 + wn + j * 32 + lr;
+    if (n >= p.N) continue;
+    const float bias = p.bias ? to_float<bf16>(p.bias[n]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int64_t m = m0 + wm + i * 32 + (q >> 2) * 8 + lk * 4 + (q & 3);
+        if (m >= p.M) continue;
+        float v = acc[i][j][q] + bias;
+        if (p.act == ACT_GELU) { p.aux[m * p.ldaux + n] = from_float<bf16>(v); v = gelu_tanh(v); }
+        else if (p.act == ACT_GELU_BWD) v *= gelu_tanh_grad(to_float<bf16>(p.aux[m * p.ldaux + n]));
+        if (p.residual) v += to_float<bf16>(p.residual[m * p.ldc + n]);
+        if (p.c_float) {
+          float* c = reinterpret_cast<float*>(p.C) + m * p.ldc + n;
+          if (p.atomic) unsafeAtomicAdd(c, v);
+          else *c = p.beta != 0.f ? v + p.beta * *c : v;
+        } else {
+          reinterpret_cast<bf16*>(p.C)[m * p.ldc + n] = from_float<bf16>(v);
+        }
+      }
+    }
+  }
+}
+
+template <int TM, int TN>
+static void launch_tiles(hipStream_t s, int layout, dim3 grid, const MfmaGemmParams& p) {
+  switch (layout) {
+    case GEMM_NT: hipLaunchKernelGGL((gemm_mfma_kernel<GEMM_NT, TM, TN>), grid, dim3(256), 0, s, p); break;
+    case GEMM_NN: hipLaunchKernelGGL((gemm_mfma_kernel<GEMM_NN, TM, TN>), grid, dim3(256), 0, s, p); break;
+    default: hipLaunchKernelGGL((gemm_mfma_kernel<GEMM_TN, TM, TN>), grid, dim3(256), 0, s, p); break;
+  }
+}
+
+int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a) {
+  if (a.M == 0 || a.N == 0) return POPLAR_OK;
+  if (a.layout < GEMM_NT || a.layout > GEMM_TN) return poplar_fail(POPLAR_ERR_INVALID, "unknown GEMM layout %d", a.layout);
+  MfmaGemmParams p;
+  p.A = (const bf16*)a.A; p.B = (const bf16*)a.B; p.C = a.C;
+  p.bias = (const bf16*)a.bias; p.residual = (const bf16*)a.residual; p.aux = (bf16*)a.aux;
+  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc; p.ldaux = a.ldaux;
+  p.c_float = a.c_float; p.act = a.act; p.beta = a.beta; p.atomic = 0;
+  // contiguous dimension of each operand: K for row-major [rows, K] operands, M or N for the transposed ones
+  const int64_t a_dim = a.layout == GEMM_TN ? a.M : a.K;
+  const int64_t b_dim = a.layout == GEMM_NT ? a.K : a.N;
+  p.a_ext = round_up(a_dim, 8);
+  p.b_ext = round_up(b_dim, 8);
+  if (p.a_ext > a.lda || p.b_ext > a.ldb)
+    return poplar_fail(POPLAR_ERR_INVALID, "bf16 GEMM needs contiguous dimensions padded to 8 elements (dims %lld/%lld, strides %lld/%lld)",
+                       (long long)a_dim, (long long)b_dim, (long long)a.lda, (long long)a.ldb);
+  if (a.lda % 8 || a.ldb % 8 || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15))
+    return poplar_fail(POPLAR_ERR_INVALID, "bf16 GEMM operands need 16-byte aligned rows");
+
+  // tile shape: 256x128 when that still fills the chip, else 128x128
+  const bool big = cdiv(a.M, 256) * cdiv(a.N, 128) >= 512;
+  const int BM = big ? 256 : 128, BN = 128;
+  p.tiles_m = (int)cdiv(a.M, BM);
+  p.tiles_n = (int)cdiv(a.N, BN);
+  const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+  // split K only for plain float-output GEMMs (weight gradients) that leave CUs idle
+  int splits = 1;
+  const bool plain = a.c_float && !a.bias && !a.residual && a.act == ACT_NONE;
+  if (plain && tiles < 384) {
+    splits = (int)std::min<int64_t>(cdiv(768, tiles), cdiv(a.K, 512));
+    if (splits < 1) splits = 1;
+  }
+  p.k_per_split = (int)round_up(cdiv(a.K, splits), BK);
+  splits = (int)cdiv(a.K, p.k_per_split);
+  if (splits > 1) {
+    p.atomic = 1;
+    if (a.beta == 0.f) {
+      if (a.ldc != a.N) {
+        for (int64_t m = 0; m < a.M; ++m) POPLAR_TRY(fill_zero(s, (float*)a.C + m * a.ldc, a.N * 4));
+      } else {
+        POPLAR_TRY(fill_zero(s, a.C, a.M * a.N * 4));
+      }
+    }
+  }
+  dim3 grid((unsigned)tiles, (unsigned)splits);
+  if (big) launch_tiles<4, 2>(s, a.layout, grid, p);
+  else launch_tiles<2, 2>(s, a.layout, grid, p);
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}

@@ -8,16 +8,56 @@ int gemm(hipStream_t s, int dtype, const GemmArgs& a) {
   return gemm_simple(s, dtype, a);
 }
 
-static int attn_fwd(hipStream_t s, const poplar_model_cfg& c, int B, const void* qkv, void* o, float* lse) {
-  const int d = c.hidden / c.n_head;
-  if (c.dtype == POPLAR_BF16) return attn_fwd_flash(s, B, c.seq, c.n_head, d, c.causal, qkv, o, lse);
-  return attn_fwd_simple(s, c.dtype, B, c.seq, c.n_head, d, c.causal, qkv, o, lse);
+// Launch wrappers that, inside a profiled step with kernel timing on, bracket
+// the launch with two events and note its algorithmic flop count.
+struct LaunchTimer {
+  poplar_ctx* ctx;
+  bool on;
+  TimedLaunch tl;
+  int begin(int kind, double flops) {
+    on = ctx->kernel_timing && ctx->in_step;
+    if (!on) return POPLAR_OK;
+    tl.kind = kind; tl.flops = flops;
+    return ctx_mark(ctx, &tl.a);
+  }
+  int end() {
+    if (!on) return POPLAR_OK;
+    POPLAR_TRY(ctx_mark(ctx, &tl.b));
+    ctx->launches.push_back(tl);
+    return POPLAR_OK;
+  }
+};
+static int gemm(poplar_ctx* ctx, const GemmArgs& a) {
+  LaunchTimer t{ctx};
+  POPLAR_TRY(t.begin(KIND_GEMM, 2.0 * (double)a.M * (double)a.N * (double)a.K));
+  POPLAR_TRY(gemm(ctx->stream, ctx->cfg.dtype, a));
+  return t.end();
 }
-static int attn_bwd(hipStream_t s, const poplar_model_cfg& c, int B, const void* qkv, const void* o, const void* dout,
-                    const float* lse, void* dqkv, float* delta) {
+
+// algorithmic attention flop: 2 S^2 H forward and 5 S^2 H backward per sample under a causal mask, twice that without
+static double attn_flops(const poplar_model_cfg& c, int B, double per_pair) {
+  return per_pair * (c.causal ? 1.0 : 2.0) * (double)B * (double)c.seq * (double)c.seq * (double)c.hidden;
+}
+static int attn_fwd(poplar_ctx* ctx, int B, const void* qkv, void* o, float* lse) {
+  const poplar_model_cfg& c = ctx->cfg;
+  hipStream_t s = ctx->stream;
   const int d = c.hidden / c.n_head;
-  if (c.dtype == POPLAR_BF16) return attn_bwd_flash(s, B, c.seq, c.n_head, d, c.causal, qkv, o, dout, lse, dqkv, delta);
-  return attn_bwd_simple(s, c.dtype, B, c.seq, c.n_head, d, c.causal, qkv, o, dout, lse, dqkv, delta);
+  LaunchTimer t{ctx};
+  POPLAR_TRY(t.begin(KIND_ATTN, attn_flops(c, B, 2.0)));
+  if (c.dtype == POPLAR_BF16) POPLAR_TRY(attn_fwd_flash(s, B, c.seq, c.n_head, d, c.causal, qkv, o, lse));
+  else POPLAR_TRY(attn_fwd_simple(s, c.dtype, B, c.seq, c.n_head, d, c.causal, qkv, o, lse));
+  return t.end();
+}
+static int attn_bwd(poplar_ctx* ctx, int B, const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv,
+                    float* delta) {
+  const poplar_model_cfg& c = ctx->cfg;
+  hipStream_t s = ctx->stream;
+  const int d = c.hidden / c.n_head;
+  LaunchTimer t{ctx};
+  POPLAR_TRY(t.begin(KIND_ATTN, attn_flops(c, B, 5.0)));
+  if (c.dtype == POPLAR_BF16) POPLAR_TRY(attn_bwd_flash(s, B, c.seq, c.n_head, d, c.causal, qkv, o, dout, lse, dqkv, delta));
+  else POPLAR_TRY(attn_bwd_simple(s, c.dtype, B, c.seq, c.n_head, d, c.causal, qkv, o, dout, lse, dqkv, delta));
+  return t.end();
 }
 
 static GemmArgs gemm_args(int layout, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb,
@@ -110,25 +150,25 @@ int layer_fwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* params,
   POPLAR_TRY(layernorm_fwd(s, c.dtype, T, (int)H, x_in, P(lo.g1), P(lo.b1), a, stats1, llama));
   GemmArgs ga = gemm_args(GEMM_NT, T, 3 * H, H, a, H, P(lo.wqkv), H, qkv, 3 * H);
   ga.bias = P(lo.bqkv);
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   if (llama) POPLAR_TRY(rope_inplace(s, c.dtype, B, c.seq, c.n_head, (int)(H / c.n_head), qkv, 3 * H, 1.0f));
-  POPLAR_TRY(attn_fwd(s, c, B, qkv, o, lse));
+  POPLAR_TRY(attn_fwd(ctx, B, qkv, o, lse));
   ga = gemm_args(GEMM_NT, T, H, H, o, H, P(lo.wo), H, x1, H);
   ga.bias = P(lo.bo); ga.residual = x_in;
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   POPLAR_TRY(layernorm_fwd(s, c.dtype, T, (int)H, x1, P(lo.g2), P(lo.b2), m, stats2, llama));
   if (llama) {
     ga = gemm_args(GEMM_NT, T, 2 * F, H, m, H, P(lo.w1), H, h, 2 * F);
-    POPLAR_TRY(gemm(s, c.dtype, ga));
+    POPLAR_TRY(gemm(ctx, ga));
     POPLAR_TRY(swiglu_fwd(s, c.dtype, T, (int)F, h, g));
   } else {
     ga = gemm_args(GEMM_NT, T, F, H, m, H, P(lo.w1), H, g, F);
     ga.bias = P(lo.bm1); ga.act = ACT_GELU; ga.aux = h; ga.ldaux = F;
-    POPLAR_TRY(gemm(s, c.dtype, ga));
+    POPLAR_TRY(gemm(ctx, ga));
   }
   ga = gemm_args(GEMM_NT, T, H, F, g, F, P(lo.w2), F, x_out, H);
   ga.bias = P(lo.bm2); ga.residual = x1;
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   return POPLAR_OK;
 }
 
@@ -161,43 +201,43 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
   if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, H, dy, H, G(lo.bm2), accumulate, scratch, scratch_n));
   ga = gemm_args(GEMM_TN, H, F, T, dy, H, g, F, G(lo.w2), F);
   ga.c_float = 1; ga.beta = beta;
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   if (llama) {
     void* dg = ws + bp.dg;
     ga = gemm_args(GEMM_NN, T, F, H, dy, H, P(lo.w2), F, dg, F);
-    POPLAR_TRY(gemm(s, c.dtype, ga));
+    POPLAR_TRY(gemm(ctx, ga));
     POPLAR_TRY(swiglu_bwd(s, c.dtype, T, (int)F, dg, h, dh));
   } else {
     ga = gemm_args(GEMM_NN, T, F, H, dy, H, P(lo.w2), F, dh, F);
     ga.act = ACT_GELU_BWD; ga.aux = const_cast<void*>(h); ga.ldaux = F;
-    POPLAR_TRY(gemm(s, c.dtype, ga));
+    POPLAR_TRY(gemm(ctx, ga));
     POPLAR_TRY(colsum(s, c.dtype, T, F, dh, F, G(lo.bm1), accumulate, scratch, scratch_n));
   }
   // MLP up projection
   ga = gemm_args(GEMM_TN, hw, H, T, dh, hw, m, H, G(lo.w1), H);
   ga.c_float = 1; ga.beta = beta;
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   ga = gemm_args(GEMM_NN, T, H, hw, dh, hw, P(lo.w1), H, dm, H);
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   // second norm; dx1 = dy + norm_bwd(dm)
   POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, dm, x1, P(lo.g2), stats2, dy, dx1, G(lo.g2), G(lo.b2), accumulate, scratch, scratch_n, llama));
   // attention output projection: x1 = x + o Wo^T + bo
   if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, H, dx1, H, G(lo.bo), accumulate, scratch, scratch_n));
   ga = gemm_args(GEMM_TN, H, H, T, dx1, H, o, H, G(lo.wo), H);
   ga.c_float = 1; ga.beta = beta;
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   ga = gemm_args(GEMM_NN, T, H, H, dx1, H, P(lo.wo), H, dob, H);
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   // attention
-  POPLAR_TRY(attn_bwd(s, c, B, qkv, o, dob, lse, dqkv, delta));
+  POPLAR_TRY(attn_bwd(ctx, B, qkv, o, dob, lse, dqkv, delta));
   if (llama) POPLAR_TRY(rope_inplace(s, c.dtype, B, c.seq, c.n_head, (int)(H / c.n_head), dqkv, 3 * H, -1.0f));
   // QKV projection
   if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, 3 * H, dqkv, 3 * H, G(lo.bqkv), accumulate, scratch, scratch_n));
   ga = gemm_args(GEMM_TN, 3 * H, H, T, dqkv, 3 * H, a, H, G(lo.wqkv), H);
   ga.c_float = 1; ga.beta = beta;
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   ga = gemm_args(GEMM_NN, T, H, 3 * H, dqkv, 3 * H, P(lo.wqkv), H, da, H);
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   // first norm; dx = dx1 + norm_bwd(da)
   POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, da, x_in, P(lo.g1), stats1, dx1, dx, G(lo.g1), G(lo.b1), accumulate, scratch, scratch_n, llama));
   return POPLAR_OK;
@@ -281,7 +321,7 @@ int head_fwd_part(poplar_ctx* ctx, int B, const void* x, const int32_t* targets,
   float *stats = (float*)(ws + hp.stats), *row_loss = (float*)(ws + hp.row_loss);
   POPLAR_TRY(layernorm_fwd(s, c.dtype, T, (int)H, x, gf, bf, hf, stats, llama));
   GemmArgs ga = gemm_args(GEMM_NT, T, V, H, hf, H, whead, H, logits, hp.ldl);
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   // the gradient of the logits replaces them in place; it belongs to the
   // forward half because it is one pass over the same rows
   POPLAR_TRY(xent_fwd_bwd(s, c.dtype, T, (int)V, hp.ldl, logits, targets, tgt_ld, c.seq, loss_scale, loss, row_loss));
@@ -300,9 +340,9 @@ int head_bwd_part(poplar_ctx* ctx, int B, const void* x, const void* gf, const v
   float *stats = (float*)(ws + hp.stats), *scratch = (float*)(ws + hp.scratch);
   GemmArgs ga = gemm_args(GEMM_TN, V, H, T, logits, hp.ldl, hf, H, d_whead, H);
   ga.c_float = 1; ga.beta = accumulate ? 1.f : 0.f;
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   ga = gemm_args(GEMM_NN, T, H, V, logits, hp.ldl, whead, H, dhf, H);
-  POPLAR_TRY(gemm(s, c.dtype, ga));
+  POPLAR_TRY(gemm(ctx, ga));
   POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, dhf, x, gf, stats, nullptr, dx, d_gf, d_bf, accumulate, scratch, scratch_floats(c), llama));
   return POPLAR_OK;
 }

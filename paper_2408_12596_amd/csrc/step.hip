@@ -13,6 +13,9 @@ extern "C" int poplar_create(const poplar_model_cfg* cfg, void* hip_stream, popl
   c->stream = (hipStream_t)hip_stream;
   memset(&c->st, 0, sizeof c->st);
   c->bound = false;
+  c->ev_next = 0;
+  c->kernel_timing = false;
+  c->in_step = false;
   *out = c;
   return POPLAR_OK;
 }
@@ -120,24 +123,27 @@ static double step_flops(const poplar_model_cfg& c, int B) {
 }
 
 // ---- event pool --------------------------------------------------------------
+int ctx_mark(poplar_ctx* ctx, hipEvent_t* e) {
+  if (ctx->ev_next == ctx->events.size()) {
+    hipEvent_t ne;
+    POPLAR_CHECK_HIP(hipEventCreate(&ne));
+    ctx->events.push_back(ne);
+  }
+  *e = ctx->events[ctx->ev_next++];
+  POPLAR_CHECK_HIP(hipEventRecord(*e, ctx->stream));
+  return POPLAR_OK;
+}
 struct EventCursor {
   poplar_ctx* ctx;
-  size_t next;
-  int get(hipEvent_t* e) {
-    if (next == ctx->events.size()) {
-      hipEvent_t ne;
-      POPLAR_CHECK_HIP(hipEventCreate(&ne));
-      ctx->events.push_back(ne);
-    }
-    *e = ctx->events[next++];
-    return POPLAR_OK;
-  }
-  int mark(hipEvent_t* e) {
-    POPLAR_TRY(get(e));
-    POPLAR_CHECK_HIP(hipEventRecord(*e, ctx->stream));
-    return POPLAR_OK;
-  }
+  int mark(hipEvent_t* e) { return ctx_mark(ctx, e); }
 };
+
+extern "C" int poplar_set_kernel_timing(poplar_ctx* ctx, int32_t on) {
+  if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
+  ctx->kernel_timing = on != 0;
+  return POPLAR_OK;
+}
+
 struct Span { hipEvent_t a, b; };
 
 static int span_seconds(const std::vector<Span>& v, double* out) {
@@ -178,7 +184,11 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   const int32_t* targets = st.tokens + 1;
   const float loss_scale = 1.0f / (float)((double)B * c.seq);
 
-  EventCursor ev{ctx, 0};
+  ctx->ev_next = 0;
+  ctx->launches.clear();
+  ctx->in_step = true;
+  struct StepScope { poplar_ctx* c; ~StepScope() { c->in_step = false; } } scope{ctx};
+  EventCursor ev{ctx};
   std::vector<Span> sp_gf, sp_gb, sp_red;
   hipEvent_t e_start, e_mid, e_bwd_end, e_adam_end;
 
@@ -298,6 +308,11 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   out->accounted_bytes = accounted_bytes(c, stage, B, forward_only);
   out->flops = forward_only ? step_flops(c, B) / 3.0 : step_flops(c, B);
   out->loss = loss_host;
+  for (const TimedLaunch& tl : ctx->launches) {
+    POPLAR_CHECK_HIP(hipEventElapsedTime(&ms, tl.a, tl.b));
+    if (tl.kind == KIND_GEMM) { out->t_gemm += ms * 1e-3; out->gemm_flops += tl.flops; out->n_gemm += 1; }
+    else { out->t_attn += ms * 1e-3; out->attn_flops += tl.flops; out->n_attn += 1; }
+  }
   return POPLAR_OK;
 }
 
