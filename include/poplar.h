@@ -130,6 +130,20 @@ int poplar_layer_bwd(poplar_ctx* ctx, int32_t B, const void* x_in, const void* d
                      const void* saved, void* dx, float* grads, int32_t accumulate,
                      void* workspace, int64_t workspace_bytes);
 
+/* The projection GEMM the layer is built from, on its own (lowp inputs, float
+ * accumulation): the three operand layouts of a Linear layer y = x W^T,
+ *   POPLAR_GEMM_NT  C[M,N] = A[M,K] B[N,K]^T      (forward)
+ *   POPLAR_GEMM_NN  C[M,N] = A[M,K] B[K,N]        (input gradient dx = dy W)
+ *   POPLAR_GEMM_TN  C[M,N] = A[K,M]^T B[K,N]      (weight gradient dW = dy^T x)
+ * A, B: device lowp, row-major with strides lda, ldb (elements).  C: device,
+ * lowp, or float when c_float = 1 (then C = A.B + beta C, beta 0 or 1).
+ * POPLAR_BF16 needs 16-byte aligned pointers, strides that are multiples of 8
+ * and at least the contiguous dimension rounded up to 8 (the padding of the
+ * reduction dimension must hold zeros). */
+enum { POPLAR_GEMM_NT = 0, POPLAR_GEMM_NN = 1, POPLAR_GEMM_TN = 2 };
+int poplar_gemm(poplar_ctx* ctx, int32_t layout, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_float, float beta);
+
 /* ---- embedding, head and loss --------------------------------------------- */
 
 /* x[b,s,:] = wte[tok[b,s],:] (+ wpe[s,:] for GPT).  tokens: device int32 [B,S]

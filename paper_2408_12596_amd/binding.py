@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(HERE, "libpoplar.so")
 
 OK, ERR_INVALID, ERR_OOM, ERR_HIP, ERR_UNIMPLEMENTED = 0, -1, -2, -3, -4
 ARCH_GPT, ARCH_LLAMA = 0, 1
+GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
 F32, BF16 = 0, 1
 (T_G1, T_B1, T_WQKV, T_BQKV, T_WO, T_BO, T_G2, T_B2, T_W1, T_BM1, T_W2, T_BM2) = range(12)
 T_WTE, T_WPE, T_GF, T_BF, T_WHEAD = 100, 101, 102, 103, 104
@@ -70,6 +71,7 @@ EXPORTS = [
     "poplar_head_loss_fwd_bwd", "poplar_adam_shard", "poplar_zero2_reduce_local", "poplar_zero3_gather_local",
     "poplar_bind_state", "poplar_step_workspace_bytes", "poplar_step_accounted_bytes", "poplar_profile_step",
     "poplar_search_mbs", "poplar_speed_curve", "poplar_allocate", "poplar_set_kernel_timing",
+    "poplar_gemm",
 ]
 
 _lib = None
@@ -114,6 +116,7 @@ def _declare(L):
         "poplar_profile_step": [vp, i32, i32, C.POINTER(Profile)],
         "poplar_search_mbs": [vp, i32, C.POINTER(i32), C.POINTER(Profile), i32, C.POINTER(i32)],
         "poplar_set_kernel_timing": [vp, i32],
+        "poplar_gemm": [vp, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, f32],
         "poplar_speed_curve": [C.POINTER(Curve), C.POINTER(f64)],
         "poplar_allocate": [i32, i32, C.POINTER(Curve), i64, f64, f64, C.POINTER(Alloc)],
     }
@@ -278,6 +281,9 @@ class Context:
     def layer_bwd(self, B, x_in, dy, params, saved, dx, grads, accumulate, workspace, workspace_bytes):
         _check(lib().poplar_layer_bwd(self._h, B, _ptr(x_in), _ptr(dy), _ptr(params), _ptr(saved), _ptr(dx), _ptr(grads),
                                       int(accumulate), _ptr(workspace), C.c_int64(workspace_bytes)))
+
+    def gemm(self, layout, M, N, K, A, lda, B, ldb, C, ldc, c_float=False, beta=0.0):
+        _check(lib().poplar_gemm(self._h, layout, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, int(c_float), beta))
 
     def embed_fwd(self, B, tokens, wte, wpe, x):
         _check(lib().poplar_embed_fwd(self._h, B, _ptr(tokens), _ptr(wte), _ptr(wpe), _ptr(x)))

@@ -86,6 +86,22 @@ __device__ inline float gelu_tanh_grad(float h) {
   return 0.5f * (1.0f + t) + 0.5f * h * dt;
 }
 
+// fast variants for bf16 outputs: tanh(u) = 1 - 2 / (exp(2u) + 1) with the hardware exp and reciprocal
+__device__ inline float tanh_fast(float u) {
+  const float e = __expf(2.0f * u);          // inf for large u gives 1, 0 for very negative u gives -1
+  return 1.0f - 2.0f * __frcp_rn(e + 1.0f);
+}
+__device__ inline float gelu_tanh_fast(float h) {
+  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
+  return 0.5f * h * (1.0f + tanh_fast(k0 * (h + k1 * h * h * h)));
+}
+__device__ inline float gelu_tanh_grad_fast(float h) {
+  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
+  const float t = tanh_fast(k0 * (h + k1 * h * h * h));
+  const float dt = (1.0f - t * t) * k0 * (1.0f + 3.0f * k1 * h * h);
+  return 0.5f * (1.0f + t) + 0.5f * h * dt;
+}
+
 // streaming (non-temporal) 16-byte / 8-byte accesses: index i counts vectors
 typedef float nt_f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t nt_u2 __attribute__((ext_vector_type(2)));

@@ -36,6 +36,7 @@ struct MfmaGemmParams {
 
 #define BK 64
 
+__device__ inline int64_t round_up_dev(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 __device__ inline int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
 // ---- operand tile, reduction index contiguous in memory: elem(r, k) = p[(r0+r)*ld + k] ----
@@ -110,8 +111,9 @@ template <int R> struct BTile<GEMM_NT, R> { typedef DirectTile<R> type; };
 template <int LAYOUT, int TM, int TN>
 __global__ void __launch_bounds__(256, (TM * TN > 4 ? 1 : 2)) gemm_mfma_kernel(MfmaGemmParams p) {
   constexpr int BM = TM * 64, BN = TN * 64;
-  __shared__ __attribute__((aligned(16))) char lds_a[BM * 128];
-  __shared__ __attribute__((aligned(16))) char lds_b[BN * 128];
+  __shared__ __attribute__((aligned(16))) char lds_all[(BM + BN) * 128];
+  char* const lds_a = lds_all;
+  char* const lds_b = lds_all + BM * 128;
 
   // XCD-aware renumbering, then bands of 8 tile rows with the column index fastest inside a band
   const int nt = p.tiles_m * p.tiles_n;
@@ -175,30 +177,80 @@ __global__ void __launch_bounds__(256, (TM * TN > 4 ? 1 : 2)) gemm_mfma_kernel(M
     __syncthreads();
   }
 
-  // epilogue: accumulator q of a 32x32 tile is row (q/4)*8 + (lane/32)*4 + q%4, column lane%32
+  // Epilogue.  Accumulator q of a 32x32 tile is row (q/4)*8 + (lane/32)*4 + q%4,
+  // column lane%32.  Each wavefront passes its tiles through a private float
+  // staging area in LDS, 16 rows at a time, and reads them back as groups of 8
+  // consecutive columns, so that bias / activation / residual work on vectors
+  // and every global access is 16 bytes wide.
+  constexpr int SW = TN * 32 + 4;          // staging row stride in floats
+  constexpr int GROUPS = TN * 4;           // 8-column groups per staging row
+  float* stage = reinterpret_cast<float*>(lds_a) + wave * (16 * SW);
+  const int64_t n_ext = round_up_dev(p.N, 8);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int64_t n = n0 + wn + j * 32 + lr;
-    if (n >= p.N) continue;
-    const float bias = p.bias ? to_float<bf16>(p.bias[n]) : 0.f;
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int half = 0; half < 2; ++half) {
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int64_t m = m0 + wm + i * 32 + (q >> 2) * 8 + lk * 4 + (q & 3);
-        if (m >= p.M) continue;
-        float v = acc[i][j][q] + bias;
-        if (p.act == ACT_GELU) { p.aux[m * p.ldaux + n] = from_float<bf16>(v); v = gelu_tanh(v); }
-        else if (p.act == ACT_GELU_BWD) v *= gelu_tanh_grad(to_float<bf16>(p.aux[m * p.ldaux + n]));
-        if (p.residual) v += to_float<bf16>(p.residual[m * p.ldc + n]);
-        if (p.c_float) {
-          float* c = reinterpret_cast<float*>(p.C) + m * p.ldc + n;
-          if (p.atomic) unsafeAtomicAdd(c, v);
-          else *c = p.beta != 0.f ? v + p.beta * *c : v;
-        } else {
-          reinterpret_cast<bf16*>(p.C)[m * p.ldc + n] = from_float<bf16>(v);
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          stage[((q >> 2) * 8 + lk * 4 + (q & 3)) * SW + j * 32 + lr] = acc[i][j][half * 8 + q];
+      wave_lds_sync();
+#pragma unroll
+      for (int it = 0; it < 16 * GROUPS / 64; ++it) {
+        const int gid = lane + it * 64;
+        const int row = gid / GROUPS, cg = gid % GROUPS;
+        const int64_t m = m0 + wm + i * 32 + half * 16 + row;
+        const int64_t n = n0 + wn + cg * 8;
+        float v[8];
+        {
+          const float4 lo = *reinterpret_cast<const float4*>(stage + row * SW + cg * 8);
+          const float4 hi = *reinterpret_cast<const float4*>(stage + row * SW + cg * 8 + 4);
+          v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+        }
+        if (m < p.M && n < n_ext) {
+          Vec<bf16> t;
+          float f[8];
+          if (p.bias) {
+            t.load(p.bias + n); t.unpack(f);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] += f[k];
+          }
+          if (p.act == ACT_GELU) {
+            t.pack(v); t.store(p.aux + m * p.ldaux + n);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = gelu_tanh_fast(v[k]);
+          } else if (p.act == ACT_GELU_BWD) {
+            t.load(p.aux + m * p.ldaux + n); t.unpack(f);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] *= gelu_tanh_grad_fast(f[k]);
+          }
+          if (p.residual) {
+            t.load(p.residual + m * p.ldc + n); t.unpack(f);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] += f[k];
+          }
+          if (p.c_float) {
+            float* c = reinterpret_cast<float*>(p.C) + m * p.ldc + n;
+            if (p.atomic) {
+#pragma unroll
+              for (int k = 0; k < 8; ++k) unsafeAtomicAdd(c + k, v[k]);
+            } else {
+              float4 lo = make_float4(v[0], v[1], v[2], v[3]), hi = make_float4(v[4], v[5], v[6], v[7]);
+              if (p.beta != 0.f) {
+                const float4 ol = *reinterpret_cast<const float4*>(c), oh = *reinterpret_cast<const float4*>(c + 4);
+                lo.x += p.beta * ol.x; lo.y += p.beta * ol.y; lo.z += p.beta * ol.z; lo.w += p.beta * ol.w;
+                hi.x += p.beta * oh.x; hi.y += p.beta * oh.y; hi.z += p.beta * oh.z; hi.w += p.beta * oh.w;
+              }
+              *reinterpret_cast<float4*>(c) = lo;
+              *reinterpret_cast<float4*>(c + 4) = hi;
+            }
+          } else {
+            t.pack(v); t.store(reinterpret_cast<bf16*>(p.C) + m * p.ldc + n);
+          }
         }
       }
+      wave_lds_sync();
     }
   }
 }
@@ -230,6 +282,10 @@ int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a) {
                        (long long)a_dim, (long long)b_dim, (long long)a.lda, (long long)a.ldb);
   if (a.lda % 8 || a.ldb % 8 || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15))
     return poplar_fail(POPLAR_ERR_INVALID, "bf16 GEMM operands need 16-byte aligned rows");
+  // the epilogue moves 8 columns at a time
+  if (a.ldc % 8 || a.ldc < round_up(a.N, 8) || ((uintptr_t)a.C & 15) || (a.aux && (a.ldaux % 8 || ((uintptr_t)a.aux & 15))) ||
+      (a.bias && ((uintptr_t)a.bias & 15)) || (a.residual && ((uintptr_t)a.residual & 15)))
+    return poplar_fail(POPLAR_ERR_INVALID, "bf16 GEMM output rows need 16-byte alignment and a stride covering N rounded up to 8");
 
   // tile shape: 256x128 when that still fills the chip, else 128x128
   const bool big = cdiv(a.M, 256) * cdiv(a.N, 128) >= 512;

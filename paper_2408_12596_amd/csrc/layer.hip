@@ -268,6 +268,19 @@ extern "C" int poplar_layer_bwd(poplar_ctx* ctx, int32_t B, const void* x_in, co
   return layer_bwd_impl(ctx, B, x_in, dy, params, saved, dx, grads, accumulate, workspace);
 }
 
+extern "C" int poplar_gemm(poplar_ctx* ctx, int32_t layout, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                           const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_float, float beta) {
+  if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
+  if (layout < GEMM_NT || layout > GEMM_TN) return poplar_fail(POPLAR_ERR_INVALID, "unknown GEMM layout %d", layout);
+  if (M < 0 || N < 0 || K < 0 || lda < 1 || ldb < 1 || ldc < N) return poplar_fail(POPLAR_ERR_INVALID, "bad GEMM extents");
+  if (M == 0 || N == 0) return POPLAR_OK;
+  if (!A || !B || !C) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
+  if (beta != 0.f && !(c_float && beta == 1.f)) return poplar_fail(POPLAR_ERR_INVALID, "beta must be 0, or 1 with a float output");
+  GemmArgs ga = gemm_args(layout, M, N, K, A, lda, B, ldb, C, ldc);
+  ga.c_float = c_float ? 1 : 0; ga.beta = beta;
+  return gemm(ctx, ga);
+}
+
 // ---- embedding -------------------------------------------------------------
 extern "C" int poplar_embed_fwd(poplar_ctx* ctx, int32_t B, const int32_t* tokens, const void* wte, const void* wpe, void* x) {
   POPLAR_TRY(check_ctx_batch(ctx, B));

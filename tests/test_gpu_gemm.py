@@ -1,0 +1,100 @@
+"""GPU parity of the projection GEMM on its own: the three layouts, ragged and
+tile-straddling extents, float accumulation into an existing output, and the
+workload's full-size shapes checked on sampled outputs."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2408_12596_amd import binding as pb
+from gpu_util import DEV, rel_l2, to_np, sync
+
+pytestmark = pytest.mark.gpu
+
+
+def operands(layout, M, N, K, dtype, seed, pad=0):
+    """A, B as the layout stores them, with row strides padded by `pad` elements."""
+    g = torch.Generator().manual_seed(seed)
+    shape_a = (K, M) if layout == pb.GEMM_TN else (M, K)
+    shape_b = (N, K) if layout == pb.GEMM_NT else (K, N)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+
+    def mk(shape):
+        full = torch.zeros(shape[0], shape[1] + (-shape[1]) % 8 + pad, dtype=td)   # zero-padded rows, stride a multiple of 8
+        full[:, :shape[1]] = torch.randn(shape, generator=g).to(td)
+        return full.to(DEV)
+    return mk(shape_a), mk(shape_b), shape_a, shape_b
+
+
+def oracle(layout, A, B, shape_a, shape_b):
+    """The definition: C = sum_k A(m,k) B(k,n) in float64 on the host."""
+    a = A[:, :shape_a[1]].double().cpu().numpy()
+    b = B[:, :shape_b[1]].double().cpu().numpy()
+    if layout == pb.GEMM_NT:
+        return a @ b.T
+    if layout == pb.GEMM_NN:
+        return a @ b
+    return a.T @ b
+
+
+SHAPES = [(64, 64, 64), (128, 128, 64), (200, 136, 72), (129, 257, 520), (1000, 72, 40), (8, 8, 8), (300, 520, 1288), (1, 8, 16)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("layout", [pb.GEMM_NT, pb.GEMM_NN, pb.GEMM_TN])
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_gemm_matches_definition(layout, M, N, K, dtype):
+    ctx = pb.Context(pb.make_cfg(dtype=dtype))
+    A, B, sa, sb = operands(layout, M, N, K, dtype, seed=M + N + K, pad=8)
+    ref = oracle(layout, A, B, sa, sb)
+    tol = 5e-3 if dtype == "bf16" else 1e-5
+    # lowp output
+    C = torch.full((M, N + (-N) % 8 + 8), 7.0, dtype=A.dtype, device=DEV)
+    ctx.gemm(layout, M, N, K, A, A.shape[1], B, B.shape[1], C, C.shape[1])
+    # float output, overwritten then accumulated
+    ldc = N + (-N) % 8                      # output stride: a multiple of 8 covering N
+    Cf = torch.full((M, ldc), float("nan"), device=DEV)
+    ctx.gemm(layout, M, N, K, A, A.shape[1], B, B.shape[1], Cf, ldc, c_float=True, beta=0.0)
+    sync()
+    assert rel_l2(to_np(C[:, :N]), ref) <= tol
+    assert rel_l2(to_np(Cf[:, :N]), ref) <= 1e-5   # float output: only the accumulation order differs
+    ctx.gemm(layout, M, N, K, A, A.shape[1], B, B.shape[1], Cf, ldc, c_float=True, beta=1.0)
+    sync()
+    assert rel_l2(to_np(Cf[:, :N]), 2 * ref) <= 1e-5
+
+
+FULL = [
+    # the GPT-2-small workload at local batch 16 (T = 16384 tokens): QKV, MLP up/down, their gradients, the LM head
+    (pb.GEMM_NT, 16384, 2304, 768), (pb.GEMM_NT, 16384, 768, 3072), (pb.GEMM_NN, 16384, 3072, 768),
+    (pb.GEMM_TN, 3072, 768, 16384), (pb.GEMM_TN, 768, 3072, 16384), (pb.GEMM_NT, 4096, 50257, 768), (pb.GEMM_TN, 50257, 768, 4096),
+    (pb.GEMM_NN, 4096, 768, 50257),
+]
+
+
+@pytest.mark.parametrize("layout,M,N,K", FULL)
+def test_gemm_full_size_on_sampled_outputs(layout, M, N, K):
+    ctx = pb.Context(pb.make_cfg(dtype="bf16"))
+    pad = (-(N if layout != pb.GEMM_NT else K)) % 8 + 8
+    pad_a = (-(M if layout == pb.GEMM_TN else K)) % 8 + 8
+    g = torch.Generator().manual_seed(layout * 7 + 1)
+    sa = (K, M) if layout == pb.GEMM_TN else (M, K)
+    sb = (N, K) if layout == pb.GEMM_NT else (K, N)
+    A = torch.zeros(sa[0], sa[1] + pad_a, dtype=torch.bfloat16)
+    A[:, :sa[1]] = torch.randn(sa, generator=g).to(torch.bfloat16)
+    B = torch.zeros(sb[0], sb[1] + pad, dtype=torch.bfloat16)
+    B[:, :sb[1]] = torch.randn(sb, generator=g).to(torch.bfloat16)
+    A, B = A.to(DEV), B.to(DEV)
+    ldc = N + (-N) % 8
+    Cf = torch.full((M, ldc), float("nan"), device=DEV)
+    ctx.gemm(layout, M, N, K, A, A.shape[1], B, B.shape[1], Cf, ldc, c_float=True, beta=0.0)
+    sync()
+    rng = np.random.default_rng(0)
+    ms = np.unique(np.concatenate([rng.integers(0, M, 40), [0, M - 1, min(M - 1, 255), min(M - 1, 256)]]))
+    ns = np.unique(np.concatenate([rng.integers(0, N, 40), [0, N - 1, min(N - 1, 127), min(N - 1, 128)]]))
+    a = A[:, :sa[1]].double().cpu()
+    b = B[:, :sb[1]].double().cpu()
+    rows = a[:, ms].T if layout == pb.GEMM_TN else a[ms]          # [len(ms), K]
+    cols = b[ns].T if layout == pb.GEMM_NT else b[:, ns]           # [K, len(ns)]
+    ref = (rows @ cols).numpy()
+    got = Cf[ms][:, ns].double().cpu().numpy()
+    assert rel_l2(got, ref) <= 1e-5
+    assert torch.isfinite(Cf[:, :N]).all()
