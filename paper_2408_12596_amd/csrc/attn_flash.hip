@@ -79,7 +79,7 @@ struct PermutedTranspose {
   __device__ static bool mine(int tid0) { return (int)threadIdx.x >= tid0 && (int)threadIdx.x < tid0 + D; }
   __device__ void load(const bf16* __restrict__ p, int64_t ld, int r0, int rlim, int tid0) {
     const int bid = threadIdx.x - tid0;
-    const int cx = bid % (D / 8), jg = bid / (D / 8);
+    const int jg = bid & 7, cx = bid >> 3;   // 8 lanes share a column chunk: their LDS writes fill one 128-byte row
     const int rbase = r0 + 16 * (jg >> 1) + 4 * (jg & 1);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -90,7 +90,7 @@ struct PermutedTranspose {
   }
   __device__ void store(char* lds, int tid0) const {
     const int bid = threadIdx.x - tid0;
-    const int cx = bid % (D / 8), jg = bid / (D / 8);
+    const int jg = bid & 7, cx = bid >> 3;
     const uint32_t* w = reinterpret_cast<const uint32_t*>(&v[0]);  // w[row * 4 + word]
 #pragma unroll
     for (int x = 0; x < 8; ++x) {

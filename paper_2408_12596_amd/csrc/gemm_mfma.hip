@@ -9,9 +9,9 @@
 //    16-byte chunks XOR-swizzled with the row index so that the 16-byte
 //    fragment reads of 8 consecutive rows cover all banks.
 //  * An operand whose reduction index is not the contiguous one in memory (B in
-//    NN, both in TN) is loaded as 8x8 blocks with 16-byte global loads and
-//    transposed in registers before it goes to LDS, so the compute loop is the
-//    same for the three layouts.
+//    NN, both in TN) is copied to LDS as it lies in memory and its fragments are
+//    read with the transposing LDS load of gfx950 (ds_read_b64_tr_b16), so no
+//    layout pays for a register transpose.
 //  * Global loads of step i+1 are issued before the MFMAs of step i (register
 //    prefetch); two blocks per CU overlap one block's LDS phase with the
 //    other's MFMA phase.
@@ -40,9 +40,11 @@ __device__ inline int64_t round_up_dev(int64_t x, int64_t a) { return (x + a - 1
 __device__ inline int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
 // ---- operand tile, reduction index contiguous in memory: elem(r, k) = p[(r0+r)*ld + k] ----
+// LDS image: R rows of 64 k-values (128 B), 16-byte chunks XOR-swizzled with the row.
 template <int R>
 struct DirectTile {
   static constexpr int N = R / 32;
+  static constexpr int LDS_BYTES = R * 128;
   uint4 v[N];
   __device__ void load(const bf16* __restrict__ p, int64_t ld, int64_t r0, int64_t rlim, int64_t k0, int64_t kend) {
     const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
@@ -59,61 +61,70 @@ struct DirectTile {
 #pragma unroll
     for (int i = 0; i < N; ++i) *reinterpret_cast<uint4*>(lds + lds_off(rr + i * 32, c)) = v[i];
   }
+  // fragment of the 32-row MFMA tile starting at row `ro`, k-slice kk (16 values)
+  __device__ static bf16x8 frag(const char* lds, int ro, int kk, int lane) {
+    return *reinterpret_cast<const bf16x8*>(lds + lds_off(ro + (lane & 31), kk * 2 + (lane >> 5)));
+  }
 };
 
 // ---- operand tile, reduction index strided in memory: elem(r, k) = p[k*ld + r0 + r] ----
-// A thread owns 8(k) x 8(r) blocks: 8 global loads of 16 bytes, transposed in registers.
+// LDS image: the tile as it lies in memory, 64 k-rows of R values (row stride
+// padded by 64 B so that four consecutive k-rows start in different bank
+// quarters).  The fragment is read with the LDS transpose load of gfx950
+// (ds_read_b64_tr_b16): inside a group of 16 lanes, lane j passes the address
+// of 4 consecutive values of k-row j/4 at column 4*(j%4), and receives the 4
+// k-values of column j - two such loads give the 8 k-values of an MFMA
+// fragment.
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 template <int R>
-struct TransTile {
-  static constexpr int NB = R >= 256 ? R / 256 : 1;
-  uint4 v[NB][8];
+struct TrTile {
+  static constexpr int N = R / 32;              // 16-byte chunks per thread
+  static constexpr int STRIDE = R * 2 + 64;     // bytes per k-row
+  static constexpr int LDS_BYTES = 64 * STRIDE;
+  uint4 v[N];
   __device__ void load(const bf16* __restrict__ p, int64_t ld, int64_t r0, int64_t rext, int64_t k0, int64_t kend) {
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      const int blk = threadIdx.x + b * 256;
-      const int xc = blk % (R / 8), kg = blk / (R / 8);
-      const int64_t r = r0 + xc * 8;
-      const bool live = blk < R && r < rext;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int64_t k = k0 + kg * 8 + i;
-        if (live && k < kend) v[b][i] = *reinterpret_cast<const uint4*>(p + k * ld + r);
-        else v[b][i] = make_uint4(0, 0, 0, 0);
-      }
+    for (int i = 0; i < N; ++i) {
+      const int idx = threadIdx.x + i * 256;
+      const int k = idx / (R / 8), c = idx % (R / 8);
+      const int64_t r = r0 + c * 8;
+      if (k0 + k < kend && r < rext) v[i] = *reinterpret_cast<const uint4*>(p + (k0 + k) * ld + r);
+      else v[i] = make_uint4(0, 0, 0, 0);
     }
   }
   __device__ void store(char* lds) const {
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      const int blk = threadIdx.x + b * 256;
-      if (blk >= R) continue;
-      const int xc = blk % (R / 8), kg = blk / (R / 8);
-      const uint32_t* w = reinterpret_cast<const uint32_t*>(&v[b][0]);  // w[k*4 + word]
-#pragma unroll
-      for (int x = 0; x < 8; ++x) {
-        uint32_t o[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint32_t lo = w[(2 * j) * 4 + (x >> 1)], hi = w[(2 * j + 1) * 4 + (x >> 1)];
-          o[j] = (x & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
-        }
-        *reinterpret_cast<uint4*>(lds + lds_off(xc * 8 + x, kg)) = make_uint4(o[0], o[1], o[2], o[3]);
-      }
+    for (int i = 0; i < N; ++i) {
+      const int idx = threadIdx.x + i * 256;
+      const int k = idx / (R / 8), c = idx % (R / 8);
+      *reinterpret_cast<uint4*>(lds + k * STRIDE + c * 16) = v[i];
     }
+  }
+  __device__ static bf16x8 frag(const char* lds, int ro, int kk, int lane) {
+    const int j = lane & 15, gi = (lane >> 4) & 1, lk = lane >> 5;
+    const char* q = lds + (kk * 16 + lk * 8 + (j >> 2)) * STRIDE + (ro + gi * 16 + 4 * (j & 3)) * 2;
+    typedef __attribute__((address_space(3))) bf16x4* lds_ptr;
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(q));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(q + 4 * STRIDE));
+    bf16x8 f;
+    f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3]; f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
+    return f;
   }
 };
 
 template <int LAYOUT, int R> struct ATile { typedef DirectTile<R> type; };
-template <int R> struct ATile<GEMM_TN, R> { typedef TransTile<R> type; };
-template <int LAYOUT, int R> struct BTile { typedef TransTile<R> type; };
+template <int R> struct ATile<GEMM_TN, R> { typedef TrTile<R> type; };
+template <int LAYOUT, int R> struct BTile { typedef TrTile<R> type; };
 template <int R> struct BTile<GEMM_NT, R> { typedef DirectTile<R> type; };
 
-template <int LAYOUT, int TM, int TN>
-__global__ void __launch_bounds__(256, (TM * TN > 4 ? 1 : 2)) gemm_mfma_kernel(MfmaGemmParams p) {
+template <int LAYOUT, int TM, int TN, bool ATOMIC>
+__global__ void __launch_bounds__(256, (TM * TN > 4 && LAYOUT == GEMM_TN ? 1 : 2)) gemm_mfma_kernel(MfmaGemmParams p) {
   constexpr int BM = TM * 64, BN = TN * 64;
-  __shared__ __attribute__((aligned(16))) char lds_all[(BM + BN) * 128];
+  typedef typename ATile<LAYOUT, BM>::type TileA;
+  typedef typename BTile<LAYOUT, BN>::type TileB;
+  __shared__ __attribute__((aligned(16))) char lds_all[TileA::LDS_BYTES + TileB::LDS_BYTES];
   char* const lds_a = lds_all;
-  char* const lds_b = lds_all + BM * 128;
+  char* const lds_b = lds_all + TileA::LDS_BYTES;
 
   // XCD-aware renumbering, then bands of 8 tile rows with the column index fastest inside a band
   const int nt = p.tiles_m * p.tiles_n;
@@ -137,8 +148,8 @@ __global__ void __launch_bounds__(256, (TM * TN > 4 ? 1 : 2)) gemm_mfma_kernel(M
   const int64_t ra_lim = LAYOUT == GEMM_TN ? p.a_ext : p.M;
   const int64_t rb_lim = LAYOUT == GEMM_NT ? p.N : p.b_ext;
 
-  typename ATile<LAYOUT, BM>::type ta;
-  typename BTile<LAYOUT, BN>::type tb;
+  TileA ta;
+  TileB tb;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = (wave >> 1) * (TM * 32), wn = (wave & 1) * (TN * 32);
@@ -166,9 +177,9 @@ __global__ void __launch_bounds__(256, (TM * TN > 4 ? 1 : 2)) gemm_mfma_kernel(M
     for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8 fa[TM], fb[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(lds_a + lds_off(wm + i * 32 + lr, kk * 2 + lk));
+      for (int i = 0; i < TM; ++i) fa[i] = TileA::frag(lds_a, wm + i * 32, kk, lane);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(lds_b + lds_off(wn + j * 32 + lr, kk * 2 + lk));
+      for (int j = 0; j < TN; ++j) fb[j] = TileB::frag(lds_b, wn + j * 32, kk, lane);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -182,6 +193,22 @@ __global__ void __launch_bounds__(256, (TM * TN > 4 ? 1 : 2)) gemm_mfma_kernel(M
   // staging area in LDS, 16 rows at a time, and reads them back as groups of 8
   // consecutive columns, so that bias / activation / residual work on vectors
   // and every global access is 16 bytes wide.
+  if (ATOMIC) {
+    // split-K partial sums: float atomics straight from the accumulators, 32
+    // lanes on 32 consecutive columns of one row per instruction
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int64_t n = n0 + wn + j * 32 + lr;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const int64_t m = m0 + wm + i * 32 + (q >> 2) * 8 + lk * 4 + (q & 3);
+          if (m < p.M && n < p.N) unsafeAtomicAdd(reinterpret_cast<float*>(p.C) + m * p.ldc + n, acc[i][j][q]);
+        }
+    }
+    return;
+  }
   constexpr int SW = TN * 32 + 4;          // staging row stride in floats
   constexpr int GROUPS = TN * 4;           // 8-column groups per staging row
   float* stage = reinterpret_cast<float*>(lds_a) + wave * (16 * SW);
@@ -232,10 +259,7 @@ __global__ void __launch_bounds__(256, (TM * TN > 4 ? 1 : 2)) gemm_mfma_kernel(M
           }
           if (p.c_float) {
             float* c = reinterpret_cast<float*>(p.C) + m * p.ldc + n;
-            if (p.atomic) {
-#pragma unroll
-              for (int k = 0; k < 8; ++k) unsafeAtomicAdd(c + k, v[k]);
-            } else {
+            {
               float4 lo = make_float4(v[0], v[1], v[2], v[3]), hi = make_float4(v[4], v[5], v[6], v[7]);
               if (p.beta != 0.f) {
                 const float4 ol = *reinterpret_cast<const float4*>(c), oh = *reinterpret_cast<const float4*>(c + 4);
@@ -255,12 +279,12 @@ __global__ void __launch_bounds__(256, (TM * TN > 4 ? 1 : 2)) gemm_mfma_kernel(M
   }
 }
 
-template <int TM, int TN>
+template <int TM, int TN, bool ATOMIC>
 static void launch_tiles(hipStream_t s, int layout, dim3 grid, const MfmaGemmParams& p) {
   switch (layout) {
-    case GEMM_NT: hipLaunchKernelGGL((gemm_mfma_kernel<GEMM_NT, TM, TN>), grid, dim3(256), 0, s, p); break;
-    case GEMM_NN: hipLaunchKernelGGL((gemm_mfma_kernel<GEMM_NN, TM, TN>), grid, dim3(256), 0, s, p); break;
-    default: hipLaunchKernelGGL((gemm_mfma_kernel<GEMM_TN, TM, TN>), grid, dim3(256), 0, s, p); break;
+    case GEMM_NT: hipLaunchKernelGGL((gemm_mfma_kernel<GEMM_NT, TM, TN, ATOMIC>), grid, dim3(256), 0, s, p); break;
+    case GEMM_NN: hipLaunchKernelGGL((gemm_mfma_kernel<GEMM_NN, TM, TN, ATOMIC>), grid, dim3(256), 0, s, p); break;
+    default: hipLaunchKernelGGL((gemm_mfma_kernel<GEMM_TN, TM, TN, ATOMIC>), grid, dim3(256), 0, s, p); break;
   }
 }
 
@@ -313,8 +337,13 @@ int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a) {
     }
   }
   dim3 grid((unsigned)tiles, (unsigned)splits);
-  if (big) launch_tiles<4, 2>(s, a.layout, grid, p);
-  else launch_tiles<2, 2>(s, a.layout, grid, p);
+  if (p.atomic) {
+    if (big) launch_tiles<4, 2, true>(s, a.layout, grid, p);
+    else launch_tiles<2, 2, true>(s, a.layout, grid, p);
+  } else {
+    if (big) launch_tiles<4, 2, false>(s, a.layout, grid, p);
+    else launch_tiles<2, 2, false>(s, a.layout, grid, p);
+  }
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }
