@@ -31,7 +31,15 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 __device__ inline bf16x8 as_frag(uint4 v) { return *reinterpret_cast<bf16x8*>(&v); }
 
-__device__ inline uint32_t pack_bf16(float a, float b) { return float_to_bf16_bits(a) | (float_to_bf16_bits(b) << 16); }
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+// two floats to packed bfloat16 (round to nearest even) with one v_cvt_pk_bf16_f32
+__device__ inline uint32_t pack_bf16(float a, float b) {
+  floatx2 f = {a, b};
+  bf16x2 h = __builtin_convertvector(f, bf16x2);
+  return *reinterpret_cast<uint32_t*>(&h);
+}
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // registers 8s .. 8s+7 of a C tile as a B fragment
 __device__ inline bf16x8 regs_to_frag(const floatx16& c, int s) {
@@ -195,26 +203,33 @@ __global__ void __launch_bounds__(256) flash_fwd_kernel(const bf16* __restrict__
       for (int s = 0; s < D / 16; ++s)
         st[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(DirectRows<D>::frag(k_lds, u * 32 + lr, s, g), qf[s], st[u], 0, 0, 0);
     }
+    // only tiles that touch the diagonal of this wave's queries or the end of the sequence need the mask
+    const int qw0 = q0 + wave * 32;
+    if ((causal && kv0 + 63 > qw0) || kv0 + 64 > S) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int kv = kv0 + u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
+          const bool ok = kv < S && (!causal || kv <= q);
+          st[u][i] = ok ? st[u][i] : -INFINITY;
+        }
+    }
     float mx = -INFINITY;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int kv = kv0 + u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-        const bool ok = kv < S && (!causal || kv <= q);
-        st[u][i] = ok ? st[u][i] * c2 : -INFINITY;
-        mx = fmaxf(mx, st[u][i]);
-      }
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, st[u][i]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = exp2f(m_run - m_use);   // m_run = -inf gives 0
+    const float m_new = fmaxf(m_run, mx);                   // running max of the raw scores
+    const float mc = (m_new == -INFINITY ? 0.f : m_new) * c2;
+    const float alpha = fast_exp2(m_run * c2 - mc);         // m_run = -inf gives 0
     float psum = 0.f;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        st[u][i] = exp2f(st[u][i] - m_use);
+        st[u][i] = fast_exp2(__builtin_fmaf(st[u][i], c2, -mc));
         psum += st[u][i];
       }
     l_run = l_run * alpha + psum;
@@ -236,7 +251,7 @@ __global__ void __launch_bounds__(256) flash_fwd_kernel(const bf16* __restrict__
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   store_rows_from_transposed<D>(o + (int64_t)b * S * H + h * D, H, q, S, g, oacc, inv);
-  if (g == 0 && q < S) lse[((int64_t)b * nh + h) * S + q] = (m_run + log2f(l_tot)) * LN2;
+  if (g == 0 && q < S) lse[((int64_t)b * nh + h) * S + q] = (m_run * c2 + log2f(l_tot)) * LN2;
 }
 
 // =============================================================================
@@ -330,12 +345,20 @@ __global__ void __launch_bounds__(256) flash_bwd_dq_kernel(const bf16* __restric
         st[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(DirectRows<D>::frag(k_lds, u * 32 + lr, s, g), qf[s], st[u], 0, 0, 0);
         dpt[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(DirectRows<D>::frag(v_lds, u * 32 + lr, s, g), dof[s], dpt[u], 0, 0, 0);
       }
+      if ((causal && kv0 + 63 > q0 + wave * 32) || kv0 + 64 > S || q0 + 128 > S) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int kv = kv0 + u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-        const bool ok = kv < S && q < S && (!causal || kv <= q);
-        const float p = ok ? exp2f(st[u][i] * c2 - lse2) : 0.f;
-        st[u][i] = p * (dpt[u][i] - dl);   // dS^T
+        for (int i = 0; i < 16; ++i) {
+          const int kv = kv0 + u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
+          const bool ok = kv < S && q < S && (!causal || kv <= q);
+          const float p = ok ? fast_exp2(__builtin_fmaf(st[u][i], c2, -lse2)) : 0.f;
+          st[u][i] = p * (dpt[u][i] - dl);   // dS^T
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float p = fast_exp2(__builtin_fmaf(st[u][i], c2, -lse2));
+          st[u][i] = p * (dpt[u][i] - dl);
+        }
       }
     }
 #pragma unroll
@@ -422,14 +445,24 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_kernel(const bf16* __restri
         sm[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(DirectRows<D>::frag(q_lds, u * 32 + lr, s, g), kf[s], sm[u], 0, 0, 0);
         dp[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(DirectRows<D>::frag(do_lds, u * 32 + lr, s, g), vf[s], dp[u], 0, 0, 0);
       }
+      if ((causal && q0 < kvb + wave * 32 + 31) || q0 + 64 > S || kvb + 128 > S) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int ql = u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-        const int qq = q0 + ql;
-        const bool ok = qq < S && kv < S && (!causal || kv <= qq);
-        const float p = ok ? exp2f(sm[u][i] * c2 - lse_lds[ql]) : 0.f;
-        dp[u][i] = p * (dp[u][i] - delta_lds[ql]);   // dS
-        sm[u][i] = p;                                 // P
+        for (int i = 0; i < 16; ++i) {
+          const int ql = u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
+          const int qq = q0 + ql;
+          const bool ok = qq < S && kv < S && (!causal || kv <= qq);
+          const float p = ok ? fast_exp2(__builtin_fmaf(sm[u][i], c2, -lse_lds[ql])) : 0.f;
+          dp[u][i] = p * (dp[u][i] - delta_lds[ql]);   // dS
+          sm[u][i] = p;                                 // P
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int ql = u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
+          const float p = fast_exp2(__builtin_fmaf(sm[u][i], c2, -lse_lds[ql]));
+          dp[u][i] = p * (dp[u][i] - delta_lds[ql]);
+          sm[u][i] = p;
+        }
       }
     }
 #pragma unroll

@@ -37,9 +37,16 @@ template <> struct Vec<bf16> {
     }
   }
   __device__ void pack(const float* f) {
+    // v_cvt_pk_bf16_f32: two floats to packed bfloat16, round to nearest even
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float floatx2_t __attribute__((ext_vector_type(2)));
     uint32_t w[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = float_to_bf16_bits(f[2 * i]) | (float_to_bf16_bits(f[2 * i + 1]) << 16);
+    for (int i = 0; i < 4; ++i) {
+      floatx2_t p2 = {f[2 * i], f[2 * i + 1]};
+      bf16x2_t h = __builtin_convertvector(p2, bf16x2_t);
+      w[i] = *reinterpret_cast<uint32_t*>(&h);
+    }
     raw = make_uint4(w[0], w[1], w[2], w[3]);
   }
 };
