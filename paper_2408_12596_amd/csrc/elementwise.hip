@@ -376,23 +376,26 @@ __global__ void __launch_bounds__(256) norm_bwd_kernel(const T* __restrict__ dy,
 }
 
 // out[j] (+)= sum_c partials[c * stride + j]
-// 256 threads = 32 columns x 8 chunk lanes: a block sums all chunks of its 32
-// columns (128-byte reads), the 8 lanes of a column meet in LDS in a fixed order.
-__global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partials, int nchunks, int64_t stride,
-                                                               float* __restrict__ out, int64_t n, int accumulate) {
+// 1024 threads = 32 columns x 32 chunk lanes: a block sums all chunks of its 32
+// columns (128-byte reads), the 32 lanes of a column meet in LDS in a fixed
+// order.  Columns [0, n0) go to out0, columns [n0, n) to out1 (dgamma | dbeta).
+__global__ void __launch_bounds__(1024) reduce_partials_kernel(const float* __restrict__ partials, int nchunks, int64_t stride,
+                                                                float* __restrict__ out0, float* __restrict__ out1, int64_t n0,
+                                                                int64_t n, int accumulate) {
   const int col = threadIdx.x & 31, cl = threadIdx.x >> 5;
   const int64_t j = (int64_t)blockIdx.x * 32 + col;
   float acc = 0.f;
   if (j < n)
-    for (int c = cl; c < nchunks; c += 8) acc += partials[c * stride + j];
-  __shared__ float red[8][32];
+    for (int c = cl; c < nchunks; c += 32) acc += partials[c * stride + j];
+  __shared__ float red[32][33];
   red[cl][col] = acc;
   __syncthreads();
   if (cl == 0 && j < n) {
     float t = 0.f;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t += red[k][col];
-    out[j] = accumulate ? out[j] + t : t;
+    for (int k = 0; k < 32; ++k) t += red[k][col];
+    float* o = j < n0 ? out0 + j : out1 + (j - n0);
+    *o = accumulate ? *o + t : t;
   }
 }
 
@@ -431,13 +434,11 @@ int layernorm_bwd(hipStream_t s, int dtype, int64_t T_, int H, const void* dy, c
     if (rms) POPLAR_TRY((norm_bwd_launch<T, true>(s, T_, H, (const T*)dy, (const T*)x, (const T*)g, stats, (const T*)dres, (T*)dx, partials, grid)));
     else POPLAR_TRY((norm_bwd_launch<T, false>(s, T_, H, (const T*)dy, (const T*)x, (const T*)g, stats, (const T*)dres, (T*)dx, partials, grid)));
   });
-  // dgamma = partials[:, 0, :], dbeta = partials[:, 1, :]
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((int)cdiv(H, 32)), dim3(256), 0, s, partials, grid, (int64_t)2 * H, dg, (int64_t)H, accumulate);
+  // dgamma = partials[:, 0, :], dbeta = partials[:, 1, :]: one launch covers both
+  const int64_t ncols = rms ? H : 2 * (int64_t)H;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((int)cdiv(ncols, 32)), dim3(1024), 0, s, partials, grid, (int64_t)2 * H, dg, db, (int64_t)H,
+                     ncols, accumulate);
   POPLAR_LAUNCH_CHECK();
-  if (!rms) {
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((int)cdiv(H, 32)), dim3(256), 0, s, partials + H, grid, (int64_t)2 * H, db, (int64_t)H, accumulate);
-    POPLAR_LAUNCH_CHECK();
-  }
   return POPLAR_OK;
 }
 
@@ -489,7 +490,7 @@ int colsum(hipStream_t s, int dtype, int64_t T_, int64_t N, const void* x, int64
   if ((int64_t)chunks * N > partials_elems) return poplar_fail(POPLAR_ERR_OOM, "colsum scratch too small");
   DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(colsum_kernel<T>, dim3(strips, chunks), dim3(256), 0, s, (const T*)x, ldx, T_, N, rpc, partials));
   POPLAR_LAUNCH_CHECK();
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((int)cdiv(N, 32)), dim3(256), 0, s, partials, chunks, N, out, N, accumulate);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((int)cdiv(N, 32)), dim3(1024), 0, s, partials, chunks, N, out, out, N, N, accumulate);
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }

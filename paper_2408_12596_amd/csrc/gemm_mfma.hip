@@ -45,6 +45,7 @@ template <int R>
 struct DirectTile {
   static constexpr int N = R / 32;
   static constexpr int LDS_BYTES = R * 128;
+  static constexpr int FRAG_READS = 1;   // LDS instructions per fragment
   uint4 v[N];
   __device__ void load(const bf16* __restrict__ p, int64_t ld, int64_t r0, int64_t rlim, int64_t k0, int64_t kend) {
     const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
@@ -81,6 +82,7 @@ struct TrTile {
   static constexpr int N = R / 32;              // 16-byte chunks per thread
   static constexpr int STRIDE = R * 2 + 64;     // bytes per k-row
   static constexpr int LDS_BYTES = 64 * STRIDE;
+  static constexpr int FRAG_READS = 2;
   uint4 v[N];
   __device__ void load(const bf16* __restrict__ p, int64_t ld, int64_t r0, int64_t rext, int64_t k0, int64_t kend) {
 #pragma unroll
@@ -173,17 +175,35 @@ __global__ void __launch_bounds__(256, (TM * TN > 4 && LAYOUT == GEMM_TN ? 1 : 2
       ta.load(p.A, p.lda, m0, ra_lim, k0 + BK, ka_end);
       tb.load(p.B, p.ldb, n0, rb_lim, k0 + BK, kb_end);
     }
+    // fragments of k-slice kk+1 are fetched from LDS while the MFMAs of slice kk run
+    bf16x8 fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = TileA::frag(lds_a, wm + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = TileB::frag(lds_b, wn + j * 32, 0, lane);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[TM], fb[TN];
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < BK / 16) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = TileA::frag(lds_a, wm + i * 32, kk, lane);
+        for (int i = 0; i < TM; ++i) fa[nxt][i] = TileA::frag(lds_a, wm + i * 32, kk + 1, lane);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = TileB::frag(lds_b, wn + j * 32, kk, lane);
+        for (int j = 0; j < TN; ++j) fb[nxt][j] = TileB::frag(lds_b, wn + j * 32, kk + 1, lane);
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+      // ask the scheduler to keep that overlap: one LDS read in front of each of the first MFMAs of the slice
+      if (kk + 1 < BK / 16) {
+#pragma unroll
+        for (int x = 0; x < TileA::FRAG_READS * TM + TileB::FRAG_READS * TN; ++x) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          if (x < TM * TN) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        if (TileA::FRAG_READS * TM + TileB::FRAG_READS * TN < TM * TN)
+          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TileA::FRAG_READS * TM + TileB::FRAG_READS * TN), 0);
+      }
     }
     __syncthreads();
   }
