@@ -80,6 +80,7 @@ struct GemmArgs {
 };
 int gemm_simple(hipStream_t s, int dtype, const GemmArgs& a);
 int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a);
+int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a);   // POPLAR_ERR_UNIMPLEMENTED when the shape is outside its preconditions
 int gemm(hipStream_t s, int dtype, const GemmArgs& a);
 
 // attention on the fused qkv activation [B*S, 3H]; o [B*S, H]; lse float [B, nh, S]

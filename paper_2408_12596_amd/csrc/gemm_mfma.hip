@@ -37,7 +37,9 @@ struct MfmaGemmParams {
 #define BK 64
 
 __device__ inline int64_t round_up_dev(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
-__device__ inline int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+// 16-byte chunk c of row r sits at chunk position c ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 1): sixteen consecutive rows
+// reading the same logical chunk then touch sixteen different 16-byte slots of the 256-byte bank line
+__device__ inline int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ ((row & 7) ^ ((row >> 3) & 1))) << 4); }
 
 // ---- operand tile, reduction index contiguous in memory: elem(r, k) = p[(r0+r)*ld + k] ----
 // LDS image: R rows of 64 k-values (128 B), 16-byte chunks XOR-swizzled with the row.

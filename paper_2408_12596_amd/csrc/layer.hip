@@ -4,7 +4,11 @@
 #include "layer_plan.h"
 
 int gemm(hipStream_t s, int dtype, const GemmArgs& a) {
-  if (dtype == POPLAR_BF16) return gemm_bf16_mfma(s, a);
+  if (dtype == POPLAR_BF16) {
+    // the direct-to-LDS kernel takes every shape inside its preconditions, the register-staged one the rest (K tails)
+    const int r = gemm_bf16_dtl(s, a);
+    return r == POPLAR_ERR_UNIMPLEMENTED ? gemm_bf16_mfma(s, a) : r;
+  }
   return gemm_simple(s, dtype, a);
 }
 
