@@ -4,19 +4,28 @@
 //
 // Data: the fused projection output qkv [B*S, 3H] (q | k | v thirds, head h in
 // columns h*D..(h+1)*D of each), o and dout [B*S, H], lse and delta float
-// [B, nh, S].  D is 64 or 128.
+// [B, nh, S].  D is 64 or 128.  lse is kept in the base-2 domain:
+// lse2 = log2(sum_j exp(s_ij / sqrt(D))).
 //
 // MFMA conventions used below (32x32 tile, K = 16 per instruction):
 //   A fragment: lane holds row  (lane % 32), k-slots (lane / 32) * 8 + 0..7
 //   B fragment: lane holds col  (lane % 32), the same k-slots
 //   C tile    : lane holds col  (lane % 32); register i is row (i/4)*8 + (lane/32)*4 + i%4
 // A probability tile therefore leaves the softmax already in B-fragment form
-// if the k-slot e of lane half g inside a 16-row chunk is read as row
-// (e/4)*8 + g*4 + e%4.  The matching A operand (V^T, K^T, Q^T, dO^T) is built
-// when its tile is copied to LDS: a thread loads the 8 rows 16j + 4g +
-// {0,1,2,3,8,9,10,11} (16 bytes each), transposes them in registers and writes
-// one 16-byte chunk per column, so the fragment read is a single 16-byte LDS
-// load and the probabilities never touch LDS.
+// if k-slot e of lane half g inside a 16-row chunk is read as row
+// (e/4)*8 + g*4 + e%4: the probabilities never touch LDS.
+//
+// Tiles (64 rows of K, V, Q or dO, D values each) go from global memory to LDS
+// with direct loads (buffer_load ... lds, 16 bytes per lane, lane L of a
+// wavefront landing at base + 16 L), two stages deep, one barrier per tile.
+// The LDS image keeps the rows as they are, 16-byte chunks XOR-swizzled with
+// the row, and serves both operand forms:
+//   * rows as the M index (K for S^T = K Q^T, V for dP^T, Q and dO in dK/dV):
+//     one 16-byte read per fragment;
+//   * rows as the reduction index (V^T for O^T += V^T P^T, K^T for dQ, Q^T and
+//     dO^T for dK/dV): two transposing reads (ds_read_b64_tr_b16) per fragment,
+//     taken at rows 16j + 4g + {0..3} and 16j + 8 + 4g + {0..3}, which is exactly
+//     the k-slot order of the probability fragments.
 //
 // Forward and dQ work on S^T = K Q^T (lane = query), which keeps the running
 // max / sum / rescale of a query inside one lane (plus one exchange between the
@@ -24,15 +33,17 @@
 #include "device_utils.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 #define LOG2E 1.4426950408889634f
-#define LN2 0.6931471805599453f
+#define FA_OOB 0xfffffff0u
 
 __device__ inline bf16x8 as_frag(uint4 v) { return *reinterpret_cast<bf16x8*>(&v); }
 
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
 // two floats to packed bfloat16 (round to nearest even) with one v_cvt_pk_bf16_f32
 __device__ inline uint32_t pack_bf16(float a, float b) {
   floatx2 f = {a, b};
@@ -48,73 +59,48 @@ __device__ inline bf16x8 regs_to_frag(const floatx16& c, int s) {
   return as_frag(v);
 }
 
-// ---- 64-row tile with D contiguous columns, copied as it is ("direct") -------
+// one 16-byte-per-lane load of a wavefront straight into the KiB of LDS at dst (lane L lands at dst + 16 L);
+// offsets at or past the resource's size deliver zeros
+__device__ inline void fa_load_kib(__amdgpu_buffer_rsrc_t rsrc, char* dst, uint32_t lane_byte_offset) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)dst, 16, lane_byte_offset, 0, 0, 0);
+}
+
+// ---- LDS image of 64 rows x D values ----------------------------------------------------------
 template <int D>
-struct DirectRows {
-  static constexpr int NC = 64 * D / 8 / 256;  // 16-byte chunks per thread
-  static constexpr int ROWB = D * 2;
-  uint4 v[NC];
-  // rows r0 .. r0+63 of a [*, ld] matrix starting at column 0 of `p`; rows >= rlim read as zero
-  __device__ void load(const bf16* __restrict__ p, int64_t ld, int r0, int rlim) {
-#pragma unroll
-    for (int i = 0; i < NC; ++i) {
-      const int idx = threadIdx.x + i * 256;
-      const int row = idx / (D / 8), c = idx % (D / 8);
-      if (r0 + row < rlim) v[i] = *reinterpret_cast<const uint4*>(p + (int64_t)(r0 + row) * ld + c * 8);
-      else v[i] = make_uint4(0, 0, 0, 0);
-    }
+struct Rows64 {
+  static constexpr int ROWB = D * 2;            // 128 or 256 bytes
+  static constexpr int CPR = D / 8;             // 16-byte chunks per row
+  static constexpr int RPL = 1024 / ROWB;       // rows per wave load
+  static constexpr int BYTES = 64 * ROWB;
+  static constexpr int LOADS = BYTES / 1024;    // wave loads per tile: 8 or 16
+  static constexpr int PER_WAVE = LOADS / 4;    // four wavefronts share a tile
+
+  // byte offset, relative to row 0 of the tile, of the 16 bytes that belong at LDS position idx*1024 + lane*16
+  __device__ static uint32_t lane_offset(int idx, int lane, int64_t ld) {
+    const int row = idx * RPL + lane / CPR;
+    const int c = (lane % CPR) ^ (row & 7);
+    return (uint32_t)(((int64_t)row * ld + c * 8) * 2);
   }
-  __device__ void store(char* lds) const {
-#pragma unroll
-    for (int i = 0; i < NC; ++i) {
-      const int idx = threadIdx.x + i * 256;
-      const int row = idx / (D / 8), c = idx % (D / 8);
-      *reinterpret_cast<uint4*>(lds + row * ROWB + ((c ^ (row & 7)) << 4)) = v[i];
-    }
-  }
-  // A fragment: row `row` of the tile, k-slice s (16 columns), lane half g
+  // A fragment, rows as M index: row `row` of the tile, k-slice s (16 columns), lane half g
   __device__ static bf16x8 frag(const char* lds, int row, int s, int g) {
     return *reinterpret_cast<const bf16x8*>(lds + row * ROWB + (((2 * s + g) ^ (row & 7)) << 4));
   }
-};
-
-// ---- 64-row tile copied transposed, rows permuted into k-slot order -----------
-// LDS image: D rows (one per column of the source) of 64 values = 128 bytes.
-// Threads tid0 .. tid0+D-1 each own one 8x8 block.
-template <int D>
-struct PermutedTranspose {
-  uint4 v[8];
-  __device__ static bool mine(int tid0) { return (int)threadIdx.x >= tid0 && (int)threadIdx.x < tid0 + D; }
-  __device__ void load(const bf16* __restrict__ p, int64_t ld, int r0, int rlim, int tid0) {
-    const int bid = threadIdx.x - tid0;
-    const int jg = bid & 7, cx = bid >> 3;   // 8 lanes share a column chunk: their LDS writes fill one 128-byte row
-    const int rbase = r0 + 16 * (jg >> 1) + 4 * (jg & 1);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = rbase + (i & 3) + (i >> 2) * 8;
-      if (r < rlim) v[i] = *reinterpret_cast<const uint4*>(p + (int64_t)r * ld + cx * 8);
-      else v[i] = make_uint4(0, 0, 0, 0);
-    }
+  // per-lane base of the transposed fragments of column tile ct (32 columns)
+  __device__ static int tr_base(int ct, int lane) {
+    const int l16 = lane & 15, gi = (lane >> 4) & 1, g = lane >> 5;
+    const int row = 4 * g + (l16 >> 2);                       // row inside the 16-row chunk (first read)
+    const int chunk = ct * 4 + gi * 2 + ((l16 & 3) >> 1);     // logical 16-byte chunk of the lane's 4 values
+    return row * ROWB + ((chunk ^ (row & 7)) << 4) + (l16 & 1) * 8;
   }
-  __device__ void store(char* lds, int tid0) const {
-    const int bid = threadIdx.x - tid0;
-    const int jg = bid & 7, cx = bid >> 3;
-    const uint32_t* w = reinterpret_cast<const uint32_t*>(&v[0]);  // w[row * 4 + word]
-#pragma unroll
-    for (int x = 0; x < 8; ++x) {
-      uint32_t o[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t lo = w[(2 * j) * 4 + (x >> 1)], hi = w[(2 * j + 1) * 4 + (x >> 1)];
-        o[j] = (x & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
-      }
-      const int row = cx * 8 + x;
-      *reinterpret_cast<uint4*>(lds + row * 128 + ((jg ^ (row & 7)) << 4)) = make_uint4(o[0], o[1], o[2], o[3]);
-    }
-  }
-  // A fragment: row `row` (a source column), 16-row chunk j of the source, lane half g
-  __device__ static bf16x8 frag(const char* lds, int row, int j, int g) {
-    return *reinterpret_cast<const bf16x8*>(lds + row * 128 + (((2 * j + g) ^ (row & 7)) << 4));
+  // A fragment, rows as reduction index: 16-row chunk j, k-slots in probability order
+  __device__ static bf16x8 frag_tr(const char* lds, int base, int j) {
+    typedef __attribute__((address_space(3))) bf16x4* lds_ptr;
+    const char* q = lds + base + j * 16 * ROWB;
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(q));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(q + 8 * ROWB));
+    bf16x8 f;
+    f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3]; f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
+    return f;
   }
 };
 
@@ -150,14 +136,20 @@ __device__ inline void zero_acc(floatx16& a) {
   for (int i = 0; i < 16; ++i) a[i] = 0.f;
 }
 
+// bytes of a [rows, ld] bf16 matrix from `row0` to its end, clamped to the 32-bit range of a buffer resource
+__device__ inline uint32_t records_from(int64_t rows_total, int64_t row0, int64_t ld, int64_t last_cols) {
+  const int64_t bytes = ((rows_total - row0 - 1) * ld + last_cols) * 2;
+  return bytes < (int64_t)FA_OOB ? (uint32_t)bytes : FA_OOB;
+}
+
 // =============================================================================
 // forward
 // =============================================================================
 template <int D>
 __global__ void __launch_bounds__(256) flash_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
-                                                         int S, int nh, int causal, float scale) {
-  __shared__ __attribute__((aligned(16))) char k_lds[64 * D * 2];
-  __shared__ __attribute__((aligned(16))) char vt_lds[D * 128];
+                                                         int B, int S, int nh, int causal, float scale) {
+  typedef Rows64<D> Img;
+  __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * Img::BYTES];   // [stage][K | V]
   const int H = nh * D;
   const int64_t ld = 3 * (int64_t)H;
   const int qtiles = (S + 127) / 128;
@@ -168,32 +160,43 @@ __global__ void __launch_bounds__(256) flash_fwd_kernel(const bf16* __restrict__
   const int lr = lane & 31, g = lane >> 5;
   const int q0 = qt * 128;
   const int q = q0 + wave * 32 + lr;
-  const bf16* base = qkv + (int64_t)b * S * ld + h * D;
-  const bf16* kp = base + H;
-  const bf16* vp = base + 2 * H;
+  const bf16* base = qkv + (int64_t)b * S * ld + h * D;   // row 0 of this sequence, q columns of head h
+  // K and V tiles of this head: rows past the sequence are the next sequence's (finite, masked) or out of range (zero)
+  const uint32_t recs = records_from((int64_t)B * S, (int64_t)b * S, ld, D);
+  const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc((void*)(base + H), 0, recs, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void*)(base + 2 * H), 0, recs, 0x00020000);
+  uint32_t off[Img::PER_WAVE];
+#pragma unroll
+  for (int i = 0; i < Img::PER_WAVE; ++i) off[i] = Img::lane_offset(wave + 4 * i, lane, ld);
+  const uint32_t tile_step = (uint32_t)(64 * ld * 2);
+  auto issue = [&](char* st, uint32_t tile_off) {
+#pragma unroll
+    for (int i = 0; i < Img::PER_WAVE; ++i) {
+      fa_load_kib(rk, st + (wave + 4 * i) * 1024, off[i] + tile_off);
+      fa_load_kib(rv, st + Img::BYTES + (wave + 4 * i) * 1024, off[i] + tile_off);
+    }
+  };
 
   bf16x8 qf[D / 16];
   load_row_frags<D>(qf, base, ld, q, S, g);
   floatx16 oacc[D / 32];
+  int trb[D / 32];
 #pragma unroll
-  for (int ct = 0; ct < D / 32; ++ct) zero_acc(oacc[ct]);
+  for (int ct = 0; ct < D / 32; ++ct) { zero_acc(oacc[ct]); trb[ct] = Img::tr_base(ct, lane); }
   float m_run = -INFINITY, l_run = 0.f;
   const float c2 = scale * LOG2E;
   const int kv_end = causal ? min(S, q0 + 128) : S;
+  const int qw0 = q0 + wave * 32;
 
-  DirectRows<D> kt;
-  PermutedTranspose<D> vt;
-  const bool vmine = PermutedTranspose<D>::mine(0);
-  kt.load(kp, ld, 0, S);
-  if (vmine) vt.load(vp, ld, 0, S, 0);
-  for (int kv0 = 0; kv0 < kv_end; kv0 += 64) {
-    kt.store(k_lds);
-    if (vmine) vt.store(vt_lds, 0);
+  issue(lds, 0);
+  int par = 0;
+  for (int kv0 = 0; kv0 < kv_end; kv0 += 64, par ^= 1) {
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's part of the tile has landed
     __syncthreads();
-    if (kv0 + 64 < kv_end) {
-      kt.load(kp, ld, kv0 + 64, S);
-      if (vmine) vt.load(vp, ld, kv0 + 64, S, 0);
-    }
+    char* cur = lds + par * 2 * Img::BYTES;
+    if (kv0 + 64 < kv_end) issue(lds + (par ^ 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + 1) * tile_step);
+    const char* k_lds = cur;
+    const char* v_lds = cur + Img::BYTES;
     // S^T tiles: rows = keys kv0 + u*32 + .., cols = this wave's queries
     floatx16 st[2];
 #pragma unroll
@@ -201,10 +204,9 @@ __global__ void __launch_bounds__(256) flash_fwd_kernel(const bf16* __restrict__
       zero_acc(st[u]);
 #pragma unroll
       for (int s = 0; s < D / 16; ++s)
-        st[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(DirectRows<D>::frag(k_lds, u * 32 + lr, s, g), qf[s], st[u], 0, 0, 0);
+        st[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(k_lds, u * 32 + lr, s, g), qf[s], st[u], 0, 0, 0);
     }
     // only tiles that touch the diagonal of this wave's queries or the end of the sequence need the mask
-    const int qw0 = q0 + wave * 32;
     if ((causal && kv0 + 63 > qw0) || kv0 + 64 > S) {
 #pragma unroll
       for (int u = 0; u < 2; ++u)
@@ -244,14 +246,13 @@ __global__ void __launch_bounds__(256) flash_fwd_kernel(const bf16* __restrict__
       const bf16x8 pb = regs_to_frag(st[j >> 1], j & 1);
 #pragma unroll
       for (int ct = 0; ct < D / 32; ++ct)
-        oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(PermutedTranspose<D>::frag(vt_lds, ct * 32 + lr, j, g), pb, oacc[ct], 0, 0, 0);
+        oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag_tr(v_lds, trb[ct], j), pb, oacc[ct], 0, 0, 0);
     }
-    __syncthreads();
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   store_rows_from_transposed<D>(o + (int64_t)b * S * H + h * D, H, q, S, g, oacc, inv);
-  if (g == 0 && q < S) lse[((int64_t)b * nh + h) * S + q] = (m_run * c2 + log2f(l_tot)) * LN2;
+  if (g == 0 && q < S) lse[((int64_t)b * nh + h) * S + q] = m_run * c2 + log2f(l_tot);
 }
 
 // =============================================================================
@@ -289,10 +290,9 @@ __global__ void __launch_bounds__(256) flash_delta_kernel(const bf16* __restrict
 template <int D>
 __global__ void __launch_bounds__(256) flash_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
-                                                            bf16* __restrict__ dqkv, int S, int nh, int causal, float scale) {
-  __shared__ __attribute__((aligned(16))) char k_lds[64 * D * 2];
-  __shared__ __attribute__((aligned(16))) char v_lds[64 * D * 2];
-  __shared__ __attribute__((aligned(16))) char kt_lds[D * 128];
+                                                            bf16* __restrict__ dqkv, int B, int S, int nh, int causal, float scale) {
+  typedef Rows64<D> Img;
+  __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * Img::BYTES];   // [stage][K | V]
   const int H = nh * D;
   const int64_t ld = 3 * (int64_t)H;
   const int qtiles = (S + 127) / 128;
@@ -304,37 +304,43 @@ __global__ void __launch_bounds__(256) flash_bwd_dq_kernel(const bf16* __restric
   const int q0 = qt * 128;
   const int q = q0 + wave * 32 + lr;
   const bf16* base = qkv + (int64_t)b * S * ld + h * D;
-  const bf16* kp = base + H;
-  const bf16* vp = base + 2 * H;
+  const uint32_t recs = records_from((int64_t)B * S, (int64_t)b * S, ld, D);
+  const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc((void*)(base + H), 0, recs, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void*)(base + 2 * H), 0, recs, 0x00020000);
+  uint32_t off[Img::PER_WAVE];
+#pragma unroll
+  for (int i = 0; i < Img::PER_WAVE; ++i) off[i] = Img::lane_offset(wave + 4 * i, lane, ld);
+  const uint32_t tile_step = (uint32_t)(64 * ld * 2);
+  auto issue = [&](char* st, uint32_t tile_off) {
+#pragma unroll
+    for (int i = 0; i < Img::PER_WAVE; ++i) {
+      fa_load_kib(rk, st + (wave + 4 * i) * 1024, off[i] + tile_off);
+      fa_load_kib(rv, st + Img::BYTES + (wave + 4 * i) * 1024, off[i] + tile_off);
+    }
+  };
 
   bf16x8 qf[D / 16], dof[D / 16];
   load_row_frags<D>(qf, base, ld, q, S, g);
   load_row_frags<D>(dof, dout + (int64_t)b * S * H + h * D, H, q, S, g);
   const float c2 = scale * LOG2E;
   const int64_t stat = ((int64_t)b * nh + h) * S + q;
-  const float lse2 = q < S ? lse[stat] * LOG2E : 0.f;
+  const float lse2 = q < S ? lse[stat] : 0.f;
   const float dl = q < S ? delta[stat] : 0.f;
   floatx16 dq[D / 32];
+  int trb[D / 32];
 #pragma unroll
-  for (int ct = 0; ct < D / 32; ++ct) zero_acc(dq[ct]);
+  for (int ct = 0; ct < D / 32; ++ct) { zero_acc(dq[ct]); trb[ct] = Img::tr_base(ct, lane); }
   const int kv_end = causal ? min(S, q0 + 128) : S;
 
-  DirectRows<D> kt, vt;
-  PermutedTranspose<D> ktt;
-  const bool tmine = PermutedTranspose<D>::mine(0);
-  kt.load(kp, ld, 0, S);
-  vt.load(vp, ld, 0, S);
-  if (tmine) ktt.load(kp, ld, 0, S, 0);
-  for (int kv0 = 0; kv0 < kv_end; kv0 += 64) {
-    kt.store(k_lds);
-    vt.store(v_lds);
-    if (tmine) ktt.store(kt_lds, 0);
+  issue(lds, 0);
+  int par = 0;
+  for (int kv0 = 0; kv0 < kv_end; kv0 += 64, par ^= 1) {
+    __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();
-    if (kv0 + 64 < kv_end) {
-      kt.load(kp, ld, kv0 + 64, S);
-      vt.load(vp, ld, kv0 + 64, S);
-      if (tmine) ktt.load(kp, ld, kv0 + 64, S, 0);
-    }
+    char* cur = lds + par * 2 * Img::BYTES;
+    if (kv0 + 64 < kv_end) issue(lds + (par ^ 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + 1) * tile_step);
+    const char* k_lds = cur;
+    const char* v_lds = cur + Img::BYTES;
     floatx16 st[2], dpt[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -342,8 +348,8 @@ __global__ void __launch_bounds__(256) flash_bwd_dq_kernel(const bf16* __restric
       zero_acc(dpt[u]);
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        st[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(DirectRows<D>::frag(k_lds, u * 32 + lr, s, g), qf[s], st[u], 0, 0, 0);
-        dpt[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(DirectRows<D>::frag(v_lds, u * 32 + lr, s, g), dof[s], dpt[u], 0, 0, 0);
+        st[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(k_lds, u * 32 + lr, s, g), qf[s], st[u], 0, 0, 0);
+        dpt[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(v_lds, u * 32 + lr, s, g), dof[s], dpt[u], 0, 0, 0);
       }
       if ((causal && kv0 + 63 > q0 + wave * 32) || kv0 + 64 > S || q0 + 128 > S) {
 #pragma unroll
@@ -361,14 +367,14 @@ __global__ void __launch_bounds__(256) flash_bwd_dq_kernel(const bf16* __restric
         }
       }
     }
+    // dQ^T += K^T dS^T
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const bf16x8 dsb = regs_to_frag(st[j >> 1], j & 1);
 #pragma unroll
       for (int ct = 0; ct < D / 32; ++ct)
-        dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(PermutedTranspose<D>::frag(kt_lds, ct * 32 + lr, j, g), dsb, dq[ct], 0, 0, 0);
+        dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag_tr(k_lds, trb[ct], j), dsb, dq[ct], 0, 0, 0);
     }
-    __syncthreads();
   }
   store_rows_from_transposed<D>(dqkv + (int64_t)b * S * ld + h * D, ld, q, S, g, dq, scale);
 }
@@ -379,13 +385,10 @@ __global__ void __launch_bounds__(256) flash_bwd_dq_kernel(const bf16* __restric
 template <int D>
 __global__ void __launch_bounds__(256) flash_bwd_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
                                                              const float* __restrict__ lse, const float* __restrict__ delta,
-                                                             bf16* __restrict__ dqkv, int S, int nh, int causal, float scale) {
-  __shared__ __attribute__((aligned(16))) char q_lds[64 * D * 2];
-  __shared__ __attribute__((aligned(16))) char do_lds[64 * D * 2];
-  __shared__ __attribute__((aligned(16))) char qt_lds[D * 128];
-  __shared__ __attribute__((aligned(16))) char dot_lds[D * 128];
-  __shared__ __attribute__((aligned(16))) float lse_lds[64];
-  __shared__ __attribute__((aligned(16))) float delta_lds[64];
+                                                             bf16* __restrict__ dqkv, int B, int S, int nh, int causal, float scale) {
+  typedef Rows64<D> Img;
+  constexpr int STAGE = 2 * Img::BYTES + 2048;   // Q | dO | lse2 (first 256 bytes of a KiB) | delta (first 256 bytes of a KiB)
+  __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE];
   const int H = nh * D;
   const int64_t ld = 3 * (int64_t)H;
   const int ktiles = (S + 127) / 128;
@@ -400,41 +403,52 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_kernel(const bf16* __restri
   const bf16* dop = dout + (int64_t)b * S * H + h * D;
   const float* lsep = lse + ((int64_t)b * nh + h) * S;
   const float* delp = delta + ((int64_t)b * nh + h) * S;
+  const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc((void*)qp, 0, records_from((int64_t)B * S, (int64_t)b * S, ld, D), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rdo = __builtin_amdgcn_make_buffer_rsrc((void*)dop, 0, records_from((int64_t)B * S, (int64_t)b * S, H, D), 0x00020000);
+  // statistics of this (sequence, head): S floats each; queries past S are out of range and read as zero
+  const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc((void*)lsep, 0, (uint32_t)(S * 4), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc((void*)delp, 0, (uint32_t)(S * 4), 0x00020000);
+  uint32_t offq[Img::PER_WAVE], offd[Img::PER_WAVE];
+#pragma unroll
+  for (int i = 0; i < Img::PER_WAVE; ++i) {
+    offq[i] = Img::lane_offset(wave + 4 * i, lane, ld);
+    offd[i] = Img::lane_offset(wave + 4 * i, lane, H);
+  }
+  const uint32_t stepq = (uint32_t)(64 * ld * 2), stepd = (uint32_t)(64 * (int64_t)H * 2);
+  auto issue = [&](char* st, int q0) {
+    const uint32_t t = (uint32_t)(q0 / 64);
+#pragma unroll
+    for (int i = 0; i < Img::PER_WAVE; ++i) {
+      fa_load_kib(rq, st + (wave + 4 * i) * 1024, offq[i] + t * stepq);
+      fa_load_kib(rdo, st + Img::BYTES + (wave + 4 * i) * 1024, offd[i] + t * stepd);
+    }
+    // 64 floats = 16 lanes x 16 bytes; the other lanes are parked out of range and write zeros behind them
+    const uint32_t so = lane < 16 ? (uint32_t)(q0 * 4 + lane * 16) : FA_OOB;
+    if (wave == 0) fa_load_kib(rl, st + 2 * Img::BYTES, so);
+    if (wave == 1) fa_load_kib(rd, st + 2 * Img::BYTES + 1024, so);
+  };
 
   bf16x8 kf[D / 16], vf[D / 16];
   load_row_frags<D>(kf, qp + H, ld, kv, S, g);
   load_row_frags<D>(vf, qp + 2 * H, ld, kv, S, g);
   floatx16 dk[D / 32], dv[D / 32];
+  int trb[D / 32];
 #pragma unroll
-  for (int ct = 0; ct < D / 32; ++ct) { zero_acc(dk[ct]); zero_acc(dv[ct]); }
+  for (int ct = 0; ct < D / 32; ++ct) { zero_acc(dk[ct]); zero_acc(dv[ct]); trb[ct] = Img::tr_base(ct, lane); }
   const float c2 = scale * LOG2E;
   const int q_begin = causal ? (kvb / 64) * 64 : 0;
 
-  DirectRows<D> qd, dod;
-  PermutedTranspose<D> qtt, dott;
-  constexpr int T1 = D == 64 ? 128 : 128;  // first thread of the dO^T loaders
-  const bool qmine = PermutedTranspose<D>::mine(0), dmine = PermutedTranspose<D>::mine(T1);
-  float lse_r = 0.f, del_r = 0.f;
-  auto load_tile = [&](int q0) {
-    qd.load(qp, ld, q0, S);
-    dod.load(dop, H, q0, S);
-    if (qmine) qtt.load(qp, ld, q0, S, 0);
-    if (dmine) dott.load(dop, H, q0, S, T1);
-    if (threadIdx.x < 64) {
-      const int qq = q0 + threadIdx.x;
-      lse_r = qq < S ? lsep[qq] * LOG2E : 0.f;
-      del_r = qq < S ? delp[qq] : 0.f;
-    }
-  };
-  load_tile(q_begin);
-  for (int q0 = q_begin; q0 < S; q0 += 64) {
-    qd.store(q_lds);
-    dod.store(do_lds);
-    if (qmine) qtt.store(qt_lds, 0);
-    if (dmine) dott.store(dot_lds, T1);
-    if (threadIdx.x < 64) { lse_lds[threadIdx.x] = lse_r; delta_lds[threadIdx.x] = del_r; }
+  issue(lds, q_begin);
+  int par = 0;
+  for (int q0 = q_begin; q0 < S; q0 += 64, par ^= 1) {
+    __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();
-    if (q0 + 64 < S) load_tile(q0 + 64);
+    char* cur = lds + par * STAGE;
+    if (q0 + 64 < S) issue(lds + (par ^ 1) * STAGE, q0 + 64);
+    const char* q_lds = cur;
+    const char* do_lds = cur + Img::BYTES;
+    const float* lse_lds = reinterpret_cast<const float*>(cur + 2 * Img::BYTES);
+    const float* delta_lds = reinterpret_cast<const float*>(cur + 2 * Img::BYTES + 1024);
     floatx16 sm[2], dp[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -442,8 +456,8 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_kernel(const bf16* __restri
       zero_acc(dp[u]);
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        sm[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(DirectRows<D>::frag(q_lds, u * 32 + lr, s, g), kf[s], sm[u], 0, 0, 0);
-        dp[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(DirectRows<D>::frag(do_lds, u * 32 + lr, s, g), vf[s], dp[u], 0, 0, 0);
+        sm[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(q_lds, u * 32 + lr, s, g), kf[s], sm[u], 0, 0, 0);
+        dp[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(do_lds, u * 32 + lr, s, g), vf[s], dp[u], 0, 0, 0);
       }
       if ((causal && q0 < kvb + wave * 32 + 31) || q0 + 64 > S || kvb + 128 > S) {
 #pragma unroll
@@ -465,17 +479,17 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_kernel(const bf16* __restri
         }
       }
     }
+    // dV^T += dO^T P,  dK^T += Q^T dS
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const bf16x8 pb = regs_to_frag(sm[j >> 1], j & 1);
       const bf16x8 dsb = regs_to_frag(dp[j >> 1], j & 1);
 #pragma unroll
       for (int ct = 0; ct < D / 32; ++ct) {
-        dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(PermutedTranspose<D>::frag(dot_lds, ct * 32 + lr, j, g), pb, dv[ct], 0, 0, 0);
-        dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(PermutedTranspose<D>::frag(qt_lds, ct * 32 + lr, j, g), dsb, dk[ct], 0, 0, 0);
+        dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag_tr(do_lds, trb[ct], j), pb, dv[ct], 0, 0, 0);
+        dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag_tr(q_lds, trb[ct], j), dsb, dk[ct], 0, 0, 0);
       }
     }
-    __syncthreads();
   }
   bf16* outp = dqkv + (int64_t)b * S * ld + h * D;
   store_rows_from_transposed<D>(outp + H, ld, kv, S, g, dk, scale);
@@ -489,6 +503,8 @@ static int check_flash(int B, int S, int nh, int d, const void* qkv) {
   if (d != 64 && d != 128) return poplar_fail(POPLAR_ERR_INVALID, "bf16 attention needs head_dim 64 or 128, got %d", d);
   if ((uintptr_t)qkv & 15) return poplar_fail(POPLAR_ERR_INVALID, "qkv must be 16-byte aligned");
   if ((int64_t)B * nh * ((S + 127) / 128) > 0x7fffffff) return poplar_fail(POPLAR_ERR_INVALID, "attention grid too large");
+  // 32-bit buffer offsets: one sequence of the fused projection must stay well below 4 GiB
+  if (((int64_t)S + 128) * 3 * nh * d * 2 >= (int64_t)0xf0000000) return poplar_fail(POPLAR_ERR_INVALID, "sequence too long for the attention kernels");
   return POPLAR_OK;
 }
 
@@ -497,8 +513,8 @@ int attn_fwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const
   if (B == 0 || S == 0) return POPLAR_OK;
   const float scale = 1.0f / sqrtf((float)d);
   dim3 grid((unsigned)((int64_t)B * nh * ((S + 127) / 128)));
-  if (d == 64) hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, S, nh, causal, scale);
-  else hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, S, nh, causal, scale);
+  if (d == 64) hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, B, S, nh, causal, scale);
+  else hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, B, S, nh, causal, scale);
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }
@@ -514,11 +530,11 @@ int attn_bwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const
   POPLAR_LAUNCH_CHECK();
   dim3 grid((unsigned)((int64_t)B * nh * ((S + 127) / 128)));
   if (d == 64) {
-    hipLaunchKernelGGL(flash_bwd_dkv_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, S, nh, causal, scale);
-    hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, S, nh, causal, scale);
+    hipLaunchKernelGGL(flash_bwd_dkv_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
+    hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
   } else {
-    hipLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, S, nh, causal, scale);
-    hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, S, nh, causal, scale);
+    hipLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
+    hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
   }
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
