@@ -77,6 +77,7 @@ struct GemmArgs {
   const void* residual;   // lowp [M,N] (ldc) or null, added after activation
   int act;                // ACT_GELU: aux <- pre-activation, C <- gelu;  ACT_GELU_BWD: C <- acc * gelu'(aux)
   void* aux; int64_t ldaux;
+  int a_k_pad_zero;       // NN only: A's rows hold zeros from column K up to K rounded up to 64 (lda covers them)
 };
 int gemm_simple(hipStream_t s, int dtype, const GemmArgs& a);
 int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a);

@@ -339,7 +339,10 @@ static void launch_dtl(hipStream_t s, int layout, dim3 grid, const DtlGemmParams
 // shape is outside this kernel's preconditions; the caller then uses the register-staged kernel.
 int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) {
   if (a.layout < GEMM_NT || a.layout > GEMM_TN) return POPLAR_ERR_UNIMPLEMENTED;
-  if (a.layout != GEMM_TN && a.K % DTL_BK) return POPLAR_ERR_UNIMPLEMENTED;
+  // a K tail is fine when every operand reads zeros there: k-strided operands run out of range, a
+  // k-contiguous A only if the caller vouches for zero padding up to the next multiple of 64
+  const bool a_tail_ok = a.layout == GEMM_NN && a.a_k_pad_zero && a.lda >= round_up(a.K, DTL_BK);
+  if (a.layout != GEMM_TN && a.K % DTL_BK && !a_tail_ok) return POPLAR_ERR_UNIMPLEMENTED;
   if (a.K < DTL_BK) return POPLAR_ERR_UNIMPLEMENTED;
   if (a.lda % 8 || a.ldb % 8 || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15)) return POPLAR_ERR_UNIMPLEMENTED;
   if (a.ldc % 8 || a.ldc < round_up(a.N, 8) || ((uintptr_t)a.C & 15) || (a.aux && (a.ldaux % 8 || ((uintptr_t)a.aux & 15))) ||
@@ -349,7 +352,7 @@ int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) {
   const int64_t a_rows = a.layout == GEMM_TN ? a.K : a.M, a_cols = a.layout == GEMM_TN ? a.M : a.K;
   const int64_t b_rows = a.layout == GEMM_NT ? a.N : a.K, b_cols = a.layout == GEMM_NT ? a.K : a.N;
   if (round_up(a_cols, 8) > a.lda || round_up(b_cols, 8) > a.ldb) return POPLAR_ERR_UNIMPLEMENTED;
-  const int64_t a_bytes = ((a_rows - 1) * a.lda + round_up(a_cols, 8)) * 2;
+  const int64_t a_bytes = ((a_rows - 1) * a.lda + (a_tail_ok ? round_up(a_cols, DTL_BK) : round_up(a_cols, 8))) * 2;
   const int64_t b_bytes = ((b_rows - 1) * a.ldb + round_up(b_cols, 8)) * 2;
   // 32-bit offsets must also hold for the rows a tile reaches past the matrix
   const int64_t lim = (int64_t)0xfffffff0u - 1024;
@@ -363,17 +366,32 @@ int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) {
   p.a_records = (uint32_t)a_bytes; p.b_records = (uint32_t)b_bytes;
   p.c_float = a.c_float; p.act = a.act; p.beta = a.beta;
 
-  const bool big = cdiv(a.M, 256) * cdiv(a.N, 256) >= 384;
+  // Tile shape and K split by a small cost model, in units of one K step of a 256x256 tile on its CU:
+  // 256x256 tiles run one block per CU; 128x128 tiles two per CU, each step a quarter of the work at
+  // ~85% of the efficiency; the epilogue costs a few K steps (more when it adds with atomics); the
+  // launch takes ceil(blocks / slots) rounds.
+  const bool plain = a.c_float && !a.bias && !a.residual && a.act == ACT_NONE;
+  const int64_t ksteps = cdiv(a.K, DTL_BK);
+  bool big = true;
+  int splits = 1;
+  double best = 1e300;
+  for (int cfg = 0; cfg < 2; ++cfg) {
+    const bool bg = cfg == 0;
+    const int64_t t = cdiv(a.M, bg ? 256 : 128) * cdiv(a.N, bg ? 256 : 128);
+    const double slots = bg ? 256.0 : 512.0, step = bg ? 1.0 : 0.59;
+    static const int cand[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16};
+    for (int sp : cand) {
+      if (sp > 1 && (!plain || ksteps / sp < 8)) break;
+      const double epi = sp > 1 ? (bg ? 8.0 : 2.5) : (bg ? 4.0 : 1.2);
+      const double rounds = ceil((double)(t * sp) / slots);
+      const double cost = rounds * ((double)cdiv(ksteps, sp) * step + epi);
+      if (cost < best) { best = cost; big = bg; splits = sp; }
+    }
+  }
   const int BM = big ? 256 : 128, BN = big ? 256 : 128;
   p.tiles_m = (int)cdiv(a.M, BM);
   p.tiles_n = (int)cdiv(a.N, BN);
   const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-  int splits = 1;
-  const bool plain = a.c_float && !a.bias && !a.residual && a.act == ACT_NONE;
-  if (plain && tiles < 384) {
-    splits = (int)std::min<int64_t>(cdiv(768, tiles), cdiv(a.K, 512));
-    if (splits < 1) splits = 1;
-  }
   p.k_per_split = (int)round_up(cdiv(a.K, splits), DTL_BK);
   splits = (int)cdiv(a.K, p.k_per_split);
   const bool atomic = splits > 1;

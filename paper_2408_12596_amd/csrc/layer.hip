@@ -70,6 +70,7 @@ static GemmArgs gemm_args(int layout, int64_t M, int64_t N, int64_t K, const voi
   g.layout = layout; g.M = M; g.N = N; g.K = K;
   g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
   g.c_float = 0; g.beta = 0.f; g.bias = nullptr; g.residual = nullptr; g.act = ACT_NONE; g.aux = nullptr; g.ldaux = 0;
+  g.a_k_pad_zero = 0;
   return g;
 }
 
@@ -359,6 +360,7 @@ int head_bwd_part(poplar_ctx* ctx, int B, const void* x, const void* gf, const v
   ga.c_float = 1; ga.beta = accumulate ? 1.f : 0.f;
   POPLAR_TRY(gemm(ctx, ga));
   ga = gemm_args(GEMM_NN, T, H, V, logits, hp.ldl, whead, H, dhf, H);
+  ga.a_k_pad_zero = 1;   // the loss kernel zeroed columns V .. ldl of every row
   POPLAR_TRY(gemm(ctx, ga));
   POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, dhf, x, gf, stats, nullptr, dx, d_gf, d_bf, accumulate, scratch, scratch_floats(c), llama));
   return POPLAR_OK;
