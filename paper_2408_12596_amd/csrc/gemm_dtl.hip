@@ -12,10 +12,17 @@
 //    the global side: every lane computes once which 16 bytes belong at its LDS
 //    position.  Rows past the matrix are out of the buffer's range and arrive
 //    as zeros.
-//  * Two LDS stages, one barrier per K step of 64: the loads of step i+1 are in
-//    flight while the MFMAs of step i run; no ds_write instructions at all.
+//  * Two LDS stages, one barrier per K step of 64 (four k-slices of 16), no
+//    ds_write instructions at all.  The step is software-pipelined by hand: the
+//    barrier sits before the last k-slice, so that the loads of the tile after
+//    next are issued, one per MFMA, while that slice runs, and the first
+//    fragments of the next tile are read behind the same MFMAs.  Issued in one
+//    burst at the top of a step the loads hold every wavefront at the address
+//    unit's queue while the matrix cores idle (measured: 0.4 us of a 1.5 us
+//    step).  Scheduling fences keep MFMAs, LDS reads and loads in source order.
 //  * 256x256 block tile on 8 wavefronts (2 x 4, each 128x64) for large
-//    problems, 128x128 on 4 wavefronts (two blocks per CU) for small ones.
+//    problems, 256x192 (4 x 2, each 64x96) where that fills the CUs in whole
+//    rounds, 128x128 on 4 wavefronts (two blocks per CU) for small ones.
 // Preconditions checked by the launcher: K a multiple of 64 unless both operands
 // are k-strided (their K tail is out of range, hence zero), operand extents
 // below 4 GiB (32-bit buffer offsets).
@@ -24,6 +31,8 @@
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef int intx2 __attribute__((ext_vector_type(2)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 struct DtlGemmParams {
@@ -37,7 +46,6 @@ struct DtlGemmParams {
 };
 
 #define DTL_BK 64
-#define OOB_OFFSET 0xfffffff0u
 
 __device__ inline int dtl_swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
@@ -47,12 +55,12 @@ struct DirectImage {
   static constexpr int BYTES = R * 128;
   static constexpr int LOADS = BYTES / 1024;
   static constexpr int FRAG_READS = 1;
+  static constexpr bool MANUAL_WAIT = false;
   // byte offset (k = 0) of the 16 bytes that belong at LDS position idx*1024 + lane*16
   __device__ static uint32_t lane_offset(int idx, int lane, int64_t ld, int64_t r0) {
     const int row = idx * 8 + (lane >> 3);
     const int c = (lane & 7) ^ dtl_swz(row);
-    const int64_t off = ((r0 + row) * ld + c * 8) * 2;
-    return off < (int64_t)OOB_OFFSET ? (uint32_t)off : OOB_OFFSET;
+    return (uint32_t)(((r0 + row) * ld + c * 8) * 2);
   }
   __device__ static uint32_t k_step(int64_t ld) { return DTL_BK * 2; }   // bytes added per K step
   __device__ static bf16x8 frag(const char* lds, int ro, int kk, int lane) {
@@ -68,24 +76,28 @@ struct StridedImage {
   static constexpr int BYTES = 64 * STRIDE;
   static constexpr int LOADS = BYTES / 1024;
   static constexpr int FRAG_READS = 2;
+  static constexpr bool MANUAL_WAIT = true;
   static_assert(BYTES % 1024 == 0, "image must be whole KiB");
   __device__ static uint32_t lane_offset(int idx, int lane, int64_t ld, int64_t r0) {
     const int pos = idx * 1024 + lane * 16;
     const int krow = pos / STRIDE, col = pos % STRIDE;
-    if (col >= R * 2) return OOB_OFFSET;   // padding
-    const int64_t off = ((int64_t)krow * ld + r0 + col / 2) * 2;
-    return off < (int64_t)OOB_OFFSET ? (uint32_t)off : OOB_OFFSET;
+    // lanes that land in the padding fetch the row's first bytes again: never read back, no extra traffic
+    return (uint32_t)(((int64_t)krow * ld + r0 + (col >= R * 2 ? 0 : col / 2)) * 2);
   }
   __device__ static uint32_t k_step(int64_t ld) { return (uint32_t)(DTL_BK * ld * 2); }
+  // The transposing reads are written as assembly: the compiler orders the builtin form after every
+  // global -> LDS load in flight (it cannot tell the stage being filled from the one being read), which
+  // would serialise the pipeline.  The price: the compiler does not see these reads complete either, so
+  // the kernel waits on lgkmcnt by hand before it uses a fragment (MANUAL_WAIT).
   __device__ static bf16x8 frag(const char* lds, int ro, int kk, int lane) {
     const int j = lane & 15, gi = (lane >> 4) & 1, lk = lane >> 5;
     const char* q = lds + (kk * 16 + lk * 8 + (j >> 2)) * STRIDE + (ro + gi * 16 + 4 * (j & 3)) * 2;
-    typedef __attribute__((address_space(3))) bf16x4* lds_ptr;
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(q));
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(q + 4 * STRIDE));
-    bf16x8 f;
-    f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3]; f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
-    return f;
+    const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)q;
+    intx2 lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(addr + 4 * STRIDE));
+    intx4 f = {lo[0], lo[1], hi[0], hi[1]};
+    return __builtin_bit_cast(bf16x8, f);
   }
 };
 
@@ -129,45 +141,45 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGemmParams
   const int64_t kbeg = (int64_t)blockIdx.y * p.k_per_split;
   const int64_t kend = min(p.K, kbeg + p.k_per_split);
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
   const int wm = (wave / WN) * (TM * 32), wn = (wave % WN) * (TN * 32);
   const int lr = lane & 31, lk = lane >> 5;
 
-  const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, p.a_records, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, p.b_records, 0x00020000);
+  // buffer descriptors are rebuilt per step: with zero records every lane is out of range, which turns
+  // the loads past the last tile into zero fills without a branch in the MFMA stream
+  __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, p.a_records, 0x00020000);
+  __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, p.b_records, 0x00020000);
 
-  // per-lane source offsets of this wave's loads (wave w takes loads w, w + NW, ...)
-  constexpr int LA = (ImA::LOADS + NW - 1) / NW, LB = (ImB::LOADS + NW - 1) / NW;
-  uint32_t offa[LA], offb[LB];
+  // Per-lane source offsets of this wave's loads: wave w takes KiB w, w + NW, ... of each image; when the
+  // KiB count is not a multiple of NW the first waves take one more (XA / XB).
+  constexpr int LA = ImA::LOADS / NW, LB = ImB::LOADS / NW, NL = LA + LB;
+  constexpr int XA = ImA::LOADS % NW, XB = ImB::LOADS % NW;
+  uint32_t offa[LA + 1], offb[LB + 1];
   const uint32_t stepa = ImA::k_step(p.lda), stepb = ImB::k_step(p.ldb);
 #pragma unroll
-  for (int i = 0; i < LA; ++i) {
-    offa[i] = ImA::lane_offset(wave + i * NW, lane, p.lda, m0);
-    if (offa[i] != OOB_OFFSET) offa[i] += (uint32_t)(kbeg / DTL_BK) * stepa;
-  }
+  for (int i = 0; i <= LA; ++i) offa[i] = ImA::lane_offset(min(wave + i * NW, ImA::LOADS - 1), lane, p.lda, m0) + (uint32_t)(kbeg / DTL_BK) * stepa;
 #pragma unroll
-  for (int i = 0; i < LB; ++i) {
-    offb[i] = ImB::lane_offset(wave + i * NW, lane, p.ldb, n0);
-    if (offb[i] != OOB_OFFSET) offb[i] += (uint32_t)(kbeg / DTL_BK) * stepb;
-  }
+  for (int i = 0; i <= LB; ++i) offb[i] = ImB::lane_offset(min(wave + i * NW, ImB::LOADS - 1), lane, p.ldb, n0) + (uint32_t)(kbeg / DTL_BK) * stepb;
 
-  auto issue = [&](char* st) {
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-      const int idx = wave + i * NW;
-      if (idx < ImA::LOADS) {
-        load_kib_to_lds(rsrc_a, st + idx * 1024, offa[i]);
-        if (offa[i] != OOB_OFFSET) offa[i] += stepa;
-      }
+  // load number l (0 .. NL-1) of this wave's share of a tile into stage st
+  auto load_one = [&](char* st, int l) __attribute__((always_inline)) {
+    if (l < LA) {
+      load_kib_to_lds(rsrc_a, st + (wave + l * NW) * 1024, offa[l]);
+      offa[l] += stepa;
+    } else {
+      load_kib_to_lds(rsrc_b, st + ImA::BYTES + (wave + (l - LA) * NW) * 1024, offb[l - LA]);
+      offb[l - LA] += stepb;
     }
+  };
+  auto load_extra = [&](char* st) __attribute__((always_inline)) {
+    if (XA && wave < XA) { load_kib_to_lds(rsrc_a, st + (wave + LA * NW) * 1024, offa[LA]); offa[LA] += stepa; }
+    if (XB && wave < XB) { load_kib_to_lds(rsrc_b, st + ImA::BYTES + (wave + LB * NW) * 1024, offb[LB]); offb[LB] += stepb; }
+  };
+  auto load_tile = [&](char* st) __attribute__((always_inline)) {
+    load_extra(st);
 #pragma unroll
-    for (int i = 0; i < LB; ++i) {
-      const int idx = wave + i * NW;
-      if (idx < ImB::LOADS) {
-        load_kib_to_lds(rsrc_b, st + ImA::BYTES + idx * 1024, offb[i]);
-        if (offb[i] != OOB_OFFSET) offb[i] += stepb;
-      }
-    }
+    for (int l = 0; l < NL; ++l) load_one(st, l);
   };
 
   floatx16 acc[TM][TN];
@@ -178,68 +190,79 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGemmParams
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-  auto compute = [&](const char* st) {
-    const char* lds_a = st;
-    const char* lds_b = st + ImA::BYTES;
-    bf16x8 fa[2][TM], fb[2][TN];
+  // Fragments of k-slice kk of a stage; f = 0 .. TM+TN-1 in the order the MFMAs first need them
+  bf16x8 fa[2][TM], fb[2][TN];
+  auto read_frag = [&](const char* st, int kk, int buf, int f) __attribute__((always_inline)) {
+    // order: a0, b0, b1 .., a1, a2 ..
+    if (f == 0) fa[buf][0] = ImA::frag(st, wm, kk, lane);
+    else if (f <= TN) fb[buf][f - 1] = ImB::frag(st + ImA::BYTES, wn + (f - 1) * 32, kk, lane);
+    else fa[buf][f - TN] = ImA::frag(st, wm + (f - TN) * 32, kk, lane);
+  };
+  constexpr int NM = TM * TN, NF = TM + TN;
+  // One k-slice: the NM MFMAs in source order, with the fragment reads of the next slice (from `rst`, slice rkk) and `nload` tile loads into `lst` dealt evenly between them.  The
+  // fences keep the order as written: without them the reads drift together and the MFMAs wait on LDS.
+  auto slice = [&](int buf, const char* rst, int rkk, char* lst, int nload) __attribute__((always_inline)) {
+    if (ImA::MANUAL_WAIT || ImB::MANUAL_WAIT) {
+      __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this slice's fragments, read during the previous one
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    constexpr int SLACK = NM >= 6 ? 2 : 1;   // MFMAs left after the last read is issued
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[0][i] = ImA::frag(lds_a, wm + i * 32, 0, lane);
+    for (int x = 0; x < NM; ++x) {
+      const int i = x / TN, j = x % TN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = ImB::frag(lds_b, wn + j * 32, 0, lane);
+      for (int f = 0; f < NF; ++f)
+        if (f * (NM - SLACK) / NF == x) read_frag(rst, rkk, buf ^ 1, f);
 #pragma unroll
-    for (int kk = 0; kk < DTL_BK / 16; ++kk) {
-      const int cur = kk & 1, nxt = cur ^ 1;
-      if (kk + 1 < DTL_BK / 16) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[nxt][i] = ImA::frag(lds_a, wm + i * 32, kk + 1, lane);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[nxt][j] = ImB::frag(lds_b, wn + j * 32, kk + 1, lane);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
-      if (kk + 1 < DTL_BK / 16) {
-#pragma unroll
-        for (int x = 0; x < ImA::FRAG_READS * TM + ImB::FRAG_READS * TN; ++x) {
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          if (x < TM * TN) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        }
-        if (ImA::FRAG_READS * TM + ImB::FRAG_READS * TN < TM * TN)
-          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (ImA::FRAG_READS * TM + ImB::FRAG_READS * TN), 0);
-      }
+      for (int l = 0; l < nload; ++l)
+        if (l * NM / nload == x) load_one(lst, l);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  // two-stage pipeline: wait for this step's tile, let every wave leave the previous step, start the next
-  // tile's loads into the other stage, compute.  (The generated loop waits on vmcnt only at its top: the
-  // loads stay in flight during the MFMAs.)
-  issue(stage0);
-  if constexpr (TM * TN <= 4) {
-    // small wave tile: unrolled by two, each stage a compile-time object (measured faster; the large
-    // wave tile runs out of registers in this form)
-    for (int64_t k0 = kbeg; k0 < kend; k0 += 2 * DTL_BK) {
-      __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's tile loads have landed
-      __syncthreads();
-      if (k0 + DTL_BK < kend) issue(stage1);
-      compute(stage0);
-      if (k0 + DTL_BK >= kend) break;
-      __builtin_amdgcn_s_waitcnt(0x0f70);
-      __syncthreads();
-      if (k0 + 2 * DTL_BK < kend) issue(stage0);
-      compute(stage1);
-    }
-  } else {
-    int par = 0;
-    for (int64_t k0 = kbeg; k0 < kend; k0 += DTL_BK, par ^= 1) {
-      __builtin_amdgcn_s_waitcnt(0x0f70);
-      __syncthreads();
-      char* cur = par ? stage1 : stage0;
-      char* nxt = par ? stage0 : stage1;
-      if (k0 + DTL_BK < kend) issue(nxt);
-      compute(cur);
-    }
+  // Software pipeline over K steps of 64 (four k-slices).  At the top of step i the fragments of slice 0
+  // are in registers and tile i+1 is in flight into the other stage.  Slices 0..2 run; then the wave
+  // waits for its own loads and for its last LDS reads, the barrier tells it that every wave has done
+  // so (tile i+1 complete, stage of tile i no longer read); slice 3 runs while the loads of tile i+2
+  // start into the freed stage and slice 0 of tile i+1 is read.
+  const int nsteps = (int)((kend - kbeg + DTL_BK - 1) / DTL_BK);
+  load_tile(stage0);
+  if (nsteps > 1) load_tile(stage1);
+  if (nsteps > 1) __builtin_amdgcn_s_waitcnt(0x0f70 | (NL & 15) | ((NL >> 4) << 14));   // vmcnt(NL): tile 0 landed (extras of tile 1 are older than its regular loads)
+  else __builtin_amdgcn_s_waitcnt(0x0f70);
+  __syncthreads();
+#pragma unroll
+  for (int f = 0; f < NF; ++f) read_frag(stage0, 0, 0, f);
+  __builtin_amdgcn_sched_barrier(0);
+  int par = 0;
+  for (int i = 0; i < nsteps; ++i, par ^= 1) {
+    char* cur = par ? stage1 : stage0;
+    char* nxt = par ? stage0 : stage1;
+    slice(0, cur, 1, nullptr, 0);
+    slice(1, cur, 2, nullptr, 0);
+    slice(0, cur, 3, nullptr, 0);
+    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+    __syncthreads();
+    // the last two steps have no tile to fetch: their loads zero-fill a stage nobody reads again, and the
+    // last step's fragment reads of the other stage are never used
+    const bool more = i + 2 < nsteps;
+    rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, more ? p.a_records : 0u, 0x00020000);
+    rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, more ? p.b_records : 0u, 0x00020000);
+    load_extra(cur);
+    slice(1, nxt, 0, cur, NL);
   }
+  // The zero fills must have landed before the stages are reused below.  The last step's fragment reads
+  // must have landed too: the compiler does not know the assembly reads are in flight, their destination
+  // registers are dead here, and a late return would overwrite whatever the epilogue keeps there (an
+  // address, for one).
+  // The empty statements after the wait name those registers as inputs, which keeps them reserved up to
+  // that point.
+  __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+#pragma unroll
+  for (int i = 0; i < TM; ++i) asm volatile("" ::"v"(fa[0][i]));
+#pragma unroll
+  for (int j = 0; j < TN; ++j) asm volatile("" ::"v"(fb[0][j]));
   __syncthreads();
 
   if (ATOMIC) {
@@ -366,29 +389,29 @@ int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) {
   p.a_records = (uint32_t)a_bytes; p.b_records = (uint32_t)b_bytes;
   p.c_float = a.c_float; p.act = a.act; p.beta = a.beta;
 
-  // Tile shape and K split by a small cost model, in units of one K step of a 256x256 tile on its CU:
-  // 256x256 tiles run one block per CU; 128x128 tiles two per CU, each step a quarter of the work at
-  // ~85% of the efficiency; the epilogue costs a few K steps (more when it adds with atomics); the
-  // launch takes ceil(blocks / slots) rounds.
+  // Tile shape and K split by a small cost model, in units of one K step of a 256x256 tile on its CU.
+  // 256x256 and 256x192 tiles run one block per CU, 128x128 tiles two per CU (each step a quarter of the
+  // work at ~85% of the efficiency); the epilogue costs a few K steps (more when it adds with atomics);
+  // the launch takes ceil(blocks / slots) rounds.  The 256x192 tile exists for the block count: widths
+  // such as 768 or 2304 give whole rounds with it where 256-wide tiles leave a quarter of the CUs idle.
+  struct TileCfg { int bm, bn; double slots, step, epi, epi_atomic; };
+  static const TileCfg cfgs[3] = {{256, 256, 256.0, 1.0, 4.0, 8.0}, {256, 192, 256.0, 0.78, 3.0, 6.0}, {128, 128, 512.0, 0.59, 1.2, 2.5}};
   const bool plain = a.c_float && !a.bias && !a.residual && a.act == ACT_NONE;
   const int64_t ksteps = cdiv(a.K, DTL_BK);
-  bool big = true;
-  int splits = 1;
+  int pick = 0, splits = 1;
   double best = 1e300;
-  for (int cfg = 0; cfg < 2; ++cfg) {
-    const bool bg = cfg == 0;
-    const int64_t t = cdiv(a.M, bg ? 256 : 128) * cdiv(a.N, bg ? 256 : 128);
-    const double slots = bg ? 256.0 : 512.0, step = bg ? 1.0 : 0.59;
+  for (int cfg = 0; cfg < 3; ++cfg) {
+    const TileCfg& tc = cfgs[cfg];
+    const int64_t t = cdiv(a.M, tc.bm) * cdiv(a.N, tc.bn);
     static const int cand[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16};
     for (int sp : cand) {
       if (sp > 1 && (!plain || ksteps / sp < 8)) break;
-      const double epi = sp > 1 ? (bg ? 8.0 : 2.5) : (bg ? 4.0 : 1.2);
-      const double rounds = ceil((double)(t * sp) / slots);
-      const double cost = rounds * ((double)cdiv(ksteps, sp) * step + epi);
-      if (cost < best) { best = cost; big = bg; splits = sp; }
+      const double rounds = ceil((double)(t * sp) / tc.slots);
+      const double cost = rounds * ((double)cdiv(ksteps, sp) * tc.step + (sp > 1 ? tc.epi_atomic : tc.epi));
+      if (cost < best) { best = cost; pick = cfg; splits = sp; }
     }
   }
-  const int BM = big ? 256 : 128, BN = big ? 256 : 128;
+  const int BM = cfgs[pick].bm, BN = cfgs[pick].bn;
   p.tiles_m = (int)cdiv(a.M, BM);
   p.tiles_n = (int)cdiv(a.N, BN);
   const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
@@ -403,9 +426,12 @@ int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) {
     }
   }
   dim3 grid((unsigned)tiles, (unsigned)splits);
-  if (big) {
+  if (pick == 0) {
     if (atomic) launch_dtl<2, 4, 4, 2, true>(s, a.layout, grid, p);
     else launch_dtl<2, 4, 4, 2, false>(s, a.layout, grid, p);
+  } else if (pick == 1) {
+    if (atomic) launch_dtl<4, 2, 2, 3, true>(s, a.layout, grid, p);
+    else launch_dtl<4, 2, 2, 3, false>(s, a.layout, grid, p);
   } else {
     if (atomic) launch_dtl<2, 2, 2, 2, true>(s, a.layout, grid, p);
     else launch_dtl<2, 2, 2, 2, false>(s, a.layout, grid, p);
