@@ -391,11 +391,13 @@ int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) {
 
   // Tile shape and K split by a small cost model, in units of one K step of a 256x256 tile on its CU.
   // 256x256 and 256x192 tiles run one block per CU, 128x128 tiles two per CU (each step a quarter of the
-  // work at ~85% of the efficiency); the epilogue costs a few K steps (more when it adds with atomics);
-  // the launch takes ceil(blocks / slots) rounds.  The 256x192 tile exists for the block count: widths
-  // such as 768 or 2304 give whole rounds with it where 256-wide tiles leave a quarter of the CUs idle.
+  // work at ~80% of the efficiency); the epilogue costs a few K steps; the launch takes
+  // ceil(blocks / slots) rounds.  The 256x192 tile exists for the block count: widths such as 768 or
+  // 2304 give whole rounds with it where 256-wide tiles leave a quarter of the CUs idle.  A split adds a
+  // zero fill and float atomics, which the chip retires at a fixed rate (about 250 G/s measured)
+  // whatever the tile shape: that term is what keeps the split count low.
   struct TileCfg { int bm, bn; double slots, step, epi, epi_atomic; };
-  static const TileCfg cfgs[3] = {{256, 256, 256.0, 1.0, 4.0, 8.0}, {256, 192, 256.0, 0.78, 3.0, 6.0}, {128, 128, 512.0, 0.59, 1.2, 2.5}};
+  static const TileCfg cfgs[3] = {{256, 256, 256.0, 1.0, 4.0, 6.0}, {256, 192, 256.0, 0.84, 3.0, 5.0}, {128, 128, 512.0, 0.6, 1.2, 2.0}};
   const bool plain = a.c_float && !a.bias && !a.residual && a.act == ACT_NONE;
   const int64_t ksteps = cdiv(a.K, DTL_BK);
   int pick = 0, splits = 1;
@@ -407,7 +409,8 @@ int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) {
     for (int sp : cand) {
       if (sp > 1 && (!plain || ksteps / sp < 8)) break;
       const double rounds = ceil((double)(t * sp) / tc.slots);
-      const double cost = rounds * ((double)cdiv(ksteps, sp) * tc.step + (sp > 1 ? tc.epi_atomic : tc.epi));
+      const double cost = rounds * ((double)cdiv(ksteps, sp) * tc.step + (sp > 1 ? tc.epi_atomic : tc.epi)) +
+                          (sp > 1 ? 3.0 + 2.7e-6 * (double)sp * (double)a.M * (double)a.N : 0.0);
       if (cost < best) { best = cost; pick = cfg; splits = sp; }
     }
   }
