@@ -93,20 +93,21 @@ __device__ inline float gelu_tanh_grad(float h) {
   return 0.5f * (1.0f + t) + 0.5f * h * dt;
 }
 
-// fast variants for bf16 outputs: tanh(u) = 1 - 2 / (exp(2u) + 1) with the hardware exp and reciprocal
-__device__ inline float tanh_fast(float u) {
-  const float e = __expf(2.0f * u);          // inf for large u gives 1, 0 for very negative u gives -1
-  return 1.0f - 2.0f * __frcp_rn(e + 1.0f);
+// fast variants for bf16 outputs, on the identity 0.5 (1 + tanh u) = sigmoid(2u) = 1 / (1 + 2^(-2u log2 e))
+// with the hardware exp2 and reciprocal: gelu(h) = h s,  gelu'(h) = s + h s (1 - s) 2u'.
+// Large |h| saturate the right way: 2^z = inf gives s = 0, 2^z = 0 gives s = 1.
+__device__ inline float gelu_sigmoid_fast(float h, float h2) {
+  const float c0 = -2.0f * 0.7978845608028654f * 1.4426950408889634f, c1 = c0 * 0.044715f;
+  const float z = h * __builtin_fmaf(h2, c1, c0);
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z));
 }
-__device__ inline float gelu_tanh_fast(float h) {
-  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
-  return 0.5f * h * (1.0f + tanh_fast(k0 * (h + k1 * h * h * h)));
-}
+__device__ inline float gelu_tanh_fast(float h) { return h * gelu_sigmoid_fast(h, h * h); }
 __device__ inline float gelu_tanh_grad_fast(float h) {
   const float k0 = 0.7978845608028654f, k1 = 0.044715f;
-  const float t = tanh_fast(k0 * (h + k1 * h * h * h));
-  const float dt = (1.0f - t * t) * k0 * (1.0f + 3.0f * k1 * h * h);
-  return 0.5f * (1.0f + t) + 0.5f * h * dt;
+  const float h2 = h * h;
+  const float s = gelu_sigmoid_fast(h, h2);
+  const float du2 = __builtin_fmaf(h2, 6.0f * k0 * k1, 2.0f * k0);   // 2 u'
+  return __builtin_fmaf(h * du2 * s, 1.0f - s, s);
 }
 
 // streaming (non-temporal) 16-byte / 8-byte accesses: index i counts vectors
