@@ -23,6 +23,10 @@ WORLD, RANK, STAGE = 8, 0, 1
 SWEEP = (1, 2, 4, 8, 16)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# Bytes that cross the L2 per GEMM launch at local batch 16, averaged over the 147 launches of a step: rocprofv3
+# counters FETCH_SIZE x 2.0 (calibrated on kernels of known size) + WRITE_SIZE, summarised under profiles/.
+# Valid for the GEMM kernel as profiled; set to None when that kernel changes until the counters are taken again.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 307.1e6
 
 
 def cpu_baseline(model, flat, tok, tgt):
@@ -121,8 +125,9 @@ def main():
         "frac_mfma_peak_step": flops / dt / 1e12 / PEAK_BF16_TFLOPS,
         "samples_per_s_time_consumed": B / mean("t_consumed"),
         "step_breakdown_ms": {k: mean(k) * 1e3 for k in ("t_fwd", "t_bwd", "t_adam", "t_gemm", "t_attn")},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16 (all GEMM launches of the step)", "achieved": gemm_tflops,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+        "roofline": {"bound": "mfma", "kernel": "gemm_dtl_kernel (all GEMM launches of the step)", "achieved": gemm_tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if B == 16 else None, "traffic_unit": "bytes per launch",
                      "launches_per_step": n_gemm, "avg_launch_ms": t_gemm / max(n_gemm, 1) * 1e3,
                      "flop_per_launch": f_gemm / max(n_gemm, 1)},
         "attention": {"achieved": f_attn / t_attn / 1e12 if t_attn > 0 else 0.0, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS,
