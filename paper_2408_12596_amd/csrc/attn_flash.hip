@@ -37,6 +37,8 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef int intx2 __attribute__((ext_vector_type(2)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 #define LOG2E 1.4426950408889634f
@@ -92,17 +94,27 @@ struct Rows64 {
     const int chunk = ct * 4 + gi * 2 + ((l16 & 3) >> 1);     // logical 16-byte chunk of the lane's 4 values
     return row * ROWB + ((chunk ^ (row & 7)) << 4) + (l16 & 1) * 8;
   }
-  // A fragment, rows as reduction index: 16-row chunk j, k-slots in probability order
+  // A fragment, rows as reduction index: 16-row chunk j, k-slots in probability order.
+  // Written as assembly: the compiler would make the builtin form wait for every global -> LDS load in
+  // flight (it cannot tell the stage being filled from the one being read).  It does not see these reads
+  // complete either: the caller waits with fa_wait_lds() before it uses the fragment.
   __device__ static bf16x8 frag_tr(const char* lds, int base, int j) {
-    typedef __attribute__((address_space(3))) bf16x4* lds_ptr;
     const char* q = lds + base + j * 16 * ROWB;
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(q));
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(q + 8 * ROWB));
-    bf16x8 f;
-    f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3]; f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
-    return f;
+    const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)q;
+    intx2 lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(addr + 8 * ROWB));
+    intx4 f = {lo[0], lo[1], hi[0], hi[1]};
+    return __builtin_bit_cast(bf16x8, f);
   }
 };
+
+// all LDS reads issued so far have returned; nothing moves across
+__device__ inline void fa_wait_lds() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+  __builtin_amdgcn_sched_barrier(0);
+}
 
 // B fragments of one row of a [*, ld] matrix kept in registers: D/16 slices
 template <int D>
@@ -146,7 +158,7 @@ __device__ inline uint32_t records_from(int64_t rows_total, int64_t row0, int64_
 // forward
 // =============================================================================
 template <int D>
-__global__ void __launch_bounds__(256) flash_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
+__global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
                                                          int B, int S, int nh, int causal, float scale) {
   typedef Rows64<D> Img;
   __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * Img::BYTES];   // [stage][K | V]
@@ -206,6 +218,16 @@ __global__ void __launch_bounds__(256) flash_fwd_kernel(const bf16* __restrict__
       for (int s = 0; s < D / 16; ++s)
         st[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(k_lds, u * 32 + lr, s, g), qf[s], st[u], 0, 0, 0);
     }
+    // V^T fragments, PF 16-row chunks at a time: the first group is issued now and returns behind the
+    // softmax arithmetic, each later group behind the MFMAs of the one before
+    constexpr int PF = D == 64 ? 2 : 1;
+    bf16x8 vf[2][PF][D / 32];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < PF; ++j)
+#pragma unroll
+      for (int ct = 0; ct < D / 32; ++ct) vf[0][j][ct] = Img::frag_tr(v_lds, trb[ct], j);
+    __builtin_amdgcn_sched_barrier(0);
     // only tiles that touch the diagonal of this wave's queries or the end of the sequence need the mask
     if ((causal && kv0 + 63 > qw0) || kv0 + 64 > S) {
 #pragma unroll
@@ -236,17 +258,31 @@ __global__ void __launch_bounds__(256) flash_fwd_kernel(const bf16* __restrict__
       }
     l_run = l_run * alpha + psum;
     m_run = m_new;
-#pragma unroll
-    for (int ct = 0; ct < D / 32; ++ct)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[ct][i] *= alpha;
-    // O^T += V^T P^T
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bf16x8 pb = regs_to_frag(st[j >> 1], j & 1);
+    // once the running maxima have settled alpha is exactly 1 in every lane: skip the rescale then
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
       for (int ct = 0; ct < D / 32; ++ct)
-        oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag_tr(v_lds, trb[ct], j), pb, oacc[ct], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[ct][i] *= alpha;
+    }
+    // O^T += V^T P^T
+#pragma unroll
+    for (int c = 0; c < 4 / PF; ++c) {
+      fa_wait_lds();
+      if (c + 1 < 4 / PF) {
+#pragma unroll
+        for (int j = 0; j < PF; ++j)
+#pragma unroll
+          for (int ct = 0; ct < D / 32; ++ct) vf[(c + 1) & 1][j][ct] = Img::frag_tr(v_lds, trb[ct], (c + 1) * PF + j);
+      }
+#pragma unroll
+      for (int j = 0; j < PF; ++j) {
+        const int jj = c * PF + j;
+        const bf16x8 pb = regs_to_frag(st[jj >> 1], jj & 1);
+#pragma unroll
+        for (int ct = 0; ct < D / 32; ++ct)
+          oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c & 1][j][ct], pb, oacc[ct], 0, 0, 0);
+      }
     }
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -288,7 +324,7 @@ __global__ void __launch_bounds__(256) flash_delta_kernel(const bf16* __restrict
 // backward, dQ: block = 128 queries, loop over key tiles (S^T form, lane = query)
 // =============================================================================
 template <int D>
-__global__ void __launch_bounds__(256) flash_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+__global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
                                                             bf16* __restrict__ dqkv, int B, int S, int nh, int causal, float scale) {
   typedef Rows64<D> Img;
@@ -341,39 +377,56 @@ __global__ void __launch_bounds__(256) flash_bwd_dq_kernel(const bf16* __restric
     if (kv0 + 64 < kv_end) issue(lds + (par ^ 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + 1) * tile_step);
     const char* k_lds = cur;
     const char* v_lds = cur + Img::BYTES;
-    floatx16 st[2], dpt[2];
+    // K^T fragments of the first 32 keys: issued now, they return behind the MFMAs and the exponentials
+    bf16x8 kt[2][2][D / 32];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+      for (int ct = 0; ct < D / 32; ++ct) kt[0][jj][ct] = Img::frag_tr(k_lds, trb[ct], jj);
+    __builtin_amdgcn_sched_barrier(0);
+    // 32 keys at a time, through to dQ: half the score registers of a whole-tile pass
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      zero_acc(st[u]);
-      zero_acc(dpt[u]);
+      floatx16 st, dpt;
+      zero_acc(st);
+      zero_acc(dpt);
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        st[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(k_lds, u * 32 + lr, s, g), qf[s], st[u], 0, 0, 0);
-        dpt[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(v_lds, u * 32 + lr, s, g), dof[s], dpt[u], 0, 0, 0);
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(k_lds, u * 32 + lr, s, g), qf[s], st, 0, 0, 0);
+        dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(v_lds, u * 32 + lr, s, g), dof[s], dpt, 0, 0, 0);
       }
       if ((causal && kv0 + 63 > q0 + wave * 32) || kv0 + 64 > S || q0 + 128 > S) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int kv = kv0 + u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
           const bool ok = kv < S && q < S && (!causal || kv <= q);
-          const float p = ok ? fast_exp2(__builtin_fmaf(st[u][i], c2, -lse2)) : 0.f;
-          st[u][i] = p * (dpt[u][i] - dl);   // dS^T
+          const float p = ok ? fast_exp2(__builtin_fmaf(st[i], c2, -lse2)) : 0.f;
+          st[i] = p * (dpt[i] - dl);   // dS^T
         }
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const float p = fast_exp2(__builtin_fmaf(st[u][i], c2, -lse2));
-          st[u][i] = p * (dpt[u][i] - dl);
+          const float p = fast_exp2(__builtin_fmaf(st[i], c2, -lse2));
+          st[i] = p * (dpt[i] - dl);
         }
       }
-    }
-    // dQ^T += K^T dS^T
+      // dQ^T += K^T dS^T
+      fa_wait_lds();
+      if (u == 0) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bf16x8 dsb = regs_to_frag(st[j >> 1], j & 1);
+        for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-      for (int ct = 0; ct < D / 32; ++ct)
-        dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag_tr(k_lds, trb[ct], j), dsb, dq[ct], 0, 0, 0);
+          for (int ct = 0; ct < D / 32; ++ct) kt[1][jj][ct] = Img::frag_tr(k_lds, trb[ct], 2 + jj);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const bf16x8 dsb = regs_to_frag(st, jj);
+#pragma unroll
+        for (int ct = 0; ct < D / 32; ++ct)
+          dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt[u][jj][ct], dsb, dq[ct], 0, 0, 0);
+      }
     }
   }
   store_rows_from_transposed<D>(dqkv + (int64_t)b * S * ld + h * D, ld, q, S, g, dq, scale);
@@ -383,7 +436,7 @@ __global__ void __launch_bounds__(256) flash_bwd_dq_kernel(const bf16* __restric
 // backward, dK and dV: block = 128 keys, loop over query tiles (S form, lane = key)
 // =============================================================================
 template <int D>
-__global__ void __launch_bounds__(256) flash_bwd_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+__global__ void __launch_bounds__(256, D == 64 ? 2 : 1) flash_bwd_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
                                                              const float* __restrict__ lse, const float* __restrict__ delta,
                                                              bf16* __restrict__ dqkv, int B, int S, int nh, int causal, float scale) {
   typedef Rows64<D> Img;
@@ -449,15 +502,27 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_kernel(const bf16* __restri
     const char* do_lds = cur + Img::BYTES;
     const float* lse_lds = reinterpret_cast<const float*>(cur + 2 * Img::BYTES);
     const float* delta_lds = reinterpret_cast<const float*>(cur + 2 * Img::BYTES + 1024);
-    floatx16 sm[2], dp[2];
+    // dO^T and Q^T fragments of the first 32 queries: issued now, they return behind the MFMAs and the exponentials
+    bf16x8 dot[2][2][D / 32], qt[2][2][D / 32];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+      for (int ct = 0; ct < D / 32; ++ct) {
+        dot[0][jj][ct] = Img::frag_tr(do_lds, trb[ct], jj);
+        qt[0][jj][ct] = Img::frag_tr(q_lds, trb[ct], jj);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    // 32 queries at a time, through to dV and dK: half the score registers of a whole-tile pass
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      zero_acc(sm[u]);
-      zero_acc(dp[u]);
+      floatx16 sm, dp;
+      zero_acc(sm);
+      zero_acc(dp);
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        sm[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(q_lds, u * 32 + lr, s, g), kf[s], sm[u], 0, 0, 0);
-        dp[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(do_lds, u * 32 + lr, s, g), vf[s], dp[u], 0, 0, 0);
+        sm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(q_lds, u * 32 + lr, s, g), kf[s], sm, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(do_lds, u * 32 + lr, s, g), vf[s], dp, 0, 0, 0);
       }
       if ((causal && q0 < kvb + wave * 32 + 31) || q0 + 64 > S || kvb + 128 > S) {
 #pragma unroll
@@ -465,29 +530,40 @@ __global__ void __launch_bounds__(256) flash_bwd_dkv_kernel(const bf16* __restri
           const int ql = u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
           const int qq = q0 + ql;
           const bool ok = qq < S && kv < S && (!causal || kv <= qq);
-          const float p = ok ? fast_exp2(__builtin_fmaf(sm[u][i], c2, -lse_lds[ql])) : 0.f;
-          dp[u][i] = p * (dp[u][i] - delta_lds[ql]);   // dS
-          sm[u][i] = p;                                 // P
+          const float p = ok ? fast_exp2(__builtin_fmaf(sm[i], c2, -lse_lds[ql])) : 0.f;
+          dp[i] = p * (dp[i] - delta_lds[ql]);   // dS
+          sm[i] = p;                              // P
         }
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int ql = u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-          const float p = fast_exp2(__builtin_fmaf(sm[u][i], c2, -lse_lds[ql]));
-          dp[u][i] = p * (dp[u][i] - delta_lds[ql]);
-          sm[u][i] = p;
+          const float p = fast_exp2(__builtin_fmaf(sm[i], c2, -lse_lds[ql]));
+          dp[i] = p * (dp[i] - delta_lds[ql]);
+          sm[i] = p;
         }
       }
-    }
-    // dV^T += dO^T P,  dK^T += Q^T dS
+      // dV^T += dO^T P,  dK^T += Q^T dS
+      fa_wait_lds();
+      if (u == 0) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bf16x8 pb = regs_to_frag(sm[j >> 1], j & 1);
-      const bf16x8 dsb = regs_to_frag(dp[j >> 1], j & 1);
+        for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-      for (int ct = 0; ct < D / 32; ++ct) {
-        dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag_tr(do_lds, trb[ct], j), pb, dv[ct], 0, 0, 0);
-        dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag_tr(q_lds, trb[ct], j), dsb, dk[ct], 0, 0, 0);
+          for (int ct = 0; ct < D / 32; ++ct) {
+            dot[1][jj][ct] = Img::frag_tr(do_lds, trb[ct], 2 + jj);
+            qt[1][jj][ct] = Img::frag_tr(q_lds, trb[ct], 2 + jj);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const bf16x8 pb = regs_to_frag(sm, jj);
+        const bf16x8 dsb = regs_to_frag(dp, jj);
+#pragma unroll
+        for (int ct = 0; ct < D / 32; ++ct) {
+          dv[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot[u][jj][ct], pb, dv[ct], 0, 0, 0);
+          dk[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt[u][jj][ct], dsb, dk[ct], 0, 0, 0);
+        }
       }
     }
   }
