@@ -161,13 +161,15 @@ template <int D>
 __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
                                                          int B, int S, int nh, int causal, float scale) {
   typedef Rows64<D> Img;
-  __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * Img::BYTES];   // [stage][K | V]
+  constexpr int NS = D == 64 ? 3 : 2;   // LDS stages: tiles t+1 .. t+NS-1 are in flight while tile t is used
+  __shared__ __attribute__((aligned(1024))) char lds[NS * 2 * Img::BYTES];   // [stage][K | V]
   const int H = nh * D;
   const int64_t ld = 3 * (int64_t)H;
   const int qtiles = (S + 127) / 128;
-  const int qt = qtiles - 1 - (int)(blockIdx.x % qtiles);  // heavy (late) query tiles first
-  const int h = (int)((blockIdx.x / qtiles) % nh);
-  const int b = (int)(blockIdx.x / ((int64_t)qtiles * nh));
+  // longest blocks first over the whole grid (late query tiles see the most keys): the last blocks to start are the shortest
+  const int qt = qtiles - 1 - (int)(blockIdx.x / ((int64_t)B * nh));
+  const int h = (int)(blockIdx.x % nh);
+  const int b = (int)((blockIdx.x / nh) % B);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, g = lane >> 5;
   const int q0 = qt * 128;
@@ -200,13 +202,17 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const b
   const int kv_end = causal ? min(S, q0 + 128) : S;
   const int qw0 = q0 + wave * 32;
 
+  constexpr int NLD = 2 * Img::PER_WAVE;   // loads of this wave per tile
   issue(lds, 0);
-  int par = 0;
-  for (int kv0 = 0; kv0 < kv_end; kv0 += 64, par ^= 1) {
-    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's part of the tile has landed
+  if (NS == 3 && 64 < kv_end) issue(lds + 2 * Img::BYTES, tile_step);
+  int sc = 0;   // stage of the current tile
+  for (int kv0 = 0; kv0 < kv_end; kv0 += 64, sc = sc == NS - 1 ? 0 : sc + 1) {
+    // this wave's part of the current tile has landed (loads complete in order; with three stages the next tile's may be pending)
+    if (NS == 3 && kv0 + 64 < kv_end) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
+    else __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();
-    char* cur = lds + par * 2 * Img::BYTES;
-    if (kv0 + 64 < kv_end) issue(lds + (par ^ 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + 1) * tile_step);
+    char* cur = lds + sc * 2 * Img::BYTES;
+    if (kv0 + 64 * (NS - 1) < kv_end) issue(lds + (sc == 0 ? NS - 1 : sc - 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + NS - 1) * tile_step);
     const char* k_lds = cur;
     const char* v_lds = cur + Img::BYTES;
     // S^T tiles: rows = keys kv0 + u*32 + .., cols = this wave's queries
@@ -328,13 +334,14 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(cons
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
                                                             bf16* __restrict__ dqkv, int B, int S, int nh, int causal, float scale) {
   typedef Rows64<D> Img;
-  __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * Img::BYTES];   // [stage][K | V]
+  constexpr int NS = D == 64 ? 3 : 2;   // LDS stages: tiles t+1 .. t+NS-1 are in flight while tile t is used
+  __shared__ __attribute__((aligned(1024))) char lds[NS * 2 * Img::BYTES];   // [stage][K | V]
   const int H = nh * D;
   const int64_t ld = 3 * (int64_t)H;
   const int qtiles = (S + 127) / 128;
-  const int qt = qtiles - 1 - (int)(blockIdx.x % qtiles);
-  const int h = (int)((blockIdx.x / qtiles) % nh);
-  const int b = (int)(blockIdx.x / ((int64_t)qtiles * nh));
+  const int qt = qtiles - 1 - (int)(blockIdx.x / ((int64_t)B * nh));   // longest blocks first over the whole grid
+  const int h = (int)(blockIdx.x % nh);
+  const int b = (int)((blockIdx.x / nh) % B);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, g = lane >> 5;
   const int q0 = qt * 128;
@@ -368,13 +375,16 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(cons
   for (int ct = 0; ct < D / 32; ++ct) { zero_acc(dq[ct]); trb[ct] = Img::tr_base(ct, lane); }
   const int kv_end = causal ? min(S, q0 + 128) : S;
 
+  constexpr int NLD = 2 * Img::PER_WAVE;   // loads of this wave per tile; stages as in the forward kernel
   issue(lds, 0);
-  int par = 0;
-  for (int kv0 = 0; kv0 < kv_end; kv0 += 64, par ^= 1) {
-    __builtin_amdgcn_s_waitcnt(0x0f70);
+  if (NS == 3 && 64 < kv_end) issue(lds + 2 * Img::BYTES, tile_step);
+  int sc = 0;
+  for (int kv0 = 0; kv0 < kv_end; kv0 += 64, sc = sc == NS - 1 ? 0 : sc + 1) {
+    if (NS == 3 && kv0 + 64 < kv_end) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
+    else __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();
-    char* cur = lds + par * 2 * Img::BYTES;
-    if (kv0 + 64 < kv_end) issue(lds + (par ^ 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + 1) * tile_step);
+    char* cur = lds + sc * 2 * Img::BYTES;
+    if (kv0 + 64 * (NS - 1) < kv_end) issue(lds + (sc == 0 ? NS - 1 : sc - 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + NS - 1) * tile_step);
     const char* k_lds = cur;
     const char* v_lds = cur + Img::BYTES;
     // K^T fragments of the first 32 keys: issued now, they return behind the MFMAs and the exponentials
@@ -441,13 +451,14 @@ __global__ void __launch_bounds__(256, D == 64 ? 2 : 1) flash_bwd_dkv_kernel(con
                                                              bf16* __restrict__ dqkv, int B, int S, int nh, int causal, float scale) {
   typedef Rows64<D> Img;
   constexpr int STAGE = 2 * Img::BYTES + 2048;   // Q | dO | lse2 (first 256 bytes of a KiB) | delta (first 256 bytes of a KiB)
-  __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE];
+  constexpr int NS = D == 64 ? 3 : 2;
+  __shared__ __attribute__((aligned(1024))) char lds[NS * STAGE];
   const int H = nh * D;
   const int64_t ld = 3 * (int64_t)H;
-  const int ktiles = (S + 127) / 128;
-  const int ktile = (int)(blockIdx.x % ktiles);   // early key tiles see the most queries: they come first
-  const int h = (int)((blockIdx.x / ktiles) % nh);
-  const int b = (int)(blockIdx.x / ((int64_t)ktiles * nh));
+  // longest blocks first over the whole grid: with the causal mask early key tiles see the most queries
+  const int ktile = (int)(blockIdx.x / ((int64_t)B * nh));
+  const int h = (int)(blockIdx.x % nh);
+  const int b = (int)((blockIdx.x / nh) % B);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, g = lane >> 5;
   const int kvb = ktile * 128;
@@ -491,13 +502,18 @@ __global__ void __launch_bounds__(256, D == 64 ? 2 : 1) flash_bwd_dkv_kernel(con
   const float c2 = scale * LOG2E;
   const int q_begin = causal ? (kvb / 64) * 64 : 0;
 
+  // waves 0 and 1 issue one load more per tile (the statistics), so waiting until at most NLD loads are
+  // pending covers the current tile for every wave
+  constexpr int NLD = 2 * Img::PER_WAVE;
   issue(lds, q_begin);
-  int par = 0;
-  for (int q0 = q_begin; q0 < S; q0 += 64, par ^= 1) {
-    __builtin_amdgcn_s_waitcnt(0x0f70);
+  if (NS == 3 && q_begin + 64 < S) issue(lds + STAGE, q_begin + 64);
+  int sc = 0;
+  for (int q0 = q_begin; q0 < S; q0 += 64, sc = sc == NS - 1 ? 0 : sc + 1) {
+    if (NS == 3 && q0 + 64 < S) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
+    else __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();
-    char* cur = lds + par * STAGE;
-    if (q0 + 64 < S) issue(lds + (par ^ 1) * STAGE, q0 + 64);
+    char* cur = lds + sc * STAGE;
+    if (q0 + 64 * (NS - 1) < S) issue(lds + (sc == 0 ? NS - 1 : sc - 1) * STAGE, q0 + 64 * (NS - 1));
     const char* q_lds = cur;
     const char* do_lds = cur + Img::BYTES;
     const float* lse_lds = reinterpret_cast<const float*>(cur + 2 * Img::BYTES);
