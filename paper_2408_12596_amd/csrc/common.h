@@ -82,6 +82,8 @@ struct GemmArgs {
 int gemm_simple(hipStream_t s, int dtype, const GemmArgs& a);
 int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a);
 int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a);   // POPLAR_ERR_UNIMPLEMENTED when the shape is outside its preconditions
+// up to four problems of one layout and one K in a single launch; POPLAR_ERR_UNIMPLEMENTED (nothing launched) when it cannot
+int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n);
 int gemm(hipStream_t s, int dtype, const GemmArgs& a);
 
 // attention on the fused qkv activation [B*S, 3H]; o [B*S, H]; lse float [B, nh, S]

@@ -620,21 +620,19 @@ int embed_fwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok,
   return POPLAR_OK;
 }
 
+// One element per lane: the 64 atomics of a wavefront instruction fall on 256 consecutive bytes of one
+// (or two) rows of dwte.  With a vector of columns per lane they would be 32 bytes apart and every
+// atomic a memory transaction of its own (measured 4x slower).
 template <typename T>
 __global__ void embed_bwd_wte_kernel(const int32_t* __restrict__ tok, int64_t tok_ld, const T* __restrict__ dx, float* __restrict__ dwte,
                                      int64_t tokens, int S, int H) {
-  constexpr int VN = Vec<T>::N;
-  const int per_row = H / VN;
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (; i < tokens * per_row; i += stride) {
-    int64_t t = i / per_row;
-    int c = (int)(i % per_row) * VN;
-    int id = tok[(t / S) * tok_ld + (t % S)];
-    float a[VN];
-    Vec<T> v; v.load(dx + t * H + c); v.unpack(a);
-#pragma unroll
-    for (int k = 0; k < VN; ++k) unsafeAtomicAdd(dwte + (int64_t)id * H + c + k, a[k]);
+  for (; i < tokens * H; i += stride) {
+    const int64_t t = i / H;
+    const int c = (int)(i - t * H);
+    const int id = tok[(t / S) * tok_ld + (t % S)];
+    unsafeAtomicAdd(dwte + (int64_t)id * H + c, to_float<T>(dx[i]));
   }
 }
 template <typename T>
@@ -662,7 +660,7 @@ int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok,
   int64_t tokens = (int64_t)B * S;
   if (tokens == 0) return POPLAR_OK;
   DISPATCH_DTYPE(dtype, {
-    hipLaunchKernelGGL(embed_bwd_wte_kernel<T>, dim3(grid_for(tokens * H / Vec<T>::N, 256)), dim3(256), 0, s, tok, tok_ld, (const T*)dx, dwte, tokens, S, H);
+    hipLaunchKernelGGL(embed_bwd_wte_kernel<T>, dim3(grid_for(tokens * H, 256)), dim3(256), 0, s, tok, tok_ld, (const T*)dx, dwte, tokens, S, H);
     POPLAR_LAUNCH_CHECK();
     if (dwpe) {
       hipLaunchKernelGGL(embed_bwd_wpe_kernel<T>, dim3((unsigned)cdiv((int64_t)S * H / Vec<T>::N, 256)), dim3(256), 0, s, (const T*)dx, dwpe, B, S, H, accumulate);

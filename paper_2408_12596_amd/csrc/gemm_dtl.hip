@@ -45,6 +45,15 @@ struct DtlGemmParams {
   int tiles_m, tiles_n, k_per_split;
 };
 
+// Up to four problems of one layout, tile shape and K extent in a single launch: the block index runs
+// over the tiles of all of them (start[i] = first tile of problem i).
+#define DTL_MAX_GROUP 4
+struct DtlGroupParams {
+  DtlGemmParams g[DTL_MAX_GROUP];
+  int start[DTL_MAX_GROUP + 1];
+  int n;
+};
+
 #define DTL_BK 64
 
 __device__ inline int dtl_swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
@@ -114,7 +123,7 @@ template <int LAYOUT, int R> struct ImageB { typedef StridedImage<R> type; };
 template <int R> struct ImageB<GEMM_NT, R> { typedef DirectImage<R> type; };
 
 template <int LAYOUT, int WM, int WN, int TM, int TN, bool ATOMIC>
-__global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGemmParams p) {
+__global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParams gp) {
   constexpr int NW = WM * WN;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   typedef typename ImageA<LAYOUT, BM>::type ImA;
@@ -124,13 +133,20 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGemmParams
   __shared__ __attribute__((aligned(1024))) char stage0[STAGE];
   __shared__ __attribute__((aligned(1024))) char stage1[STAGE];
 
-  // XCD-aware renumbering, then bands of 8 tile rows with the column index fastest inside a band
-  const int nt = p.tiles_m * p.tiles_n;
+  // XCD-aware renumbering over the tiles of the whole group (blocks are dealt round-robin to the 8 XCDs; each
+  // XCD gets a contiguous run of tiles), then the problem the tile belongs to, then bands of 8 tile rows with
+  // the column index fastest inside a band
   int id = blockIdx.x;
   {
-    const int per = nt / 8;
+    const int per = gp.start[DTL_MAX_GROUP] / 8;
     if (id < per * 8) id = (id & 7) * per + (id >> 3);
   }
+  int pi = 0;
+#pragma unroll
+  for (int i = 1; i < DTL_MAX_GROUP; ++i)
+    if (i < gp.n && id >= gp.start[i]) pi = i;
+  const DtlGemmParams& p = gp.g[pi];
+  id -= gp.start[pi];
   const int band = 8 * p.tiles_n;
   const int band_id = id / band;
   const int rows_in_band = min(8, p.tiles_m - band_id * 8);
@@ -349,18 +365,17 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGemmParams
 }
 
 template <int WM, int WN, int TM, int TN, bool ATOMIC>
-static void launch_dtl(hipStream_t s, int layout, dim3 grid, const DtlGemmParams& p) {
+static void launch_dtl(hipStream_t s, int layout, dim3 grid, const DtlGroupParams& gp) {
   dim3 block(64 * WM * WN);
   switch (layout) {
-    case GEMM_NT: hipLaunchKernelGGL((gemm_dtl_kernel<GEMM_NT, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, p); break;
-    case GEMM_NN: hipLaunchKernelGGL((gemm_dtl_kernel<GEMM_NN, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, p); break;
-    default: hipLaunchKernelGGL((gemm_dtl_kernel<GEMM_TN, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, p); break;
+    case GEMM_NT: hipLaunchKernelGGL((gemm_dtl_kernel<GEMM_NT, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, gp); break;
+    case GEMM_NN: hipLaunchKernelGGL((gemm_dtl_kernel<GEMM_NN, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, gp); break;
+    default: hipLaunchKernelGGL((gemm_dtl_kernel<GEMM_TN, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, gp); break;
   }
 }
 
-// Returns POPLAR_ERR_UNIMPLEMENTED (without touching the error text's meaning for callers) when the
-// shape is outside this kernel's preconditions; the caller then uses the register-staged kernel.
-int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) {
+// Checks one problem against the kernel's preconditions and fills its parameters (not the tiling).
+static int dtl_prepare(const GemmArgs& a, DtlGemmParams& p) {
   if (a.layout < GEMM_NT || a.layout > GEMM_TN) return POPLAR_ERR_UNIMPLEMENTED;
   // a K tail is fine when every operand reads zeros there: k-strided operands run out of range, a
   // k-contiguous A only if the caller vouches for zero padding up to the next multiple of 64
@@ -381,13 +396,30 @@ int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) {
   const int64_t lim = (int64_t)0xfffffff0u - 1024;
   if ((round_up(a_rows, 256) + 64) * a.lda * 2 + 1024 > lim || (round_up(b_rows, 256) + 64) * a.ldb * 2 + 1024 > lim)
     return POPLAR_ERR_UNIMPLEMENTED;
-
-  DtlGemmParams p;
   p.A = (const bf16*)a.A; p.B = (const bf16*)a.B; p.C = a.C;
   p.bias = (const bf16*)a.bias; p.residual = (const bf16*)a.residual; p.aux = (bf16*)a.aux;
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc; p.ldaux = a.ldaux;
   p.a_records = (uint32_t)a_bytes; p.b_records = (uint32_t)b_bytes;
   p.c_float = a.c_float; p.act = a.act; p.beta = a.beta;
+  return POPLAR_OK;
+}
+
+// Up to DTL_MAX_GROUP problems of one layout and one K in a single launch (a plain GEMM is a group of one).
+// Returns POPLAR_ERR_UNIMPLEMENTED, with nothing launched, when a problem is outside the kernel's
+// preconditions or the group is not uniform; the caller then runs the problems one by one.
+int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n) {
+  if (n < 1 || n > DTL_MAX_GROUP) return POPLAR_ERR_UNIMPLEMENTED;
+  DtlGroupParams gp;
+  bool plain = true;
+  double mn = 0.0;
+  for (int i = 0; i < n; ++i) {
+    if (a[i].layout != a[0].layout || a[i].K != a[0].K) return POPLAR_ERR_UNIMPLEMENTED;
+    const int st = dtl_prepare(a[i], gp.g[i]);
+    if (st != POPLAR_OK) return st;
+    plain = plain && a[i].c_float && !a[i].bias && !a[i].residual && a[i].act == ACT_NONE;
+    mn += (double)a[i].M * (double)a[i].N;
+  }
+  gp.n = n;
 
   // Tile shape and K split by a small cost model, in units of one K step of a 256x256 tile on its CU.
   // 256x256 and 256x192 tiles run one block per CU, 128x128 tiles two per CU (each step a quarter of the
@@ -398,47 +430,61 @@ int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) {
   // whatever the tile shape: that term is what keeps the split count low.
   struct TileCfg { int bm, bn; double slots, step, epi, epi_atomic; };
   static const TileCfg cfgs[3] = {{256, 256, 256.0, 1.0, 4.0, 6.0}, {256, 192, 256.0, 0.84, 3.0, 5.0}, {128, 128, 512.0, 0.6, 1.2, 2.0}};
-  const bool plain = a.c_float && !a.bias && !a.residual && a.act == ACT_NONE;
-  const int64_t ksteps = cdiv(a.K, DTL_BK);
+  const int64_t K = a[0].K, ksteps = cdiv(K, DTL_BK);
   int pick = 0, splits = 1;
   double best = 1e300;
   for (int cfg = 0; cfg < 3; ++cfg) {
     const TileCfg& tc = cfgs[cfg];
-    const int64_t t = cdiv(a.M, tc.bm) * cdiv(a.N, tc.bn);
+    int64_t t = 0;
+    for (int i = 0; i < n; ++i) t += cdiv(a[i].M, tc.bm) * cdiv(a[i].N, tc.bn);
     static const int cand[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16};
     for (int sp : cand) {
       if (sp > 1 && (!plain || ksteps / sp < 8)) break;
       const double rounds = ceil((double)(t * sp) / tc.slots);
       const double cost = rounds * ((double)cdiv(ksteps, sp) * tc.step + (sp > 1 ? tc.epi_atomic : tc.epi)) +
-                          (sp > 1 ? 3.0 + 2.7e-6 * (double)sp * (double)a.M * (double)a.N : 0.0);
+                          (sp > 1 ? 3.0 + 2.7e-6 * (double)sp * mn : 0.0);
       if (cost < best) { best = cost; pick = cfg; splits = sp; }
     }
   }
   const int BM = cfgs[pick].bm, BN = cfgs[pick].bn;
-  p.tiles_m = (int)cdiv(a.M, BM);
-  p.tiles_n = (int)cdiv(a.N, BN);
-  const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-  p.k_per_split = (int)round_up(cdiv(a.K, splits), DTL_BK);
-  splits = (int)cdiv(a.K, p.k_per_split);
+  const int k_per_split = (int)round_up(cdiv(K, splits), DTL_BK);
+  splits = (int)cdiv(K, k_per_split);
   const bool atomic = splits > 1;
-  if (atomic && a.beta == 0.f) {
-    if (a.ldc != a.N) {
-      for (int64_t m = 0; m < a.M; ++m) POPLAR_TRY(fill_zero(s, (float*)a.C + m * a.ldc, a.N * 4));
-    } else {
-      POPLAR_TRY(fill_zero(s, a.C, a.M * a.N * 4));
+  int64_t tiles = 0;
+  for (int i = 0; i < n; ++i) {
+    DtlGemmParams& p = gp.g[i];
+    p.tiles_m = (int)cdiv(a[i].M, BM);
+    p.tiles_n = (int)cdiv(a[i].N, BN);
+    p.k_per_split = k_per_split;
+    gp.start[i] = (int)tiles;
+    tiles += (int64_t)p.tiles_m * p.tiles_n;
+    if (tiles > 0x7fffffff) return POPLAR_ERR_UNIMPLEMENTED;
+  }
+  for (int i = n; i <= DTL_MAX_GROUP; ++i) gp.start[i] = (int)tiles;
+  for (int i = n; i < DTL_MAX_GROUP; ++i) gp.g[i] = gp.g[0];
+  if (atomic) {
+    for (int i = 0; i < n; ++i) {
+      if (a[i].beta != 0.f) continue;
+      if (a[i].ldc != a[i].N) {
+        for (int64_t m = 0; m < a[i].M; ++m) POPLAR_TRY(fill_zero(s, (float*)a[i].C + m * a[i].ldc, a[i].N * 4));
+      } else {
+        POPLAR_TRY(fill_zero(s, a[i].C, a[i].M * a[i].N * 4));
+      }
     }
   }
   dim3 grid((unsigned)tiles, (unsigned)splits);
   if (pick == 0) {
-    if (atomic) launch_dtl<2, 4, 4, 2, true>(s, a.layout, grid, p);
-    else launch_dtl<2, 4, 4, 2, false>(s, a.layout, grid, p);
+    if (atomic) launch_dtl<2, 4, 4, 2, true>(s, a[0].layout, grid, gp);
+    else launch_dtl<2, 4, 4, 2, false>(s, a[0].layout, grid, gp);
   } else if (pick == 1) {
-    if (atomic) launch_dtl<4, 2, 2, 3, true>(s, a.layout, grid, p);
-    else launch_dtl<4, 2, 2, 3, false>(s, a.layout, grid, p);
+    if (atomic) launch_dtl<4, 2, 2, 3, true>(s, a[0].layout, grid, gp);
+    else launch_dtl<4, 2, 2, 3, false>(s, a[0].layout, grid, gp);
   } else {
-    if (atomic) launch_dtl<2, 2, 2, 2, true>(s, a.layout, grid, p);
-    else launch_dtl<2, 2, 2, 2, false>(s, a.layout, grid, p);
+    if (atomic) launch_dtl<2, 2, 2, 2, true>(s, a[0].layout, grid, gp);
+    else launch_dtl<2, 2, 2, 2, false>(s, a[0].layout, grid, gp);
   }
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }
+
+int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a) { return gemm_bf16_dtl_group(s, &a, 1); }

@@ -38,6 +38,23 @@ static int gemm(poplar_ctx* ctx, const GemmArgs& a) {
   return t.end();
 }
 
+// Several independent GEMMs: one grouped launch where the direct-to-LDS kernel takes the group (the weight
+// gradients of a layer: too few tiles each to fill the chip, enough together), one launch each otherwise.
+static int gemm_group(poplar_ctx* ctx, const GemmArgs* a, int n) {
+  if (ctx->cfg.dtype == POPLAR_BF16 && n > 1) {
+    double flops = 0.0;
+    for (int i = 0; i < n; ++i) flops += 2.0 * (double)a[i].M * (double)a[i].N * (double)a[i].K;
+    LaunchTimer t{ctx};
+    POPLAR_TRY(t.begin(KIND_GEMM, flops));
+    const int r = gemm_bf16_dtl_group(ctx->stream, a, n);
+    if (r == POPLAR_OK) return t.end();
+    if (r != POPLAR_ERR_UNIMPLEMENTED) return r;
+    // nothing was launched: the pair of events recorded by begin() is simply not used
+  }
+  for (int i = 0; i < n; ++i) POPLAR_TRY(gemm(ctx, a[i]));
+  return POPLAR_OK;
+}
+
 // algorithmic attention flop: 2 S^2 H forward and 5 S^2 H backward per sample under a causal mask, twice that without
 static double attn_flops(const poplar_model_cfg& c, int B, double per_pair) {
   return per_pair * (c.causal ? 1.0 : 2.0) * (double)B * (double)c.seq * (double)c.seq * (double)c.hidden;
@@ -204,9 +221,13 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
 
   // MLP down projection: out = x1 + g W2^T + bm2
   if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, H, dy, H, G(lo.bm2), accumulate, scratch, scratch_n));
-  ga = gemm_args(GEMM_TN, H, F, T, dy, H, g, F, G(lo.w2), F);
-  ga.c_float = 1; ga.beta = beta;
-  POPLAR_TRY(gemm(ctx, ga));
+  // the four weight-gradient GEMMs are collected and run as one group at the end: their operands (dy, dh,
+  // dx1, dqkv and the stashed activations) all stay valid until then
+  GemmArgs dw[4];
+  dw[0] = gemm_args(GEMM_TN, H, F, T, dy, H, g, F, G(lo.w2), F);
+  dw[0].c_float = 1; dw[0].beta = beta;
+  const bool dy_is_dx = dy == dx;   // allowed by the interface: dy is then gone at the end, so its GEMM cannot wait
+  if (dy_is_dx) POPLAR_TRY(gemm(ctx, dw[0]));
   if (llama) {
     void* dg = ws + bp.dg;
     ga = gemm_args(GEMM_NN, T, F, H, dy, H, P(lo.w2), F, dg, F);
@@ -219,18 +240,14 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
     POPLAR_TRY(colsum(s, c.dtype, T, F, dh, F, G(lo.bm1), accumulate, scratch, scratch_n));
   }
   // MLP up projection
-  ga = gemm_args(GEMM_TN, hw, H, T, dh, hw, m, H, G(lo.w1), H);
-  ga.c_float = 1; ga.beta = beta;
-  POPLAR_TRY(gemm(ctx, ga));
+  dw[1] = gemm_args(GEMM_TN, hw, H, T, dh, hw, m, H, G(lo.w1), H);
   ga = gemm_args(GEMM_NN, T, H, hw, dh, hw, P(lo.w1), H, dm, H);
   POPLAR_TRY(gemm(ctx, ga));
   // second norm; dx1 = dy + norm_bwd(dm)
   POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, dm, x1, P(lo.g2), stats2, dy, dx1, G(lo.g2), G(lo.b2), accumulate, scratch, scratch_n, llama));
   // attention output projection: x1 = x + o Wo^T + bo
   if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, H, dx1, H, G(lo.bo), accumulate, scratch, scratch_n));
-  ga = gemm_args(GEMM_TN, H, H, T, dx1, H, o, H, G(lo.wo), H);
-  ga.c_float = 1; ga.beta = beta;
-  POPLAR_TRY(gemm(ctx, ga));
+  dw[2] = gemm_args(GEMM_TN, H, H, T, dx1, H, o, H, G(lo.wo), H);
   ga = gemm_args(GEMM_NN, T, H, H, dx1, H, P(lo.wo), H, dob, H);
   POPLAR_TRY(gemm(ctx, ga));
   // attention
@@ -238,14 +255,13 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
   if (llama) POPLAR_TRY(rope_inplace(s, c.dtype, B, c.seq, c.n_head, (int)(H / c.n_head), dqkv, 3 * H, -1.0f));
   // QKV projection
   if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, 3 * H, dqkv, 3 * H, G(lo.bqkv), accumulate, scratch, scratch_n));
-  ga = gemm_args(GEMM_TN, 3 * H, H, T, dqkv, 3 * H, a, H, G(lo.wqkv), H);
-  ga.c_float = 1; ga.beta = beta;
-  POPLAR_TRY(gemm(ctx, ga));
+  dw[3] = gemm_args(GEMM_TN, 3 * H, H, T, dqkv, 3 * H, a, H, G(lo.wqkv), H);
   ga = gemm_args(GEMM_NN, T, H, 3 * H, dqkv, 3 * H, P(lo.wqkv), H, da, H);
   POPLAR_TRY(gemm(ctx, ga));
   // first norm; dx = dx1 + norm_bwd(da)
   POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, da, x_in, P(lo.g1), stats1, dx1, dx, G(lo.g1), G(lo.b1), accumulate, scratch, scratch_n, llama));
-  return POPLAR_OK;
+  for (int i = 1; i < 4; ++i) { dw[i].c_float = 1; dw[i].beta = beta; }
+  return dy_is_dx ? gemm_group(ctx, dw + 1, 3) : gemm_group(ctx, dw, 4);
 }
 
 static int check_ctx_batch(poplar_ctx* ctx, int B) {
