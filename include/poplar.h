@@ -265,6 +265,23 @@ int poplar_set_kernel_timing(poplar_ctx* ctx, int32_t on);
  * or the bound workspace is too small. */
 int poplar_profile_step(poplar_ctx* ctx, int32_t stage, int32_t local_batch, poplar_profile* out);
 
+/* One optimizer step over an uneven run of micro-batches (Section "Optimal
+ * Batch Size Searching": a device that was given gmbs samples runs gas - 1
+ * micro-steps at its micro-batch size and a last one at lbs, Algorithm 2's
+ * outputs): micro-step k runs forward and backward on micro_batch[k] samples,
+ * the rows of the bound token buffer that follow those of micro-steps 0..k-1,
+ * with the loss weighted 1 / (loss_batch * seq) per token, and adds its
+ * gradients to those of the micro-steps before it (stage 0/1 in the flat
+ * gradient buffer, stage 2/3 in the shard buffer through the local reduce);
+ * Adam then runs once on the shard.  The result equals one step on the whole
+ * run when loss_batch is the sum of micro_batch (up to rounding order).
+ * micro_batch: host array of n_micro entries, each >= 1, their sum at most the
+ * bound max_batch.  out: sums of the micro-steps' times, flops and losses;
+ * batch = the sum; accounted_bytes = the largest micro-step's.  Errors as
+ * poplar_profile_step, checked for every micro-batch before anything runs. */
+int poplar_accum_step(poplar_ctx* ctx, int32_t stage, int32_t n_micro, const int32_t* micro_batch, int32_t loss_batch,
+                      poplar_profile* out);
+
 /* Algorithm 1 for this device: estimate mbs from the memory of one forward
  * pass at batch 1, run steps at 1, 2, 4, ... and then bisect to the largest
  * batch that fits.  samples: host array of max_samples entries, filled in call

@@ -70,7 +70,7 @@ EXPORTS = [
     "poplar_layer_fwd", "poplar_layer_bwd", "poplar_embed_fwd", "poplar_embed_bwd", "poplar_head_workspace_bytes",
     "poplar_head_loss_fwd_bwd", "poplar_adam_shard", "poplar_zero2_reduce_local", "poplar_zero3_gather_local",
     "poplar_bind_state", "poplar_step_workspace_bytes", "poplar_step_accounted_bytes", "poplar_profile_step",
-    "poplar_search_mbs", "poplar_speed_curve", "poplar_allocate", "poplar_set_kernel_timing",
+    "poplar_accum_step", "poplar_search_mbs", "poplar_speed_curve", "poplar_allocate", "poplar_set_kernel_timing",
     "poplar_gemm",
 ]
 
@@ -114,6 +114,7 @@ def _declare(L):
         "poplar_step_workspace_bytes": [cfgp, i32, i32, p64],
         "poplar_step_accounted_bytes": [cfgp, i32, i32, i32, p64],
         "poplar_profile_step": [vp, i32, i32, C.POINTER(Profile)],
+        "poplar_accum_step": [vp, i32, i32, C.POINTER(i32), i32, C.POINTER(Profile)],
         "poplar_search_mbs": [vp, i32, C.POINTER(i32), C.POINTER(Profile), i32, C.POINTER(i32)],
         "poplar_set_kernel_timing": [vp, i32],
         "poplar_gemm": [vp, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, f32],
@@ -322,6 +323,12 @@ class Context:
     def profile_step(self, stage, local_batch):
         out = Profile()
         _check(lib().poplar_profile_step(self._h, stage, local_batch, C.byref(out)))
+        return out.as_dict()
+
+    def accum_step(self, stage, micro_batches, loss_batch):
+        arr = (C.c_int32 * len(micro_batches))(*micro_batches)
+        out = Profile()
+        _check(lib().poplar_accum_step(self._h, stage, len(micro_batches), arr, loss_batch, C.byref(out)))
         return out.as_dict()
 
     def search_mbs(self, stage, max_samples=64):

@@ -157,7 +157,11 @@ static int span_seconds(const std::vector<Span>& v, double* out) {
   return POPLAR_OK;
 }
 
-static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_profile* out) {
+// How one pass of run_step sits in a gradient-accumulation run: which rows of the token buffer it reads, the
+// loss weight per token, whether its gradients add to what is there, whether the optimizer runs after it.
+struct MicroStep { int row0; float loss_scale; int accumulate; int optimizer; };
+
+static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_profile* out, const MicroStep* mstep = nullptr) {
   const poplar_model_cfg& c = ctx->cfg;
   const poplar_state& st = ctx->st;
   hipStream_t s = ctx->stream;
@@ -180,9 +184,11 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   float* staging_tail = staging ? staging + u.max_unit : nullptr;  // GPT: gf, bf gradients next to the tied wte bucket
   char* gbuf = sp.gather >= 0 ? ws + sp.gather : nullptr;
   const int64_t tok_ld = c.seq + 1;
-  const int32_t* tokens = st.tokens;
-  const int32_t* targets = st.tokens + 1;
-  const float loss_scale = 1.0f / (float)((double)B * c.seq);
+  const int32_t* tokens = st.tokens + (mstep ? (int64_t)mstep->row0 * tok_ld : 0);
+  const int32_t* targets = tokens + 1;
+  const float loss_scale = mstep ? mstep->loss_scale : 1.0f / (float)((double)B * c.seq);
+  const int acc = mstep ? mstep->accumulate : 0;          // gradients add to those already in st.grads
+  const bool optimizer = mstep ? mstep->optimizer != 0 : true;
 
   ctx->ev_next = 0;
   ctx->launches.clear();
@@ -247,16 +253,16 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
 
   if (!forward_only) {
     // ---------------- backward ----------------
-    if (stage >= 2) POPLAR_TRY(fill_zero(s, st.grads, sh_len * 4));
+    if (stage >= 2 && !acc) POPLAR_TRY(fill_zero(s, st.grads, sh_len * 4));
     if (stage >= 3) POPLAR_TRY(head_params(sp_gb));
     if (llama) {
       float* gt = unit_grads(u.tail_lo);  // tail unit: gf then Whead
-      POPLAR_TRY(head_bwd_part(ctx, B, X(c.n_layer), p_gf, p_whead, dx_cur, gt, nullptr, gt + (mo.whead - mo.gf), 0, shared));
+      POPLAR_TRY(head_bwd_part(ctx, B, X(c.n_layer), p_gf, p_whead, dx_cur, gt, nullptr, gt + (mo.whead - mo.gf), stage < 2 ? acc : 0, shared));
       POPLAR_TRY(reduce_unit(gt, u.tail_lo, u.P));
     } else {
       float* gt = stage >= 2 ? staging_tail : st.grads + u.tail_lo;
       float* ge = unit_grads(0);  // embedding unit: wte first
-      POPLAR_TRY(head_bwd_part(ctx, B, X(c.n_layer), p_gf, p_whead, dx_cur, gt, gt + H, ge, 0, shared));
+      POPLAR_TRY(head_bwd_part(ctx, B, X(c.n_layer), p_gf, p_whead, dx_cur, gt, gt + H, ge, stage < 2 ? acc : 0, shared));
       POPLAR_TRY(reduce_unit(gt, u.tail_lo, u.P));
       // the tied matrix's head term goes to the shard now, the embedding term at the end
       POPLAR_TRY(reduce_unit(ge, 0, (int64_t)c.vocab * H));
@@ -266,22 +272,24 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
       const int64_t lo = u.layer0 + (int64_t)l * u.lc;
       POPLAR_TRY(params_at(lo, lo + u.lc, gbuf, sp_gb, &p_l));
       float* gl = unit_grads(lo);
-      POPLAR_TRY(layer_bwd_impl(ctx, B, X(l), dx_cur, p_l, SV(l), dx_nxt, gl, 0, shared));
+      POPLAR_TRY(layer_bwd_impl(ctx, B, X(l), dx_cur, p_l, SV(l), dx_nxt, gl, stage < 2 ? acc : 0, shared));
       POPLAR_TRY(reduce_unit(gl, lo, lo + u.lc));
       std::swap(dx_cur, dx_nxt);
     }
     {
       float* ge = unit_grads(0);
       // stage 0/1 GPT: the head already wrote dwte, the embedding adds to it; everywhere else start from zero
-      if (stage >= 2 || llama) POPLAR_TRY(fill_zero(s, ge, (int64_t)c.vocab * H * 4));
-      POPLAR_TRY(embed_bwd(s, c.dtype, B, c.seq, (int)H, tokens, tok_ld, dx_cur, ge, llama ? nullptr : ge + mo.wpe, 0));
+      // (an accumulating pass at stage 0/1 adds to the earlier micro-steps' gradient instead)
+      if (stage >= 2 || (llama && !acc)) POPLAR_TRY(fill_zero(s, ge, (int64_t)c.vocab * H * 4));
+      POPLAR_TRY(embed_bwd(s, c.dtype, B, c.seq, (int)H, tokens, tok_ld, dx_cur, ge, llama ? nullptr : ge + mo.wpe, stage < 2 ? acc : 0));
       POPLAR_TRY(reduce_unit(ge, 0, u.emb_hi));
     }
     POPLAR_TRY(ev.mark(&e_bwd_end));
     // ---------------- optimizer on the shard ----------------
     const float* g_adam = stage >= 2 ? st.grads : st.grads + sh_off;
     void* lowp_dst = stage >= 3 ? st.own_shard : (char*)st.params + sh_off * es;
-    POPLAR_TRY(adam_shard(s, c.dtype, st.master, st.m, st.v, g_adam, lowp_dst, sh_valid, st.adam_t, st.lr, st.beta1, st.beta2, st.eps));
+    if (optimizer)
+      POPLAR_TRY(adam_shard(s, c.dtype, st.master, st.m, st.v, g_adam, lowp_dst, sh_valid, st.adam_t, st.lr, st.beta1, st.beta2, st.eps));
     POPLAR_TRY(ev.mark(&e_adam_end));
   }
   float loss_host = 0.f;
@@ -343,6 +351,44 @@ extern "C" int poplar_profile_step(poplar_ctx* ctx, int32_t stage, int32_t local
   if (!out) return poplar_fail(POPLAR_ERR_INVALID, "out is null");
   POPLAR_TRY(check_memory(ctx, stage, local_batch, 0));
   return run_step(ctx, stage, local_batch, 0, out);
+}
+
+extern "C" int poplar_accum_step(poplar_ctx* ctx, int32_t stage, int32_t n_micro, const int32_t* micro_batch, int32_t loss_batch,
+                                 poplar_profile* out) {
+  if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
+  if (n_micro < 1 || !micro_batch || !out) return poplar_fail(POPLAR_ERR_INVALID, "need n_micro >= 1, micro_batch and out");
+  if (loss_batch < 1) return poplar_fail(POPLAR_ERR_INVALID, "loss_batch must be >= 1, got %d", loss_batch);
+  int64_t rows = 0;
+  for (int k = 0; k < n_micro; ++k) {
+    POPLAR_TRY(check_step_args(ctx, stage, micro_batch[k]));
+    POPLAR_TRY(check_memory(ctx, stage, micro_batch[k], 0));
+    rows += micro_batch[k];
+  }
+  if (rows > ctx->st.max_batch)
+    return poplar_fail(POPLAR_ERR_INVALID, "micro-batches sum to %lld samples, the bound token buffer holds %d", (long long)rows, ctx->st.max_batch);
+  poplar_profile tot;
+  memset(&tot, 0, sizeof tot);
+  tot.stage = stage;
+  int row0 = 0;
+  for (int k = 0; k < n_micro; ++k) {
+    MicroStep ms;
+    ms.row0 = row0;
+    ms.loss_scale = 1.0f / (float)((double)loss_batch * ctx->cfg.seq);
+    ms.accumulate = k > 0;
+    ms.optimizer = k == n_micro - 1;
+    poplar_profile pr;
+    POPLAR_TRY(run_step(ctx, stage, micro_batch[k], 0, &pr, &ms));
+    row0 += micro_batch[k];
+    tot.batch += pr.batch;
+    tot.t_fwd += pr.t_fwd; tot.t_bwd += pr.t_bwd; tot.t_gather_fwd += pr.t_gather_fwd; tot.t_gather_bwd += pr.t_gather_bwd;
+    tot.t_reduce_bwd += pr.t_reduce_bwd; tot.t_consumed += pr.t_consumed; tot.flops += pr.flops; tot.loss += pr.loss;
+    tot.t_gemm += pr.t_gemm; tot.gemm_flops += pr.gemm_flops; tot.t_attn += pr.t_attn; tot.attn_flops += pr.attn_flops;
+    tot.n_gemm += pr.n_gemm; tot.n_attn += pr.n_attn;
+    if (pr.accounted_bytes > tot.accounted_bytes) tot.accounted_bytes = pr.accounted_bytes;
+    if (ms.optimizer) tot.t_adam = pr.t_adam;
+  }
+  *out = tot;
+  return POPLAR_OK;
 }
 
 extern "C" int poplar_search_mbs(poplar_ctx* ctx, int32_t stage, int32_t* mbs, poplar_profile* samples, int32_t max_samples,

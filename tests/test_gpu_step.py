@@ -180,3 +180,104 @@ def test_search_mbs_returns_zero_when_nothing_fits():
     rk = Rank(model, "bf16", 1, 4, 0, max_batch=4, cap_bytes=1000)
     mbs, samples = rk.ctx.search_mbs(1)
     assert mbs == 0 and samples == []
+
+
+# ---- gradient accumulation over uneven micro-batches (the gas / lbs outputs of Algorithm 2) ------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("stage", [0, 1, 2, 3])
+@pytest.mark.parametrize("arch", ["gpt", "llama"])
+def test_accum_step_equals_one_step_on_the_whole_run(arch, stage, dtype):
+    """gas - 1 micro-steps at b and a last one at lbs give the gradient, loss and update of one big batch."""
+    model, world, rank = MODELS[arch], 4, 2
+    micro = [2, 2, 1]                     # b = 2, gas = 3, lbs = 1
+    n = sum(micro)
+    rk = Rank(model, dtype, stage, world, rank, max_batch=n)
+    prof = rk.ctx.accum_step(stage, micro, n)
+    sync()
+    fq = quantize(rk.flat, dtype)
+    loss, grad, _ = otr.model_fwd_bwd(model, fq, rk.tok[:n], rk.tgt[:n], 1.0 / (n * model["S"]))
+    tol = TOL[dtype]
+    assert prof["batch"] == n
+    assert abs(prof["loss"] - loss) <= (5e-3 if dtype == "bf16" else 1e-5) * abs(loss)
+    got = to_np(rk.grads)
+    sl = slice(rk.off, rk.off + rk.valid)
+    if stage < 2:
+        table, _ = otr.offsets(rk.spec)
+        for name, (off, shape) in table.items():
+            k = int(np.prod(shape))
+            assert rel_l2(got[off:off + k], grad[off:off + k]) <= tol, name
+        g_used = got[sl]
+    else:
+        assert rel_l2(got[:rk.valid], grad[sl]) <= tol
+        assert np.all(got[rk.valid:] == 0)
+        g_used = got[:rk.valid]
+    # one optimizer step, taken on the accumulated gradient
+    p0 = rk.flat[sl].astype(np.float64)
+    z = np.zeros_like(p0)
+    rp, rm, rv = oopt.adam_step(p0, z, z, g_used, 1, **HP)
+    assert rel_l2(to_np(rk.master)[:rk.valid], rp) <= 1e-6
+    assert rel_l2(to_np(rk.m)[:rk.valid], rm) <= 1e-6
+    assert rel_l2(to_np(rk.v)[:rk.valid], rv) <= 1e-6
+    assert prof["t_adam"] > 0 and prof["t_fwd"] > 0 and prof["n_gemm"] == 0
+
+
+def test_accum_step_of_one_micro_batch_is_profile_step():
+    model = MODELS["gpt"]
+    # the last rank's shard holds no part of wte, whose gradient collects float atomics in free order:
+    # everything else is bit-equal
+    a = Rank(model, "f32", 1, 4, 3, max_batch=3)
+    b = Rank(model, "f32", 1, 4, 3, max_batch=3)
+    V, H = model["V"], model["H"]
+    assert a.off >= V * H
+    a.ctx.profile_step(1, 3)
+    b.ctx.accum_step(1, [3], 3)
+    sync()
+    assert torch.equal(a.master, b.master) and torch.equal(a.m, b.m) and torch.equal(a.v, b.v)
+    assert torch.equal(a.grads[V * H:], b.grads[V * H:])
+    assert rel_l2(to_np(a.grads[:V * H]), to_np(b.grads[:V * H])) <= 1e-6
+
+
+def test_allocation_is_executable_on_two_unequal_devices():
+    """Algorithm 2's output for a fast and a slow device, run as accumulation steps on each device's share of the
+    global batch; the two gradients together are the gradient of the global batch."""
+    model, gbs = MODELS["gpt"], 7
+    bs = [1, 2, 3, 4]
+    curves = [(bs, [0.010 * b + 0.004 for b in bs], 4), (bs, [0.021 * b + 0.006 for b in bs], 2)]
+    plan = pb.allocate(1, gbs, curves, 0.0)
+    ref = oal.allocate(1, gbs, curves, 0.0)
+    assert plan["gmbs"] == ref["gmbs"] and plan["b"] == ref["b"] and plan["lbs"] == ref["lbs"]
+    assert sum(plan["gmbs"]) == gbs and plan["gmbs"][0] > plan["gmbs"][1] > 0
+    tok, tgt = synth.tokens(gbs, model["S"], model["V"], seed=3)
+    flat = synth.init_params(otr.model_spec(model), seed=0, jitter=True)
+    total = np.zeros(len(flat), np.float64)
+    row = 0
+    for dev in range(2):
+        g, b = plan["gmbs"][dev], plan["b"][dev]
+        gas = -(-g // b)
+        micro = [b] * (gas - 1) + [g - (gas - 1) * b]
+        assert micro[-1] == plan["lbs"][dev] and all(1 <= x <= curves[dev][2] for x in micro)
+        rk = Rank(model, "f32", 0, 1, 0, max_batch=g)
+        both = np.concatenate([tok[row:row + g], tgt[row:row + g, -1:]], axis=1).astype(np.int32)
+        rk.tokens.copy_(torch.from_numpy(both))
+        rk.ctx.accum_step(0, micro, gbs)
+        sync()
+        total += to_np(rk.grads).astype(np.float64)
+        row += g
+    _, grad, _ = otr.model_fwd_bwd(model, flat, tok, tgt, 1.0 / (gbs * model["S"]))
+    assert rel_l2(total, grad) <= 5e-5
+
+
+def test_accum_step_errors():
+    model = MODELS["gpt"]
+    rk = Rank(model, "f32", 1, 4, 0, max_batch=4)
+    before = rk.master.clone()
+    with pytest.raises(pb.PoplarError):
+        rk.ctx.accum_step(1, [3, 2], 5)      # five rows, the token buffer holds four
+    with pytest.raises(pb.PoplarError):
+        rk.ctx.accum_step(1, [2, 0], 2)      # empty micro-batch
+    with pytest.raises(pb.PoplarError):
+        rk.ctx.accum_step(1, [], 1)
+    with pytest.raises(pb.PoplarError):
+        rk.ctx.accum_step(1, [2], 0)
+    sync()
+    assert torch.equal(before, rk.master)
