@@ -52,6 +52,46 @@ def cpu_baseline(model, flat, tok, tgt):
             "seconds": dt, "loss": float(loss)}
 
 
+def device_info(pb, torch):
+    """What the device reports, and the bf16 matrix-core peak that follows from it (4096 flop per clock per CU)."""
+    d = pb.device_info()
+    ghz = d["clock_khz"] / 1e6
+    return {"name": torch.cuda.get_device_properties(0).name, "compute_units": d["compute_units"], "clock_mhz": d["clock_khz"] / 1e3,
+            "bf16_peak_tflops_from_device": d["compute_units"] * 4096 * ghz / 1e3,
+            "bf16_peak_tflops_used": PEAK_BF16_TFLOPS, "hbm_gib": d["memory_bytes"] / 2**30}
+
+
+def curve_report(pb, ctx, P, max_b, reps=5):
+    """The paper's curve claim on this device (Appendix "Cubic Spline Interpolation": the curve through the
+    profiled points is almost the measured one): a dense sweep of TimeConsumedDuringStep over every batch,
+    the spline through the batches Algorithm 1 visits, its error at the batches it does not visit; then
+    Algorithm 2 at stages 2 and 3 on a four-device mix built from the measured curve (times x 1, 1.5, 2, 3),
+    with the communication time of the volume model over an xGMI mesh (7 links x 153 GB/s per device)."""
+    dense = {}
+    for b in range(1, max_b + 1):
+        ctx.profile_step(STAGE, b)
+        dense[b] = float(np.median([ctx.profile_step(STAGE, b)["t_consumed"] for _ in range(reps)]))
+    visited = sorted({1 << k for k in range(max_b.bit_length()) if (1 << k) <= max_b} | {max_b})
+    speed = pb.speed_curve(visited, [dense[b] for b in visited], max_b)
+    rel = {b: speed[b] * dense[b] / b - 1.0 for b in dense if b not in visited}
+    out = {"stage": STAGE, "batches": list(dense), "t_consumed_ms": [dense[b] * 1e3 for b in dense], "visited": visited,
+           "spline_rel_err_at_unvisited": {str(b): e for b, e in rel.items()},
+           "spline_max_abs_rel_err": max(abs(e) for e in rel.values()) if rel else 0.0,
+           "spline_mean_abs_rel_err": float(np.mean([abs(e) for e in rel.values()])) if rel else 0.0}
+    bs = list(dense)
+    curves = [(bs, [dense[b] * k for b in bs], max_b) for k in (1.0, 1.5, 2.0, 3.0)]
+    gbs, alloc = 256, {}
+    for stage in (2, 3):
+        cm = pb.comm_model(P, 4, stage, 2.0, 4.0, 7 * 153e9)
+        with_comm = pb.allocate(stage, gbs, curves, cm["t_micro"])
+        without = pb.allocate(stage, gbs, curves, 0.0)
+        alloc[str(stage)] = {"t_comm_ms": cm["t_micro"] * 1e3, "micro_bytes": cm["micro_bytes"],
+                             "b": with_comm["b"], "gas": with_comm["gas"], "T_ms": with_comm["T"] * 1e3,
+                             "b_no_comm": without["b"], "gas_no_comm": without["gas"], "T_no_comm_ms": without["T"] * 1e3}
+    out["allocate_gbs256_mix_1_1.5_2_3"] = alloc
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -60,6 +100,7 @@ def main():
     ap.add_argument("--batch", type=int, default=16, help="local batch of the headline number")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--curve-report", action="store_true", help="add the dense-sweep / spline / Algorithm 2 report to the line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one rank on ONE GPU (the ZeRO world is simulated by shard offsets); --gpus must be 1", file=sys.stderr)
@@ -135,6 +176,7 @@ def main():
         "adam": {"achieved": adam_gbs, "unit": "GB/s", "peak": PEAK_HBM_GBS, "frac": adam_gbs / PEAK_HBM_GBS,
                  "bytes_per_elem": 30, "elems": valid},
         "loss": profs[-1]["loss"],
+        "device": device_info(pb, torch),
     }
     if not args.no_sweep:
         sweep = []
@@ -144,6 +186,8 @@ def main():
                           "frac_mfma_peak": pr[0]["flops"] / d / 1e12 / PEAK_BF16_TFLOPS,
                           "t_consumed_ms": float(np.mean([p["t_consumed"] for p in pr])) * 1e3})
         out["sweep"] = sweep
+    if args.curve_report:
+        out["curve_report"] = curve_report(pb, ctx, P, max_b)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(model, flat, tok, tgt)
     print(json.dumps(out))

@@ -248,6 +248,12 @@ typedef struct poplar_profile {
   int32_t n_gemm, n_attn;       /* launches counted */
 } poplar_profile;
 
+/* What the current HIP device reports: compute units, the peak engine clock in
+ * kHz, bytes of device memory.  Measurement reads the matrix-core peak off
+ * these (4096 bf16 flop per clock per compute unit) next to the published
+ * figure.  Any pointer may be NULL. */
+int poplar_device_info(int32_t* compute_units, int32_t* clock_khz, int64_t* memory_bytes);
+
 /* Kernel-level timing inside poplar_profile_step (off by default).  The paper
  * records wall time per step because no single operation explains it (Section
  * "Time Consumed Estimation"); this switch adds the per-kernel view needed to
@@ -298,6 +304,20 @@ typedef struct poplar_curve {
   const double* time;     /* host [n_pts], TimeConsumedDuringStep at that batch, > 0 */
   int32_t mbs;            /* largest batch the device can run (0 = none) */
 } poplar_curve;
+
+/* Communication one device does at a ZeRO stage, and its time on a link of
+ * bytes_per_second per device (Appendix "Analysis of Experiments": a collective
+ * over P elements moves P elements to each of the d devices, which gives the
+ * 24 d h^2 of a feed-forward block at stage 3; Appendix "Details about ZeRO"
+ * for which collectives each stage runs).  Per micro-step: stage 2 the
+ * gradient reduce-scatter, stage 3 two parameter all-gathers and the
+ * reduce-scatter.  Per optimizer step: stage 0 the gradient all-reduce (twice
+ * P), stage 1 that and the parameter all-gather, stage 2 the parameter
+ * all-gather.  A world of one moves nothing.  t_micro is the
+ * time_communication Algorithm 2 adds to every accumulation step at stages 2
+ * and 3.  Host only; any output pointer may be NULL. */
+int poplar_comm_model(int64_t P, int32_t world, int32_t stage, double param_bytes, double grad_bytes, double bytes_per_second,
+                      double* micro_bytes, double* step_bytes, double* total_micro_elements, double* t_micro, double* t_step);
 
 /* Speed curve of one device (Section "Optimal Batch Size Searching"): speed
  * points batch/time, samples at equal batch averaged, natural cubic spline

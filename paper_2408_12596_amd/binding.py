@@ -70,7 +70,7 @@ EXPORTS = [
     "poplar_layer_fwd", "poplar_layer_bwd", "poplar_embed_fwd", "poplar_embed_bwd", "poplar_head_workspace_bytes",
     "poplar_head_loss_fwd_bwd", "poplar_adam_shard", "poplar_zero2_reduce_local", "poplar_zero3_gather_local",
     "poplar_bind_state", "poplar_step_workspace_bytes", "poplar_step_accounted_bytes", "poplar_profile_step",
-    "poplar_accum_step", "poplar_search_mbs", "poplar_speed_curve", "poplar_allocate", "poplar_set_kernel_timing",
+    "poplar_accum_step", "poplar_search_mbs", "poplar_comm_model", "poplar_speed_curve", "poplar_allocate", "poplar_set_kernel_timing", "poplar_device_info",
     "poplar_gemm",
 ]
 
@@ -117,7 +117,9 @@ def _declare(L):
         "poplar_accum_step": [vp, i32, i32, C.POINTER(i32), i32, C.POINTER(Profile)],
         "poplar_search_mbs": [vp, i32, C.POINTER(i32), C.POINTER(Profile), i32, C.POINTER(i32)],
         "poplar_set_kernel_timing": [vp, i32],
+        "poplar_device_info": [C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)],
         "poplar_gemm": [vp, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, f32],
+        "poplar_comm_model": [i64, i32, i32, f64, f64, f64] + [C.POINTER(f64)] * 5,
         "poplar_speed_curve": [C.POINTER(Curve), C.POINTER(f64)],
         "poplar_allocate": [i32, i32, C.POINTER(Curve), i64, f64, f64, C.POINTER(Alloc)],
     }
@@ -227,6 +229,19 @@ def step_workspace_bytes(cfg, stage, B):
 
 def step_accounted_bytes(cfg, stage, B, forward_only=False):
     return _bytes_query(lib().poplar_step_accounted_bytes, cfg, stage, B, int(forward_only))
+
+
+def device_info():
+    cu, khz, mem = C.c_int32(), C.c_int32(), C.c_int64()
+    _check(lib().poplar_device_info(C.byref(cu), C.byref(khz), C.byref(mem)))
+    return dict(compute_units=cu.value, clock_khz=khz.value, memory_bytes=mem.value)
+
+
+def comm_model(P, world, stage, param_bytes, grad_bytes, bytes_per_second):
+    out = [C.c_double() for _ in range(5)]
+    _check(lib().poplar_comm_model(P, world, stage, param_bytes, grad_bytes, bytes_per_second, *[C.byref(x) for x in out]))
+    keys = ("micro_bytes", "step_bytes", "total_micro_elements", "t_micro", "t_step")
+    return {k: x.value for k, x in zip(keys, out)}
 
 
 def speed_curve(batches, times, mbs):

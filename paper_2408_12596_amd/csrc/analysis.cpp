@@ -88,6 +88,33 @@ void build_time(const std::vector<double>& speed, std::vector<double>& tm) {
 
 }  // namespace
 
+// Communication volume per device and its time on a given link (Appendix "Analysis of Experiments",
+// Appendix "Details about ZeRO"): a collective over P elements moves P elements per device.
+extern "C" int poplar_comm_model(int64_t P, int32_t world, int32_t stage, double param_bytes, double grad_bytes,
+                                 double bytes_per_second, double* micro_bytes, double* step_bytes, double* total_micro_elements,
+                                 double* t_micro, double* t_step) {
+  if (P < 0 || world < 1 || stage < 0 || stage > 3) return poplar_fail(POPLAR_ERR_INVALID, "need P >= 0, world >= 1, stage 0..3");
+  if (!(param_bytes > 0.0) || !(grad_bytes > 0.0) || !(bytes_per_second > 0.0))
+    return poplar_fail(POPLAR_ERR_INVALID, "element sizes and bandwidth must be positive");
+  int64_t mp = 0, mg = 0, sp = 0, sg = 0;   // elements per micro-step / per step, parameters / gradients
+  if (world > 1) {
+    switch (stage) {
+      case 0: sg = 2 * P; break;
+      case 1: sp = P; sg = 2 * P; break;
+      case 2: mg = P; sp = P; break;
+      default: mp = 2 * P; mg = P; break;
+    }
+  }
+  const double mb = (double)mp * param_bytes + (double)mg * grad_bytes;
+  const double sb = (double)sp * param_bytes + (double)sg * grad_bytes;
+  if (micro_bytes) *micro_bytes = mb;
+  if (step_bytes) *step_bytes = sb;
+  if (total_micro_elements) *total_micro_elements = (double)((mp + mg) * (int64_t)world);
+  if (t_micro) *t_micro = mb / bytes_per_second;
+  if (t_step) *t_step = sb / bytes_per_second;
+  return POPLAR_OK;
+}
+
 extern "C" int poplar_speed_curve(const poplar_curve* curve, double* speed) {
   POPLAR_TRY(check_curve(curve));
   if (!speed) return poplar_fail(POPLAR_ERR_INVALID, "speed is null");

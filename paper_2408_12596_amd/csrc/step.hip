@@ -138,6 +138,25 @@ struct EventCursor {
   int mark(hipEvent_t* e) { return ctx_mark(ctx, e); }
 };
 
+extern "C" int poplar_device_info(int32_t* compute_units, int32_t* clock_khz, int64_t* memory_bytes) {
+  int dev = 0, v = 0;
+  POPLAR_CHECK_HIP(hipGetDevice(&dev));
+  if (compute_units) {
+    POPLAR_CHECK_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+    *compute_units = v;
+  }
+  if (clock_khz) {
+    POPLAR_CHECK_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeClockRate, dev));
+    *clock_khz = v;
+  }
+  if (memory_bytes) {
+    size_t free_b = 0, total_b = 0;
+    POPLAR_CHECK_HIP(hipMemGetInfo(&free_b, &total_b));
+    *memory_bytes = (int64_t)total_b;
+  }
+  return POPLAR_OK;
+}
+
 extern "C" int poplar_set_kernel_timing(poplar_ctx* ctx, int32_t on) {
   if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
   ctx->kernel_timing = on != 0;
