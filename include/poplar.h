@@ -167,7 +167,10 @@ int poplar_head_workspace_bytes(const poplar_model_cfg* cfg, int32_t B, int64_t*
  * loss_scale is explicit because ranks with unequal local batches must all use
  * 1 / (global tokens) for the summed gradient to be the global mean (the paper
  * keeps the global batch fixed and the local batch dynamic, Section "Offline
- * Analyzing of Configuration").  targets: device int32 [B*S]. */
+ * Analyzing of Configuration").  targets: device int32 [B*S], each in [0, V), or
+ * negative for a position that is not predicted (a masked-language-model
+ * batch scores only its masked positions): such a position adds nothing to
+ * the loss and its gradient is zero. */
 int poplar_head_loss_fwd_bwd(poplar_ctx* ctx, int32_t B, const void* x, const int32_t* targets,
                              const void* gf, const void* bf, const void* whead, float loss_scale,
                              float* loss, void* dx, float* d_gf, float* d_bf, float* d_whead,
@@ -219,6 +222,8 @@ typedef struct poplar_state {
   float*   loss;         /* device float scalar */
   int32_t  adam_t;       /* step counter passed to Adam */
   float    lr, beta1, beta2, eps;
+  const int32_t* targets; /* NULL: next-token targets tokens[:, 1:].  Else int32 [max_batch, S] targets of their own
+                             (negative = position not predicted), e.g. the masked positions of a bidirectional model */
 } poplar_state;
 
 int poplar_bind_state(poplar_ctx* ctx, const poplar_state* st);

@@ -297,14 +297,21 @@ def embed_bwd(arch, dx, tok, V, S):
 
 
 def xent_fwd_bwd(logits, targets, loss_scale):
-    """logits [T, V], targets [T].  loss = loss_scale * sum_t CE_t."""
+    """logits [T, V], targets [T].  loss = loss_scale * sum_t CE_t over the positions
+    whose target is >= 0; a negative target marks a position that is not predicted
+    (a masked-language-model batch scores only its masked positions): no loss, zero
+    gradient."""
+    targets = np.asarray(targets)
     z = logits - logits.max(-1, keepdims=True)
     lse = np.log(np.exp(z).sum(-1, keepdims=True))
     logp = z - lse
     T = logits.shape[0]
-    loss = -loss_scale * logp[np.arange(T), targets].sum()
+    use = targets >= 0
+    rows = np.arange(T)[use]
+    loss = -loss_scale * logp[rows, targets[use]].sum()
     dlogits = np.exp(logp)
-    dlogits[np.arange(T), targets] -= 1.0
+    dlogits[rows, targets[use]] -= 1.0
+    dlogits[~use] = 0.0
     return loss, dlogits * loss_scale
 
 

@@ -41,7 +41,8 @@ class State(C.Structure):
     _fields_ = [("params", C.c_void_p), ("own_shard", C.c_void_p), ("master", C.c_void_p), ("m", C.c_void_p),
                 ("v", C.c_void_p), ("grads", C.c_void_p), ("tokens", C.c_void_p), ("max_batch", C.c_int32),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64), ("loss", C.c_void_p),
-                ("adam_t", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
+                ("adam_t", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("targets", C.c_void_p)]
 
 
 class Profile(C.Structure):
@@ -326,11 +327,11 @@ class Context:
                                                C.c_int64(shard_off), C.c_int64(shard_len)))
 
     def bind_state(self, params, master, m, v, grads, tokens, max_batch, workspace, workspace_bytes, loss,
-                   own_shard=None, adam_t=1, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8):
+                   own_shard=None, adam_t=1, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, targets=None):
         st = State(_ptr(params), _ptr(own_shard), _ptr(master), _ptr(m), _ptr(v), _ptr(grads), _ptr(tokens), max_batch,
-                   _ptr(workspace), workspace_bytes, _ptr(loss), adam_t, lr, beta1, beta2, eps)
+                   _ptr(workspace), workspace_bytes, _ptr(loss), adam_t, lr, beta1, beta2, eps, _ptr(targets))
         _check(lib().poplar_bind_state(self._h, C.byref(st)))
-        self._state_refs = (params, master, m, v, grads, tokens, workspace, loss, own_shard)  # keep the tensors alive
+        self._state_refs = (params, master, m, v, grads, tokens, workspace, loss, own_shard, targets)  # keep the tensors alive
 
     def set_kernel_timing(self, on):
         _check(lib().poplar_set_kernel_timing(self._h, int(on)))

@@ -674,7 +674,9 @@ int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok,
 // Softmax cross-entropy over logits [T, ld] (V valid columns), in place:
 // logits <- loss_scale * (softmax - onehot(target)), columns V..ld-1 <- 0;
 // row_loss[t] = logsumexp - logit[target].  One block per row, two passes over
-// the row (online max / sum first, gradient second).
+// the row (online max / sum first, gradient second).  A negative target marks a
+// position without a prediction (masked-language-model batches): its row of
+// the gradient is zero and it adds nothing to the loss.
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(256) xent_kernel(T* __restrict__ logits, int64_t ld, int V, const int32_t* __restrict__ targets,
@@ -683,6 +685,17 @@ __global__ void __launch_bounds__(256) xent_kernel(T* __restrict__ logits, int64
   const int64_t t = blockIdx.x;
   T* row = logits + t * ld;
   const int nvec = (int)(ld / VN);
+  const int tgt = targets[(t / S) * tgt_ld + (t % S)];
+  if (tgt < 0) {   // a position that is not predicted: no loss, zero gradient
+    Vec<T> z;
+    float f[VN];
+#pragma unroll
+    for (int k = 0; k < VN; ++k) f[k] = 0.f;
+    z.pack(f);
+    for (int i = threadIdx.x; i < nvec; i += 256) z.store(row + i * VN);
+    if (threadIdx.x == 0) row_loss[t] = 0.f;
+    return;
+  }
   float mx = -INFINITY, sum = 0.f;
   for (int i = threadIdx.x; i < nvec; i += 256) {
     float f[VN];
@@ -706,7 +719,6 @@ __global__ void __launch_bounds__(256) xent_kernel(T* __restrict__ logits, int64
 #pragma unroll
   for (int w = 0; w < 4; ++w) bs += (smx[w] == -INFINITY) ? 0.f : ssum[w] * __expf(smx[w] - bm);
   const float lse = bm + logf(bs);
-  const int tgt = targets[(t / S) * tgt_ld + (t % S)];
   if (threadIdx.x == 0) row_loss[t] = lse - to_float<T>(row[tgt]);
   __syncthreads();  // the target logit is read before anyone overwrites it
   for (int i = threadIdx.x; i < nvec; i += 256) {

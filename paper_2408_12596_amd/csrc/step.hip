@@ -204,7 +204,9 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   char* gbuf = sp.gather >= 0 ? ws + sp.gather : nullptr;
   const int64_t tok_ld = c.seq + 1;
   const int32_t* tokens = st.tokens + (mstep ? (int64_t)mstep->row0 * tok_ld : 0);
-  const int32_t* targets = tokens + 1;
+  // next-token targets out of the token rows, or the caller's own target rows (masked-language-model batches)
+  const int32_t* targets = st.targets ? st.targets + (mstep ? (int64_t)mstep->row0 * c.seq : 0) : tokens + 1;
+  const int64_t tgt_ld = st.targets ? c.seq : tok_ld;
   const float loss_scale = mstep ? mstep->loss_scale : 1.0f / (float)((double)B * c.seq);
   const int acc = mstep ? mstep->accumulate : 0;          // gradients add to those already in st.grads
   const bool optimizer = mstep ? mstep->optimizer != 0 : true;
@@ -267,7 +269,7 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   POPLAR_TRY(head_params(sp_gf));
   const void* p_gf = p_tail;
   const void* p_bf = llama ? nullptr : (const char*)p_tail + H * es;
-  POPLAR_TRY(head_fwd_part(ctx, B, X(c.n_layer), targets, tok_ld, p_gf, p_bf, p_whead, loss_scale, st.loss, shared));
+  POPLAR_TRY(head_fwd_part(ctx, B, X(c.n_layer), targets, tgt_ld, p_gf, p_bf, p_whead, loss_scale, st.loss, shared));
   POPLAR_TRY(ev.mark(&e_mid));
 
   if (!forward_only) {

@@ -153,3 +153,76 @@ def test_head_loss_fwd_bwd(arch, V, dtype):
     assert rel_l2(to_np(d_dx), r_dx) <= tol
     assert rel_l2(to_np(d_gf), r_dg) <= tol
     assert rel_l2(to_np(d_wh), r_dwh) <= tol
+
+
+# ---- bidirectional attention and a masked-language-model loss (the BERT-shaped workload) ---------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("S", [128, 200])
+def test_layer_without_causal_mask_matches_oracle(S, dtype):
+    case = dict(arch="gpt", L=1, H=256, nh=4, F=512, S=S, V=64, B=2)
+    B, H, nh = case["B"], case["H"], case["nh"]
+    cfg = pb.make_cfg(**{k: case[k] for k in ("arch", "L", "H", "nh", "F", "S", "V")}, dtype=dtype, causal=False)
+    ctx = pb.Context(cfg)
+    spec, flat, x, dy = layer_inputs(case, dtype, seed=4)
+    n = len(flat)
+    d_params, d_x, d_dy = to_dev(flat, dtype), to_dev(x, dtype), to_dev(dy, dtype)
+    d_out, d_dx = torch.empty_like(d_x), torch.empty_like(d_x)
+    saved = scratch(pb.layer_saved_bytes(cfg, B))
+    wsb = pb.layer_workspace_bytes(cfg, B)
+    ws = scratch(wsb)
+    grads = torch.full((n,), float("nan"), device=DEV)
+    ctx.layer_fwd(B, d_x, d_params, d_out, saved)
+    ctx.layer_bwd(B, d_x, d_dy, d_params, saved, d_dx, grads, 0, ws, wsb)
+    sync()
+    p = {k[3:]: v for k, v in otr.unpack(quantize(flat, dtype), spec).items()}
+    ref_out, cache = otr.layer_fwd("gpt", p, quantize(x, dtype), nh, causal=False)
+    ref_dx, ref_g = otr.layer_bwd("gpt", p, quantize(dy, dtype), cache, nh)
+    tol = TOL[dtype]
+    assert rel_l2(to_np(d_out), ref_out) <= tol
+    assert rel_l2(to_np(d_dx), ref_dx) <= tol
+    # the mask matters: the attention weights' gradient under the causal mask is far from this one (the layer
+    # output itself is dominated by the residual stream and would not tell the two apart at the bf16 tolerance)
+    _, cache_c = otr.layer_fwd("gpt", p, quantize(x, dtype), nh, causal=True)
+    _, ref_g_c = otr.layer_bwd("gpt", p, quantize(dy, dtype), cache_c, nh)
+    assert rel_l2(ref_g["Wqkv"], ref_g_c["Wqkv"]) > 10 * tol
+    table, _ = otr.offsets(spec)
+    got = to_np(grads)
+    for name, (off, shape) in table.items():
+        k = int(np.prod(shape))
+        assert rel_l2(got[off:off + k], ref_g[name[3:]]) <= tol, name
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_head_loss_scores_only_positions_with_a_target(dtype):
+    B, S, H, V = 2, 48, 128, 211
+    cfg = pb.make_cfg(arch="gpt", L=1, H=H, nh=2, F=128, S=S, V=V, dtype=dtype, causal=False)
+    ctx = pb.Context(cfg)
+    rng = np.random.default_rng(3)
+    x = synth.activations((B, S, H), seed=6)
+    gf = (1 + 0.1 * rng.standard_normal(H)).astype(np.float32)
+    bf = (0.1 * rng.standard_normal(H)).astype(np.float32)
+    wh = (rng.standard_normal((V, H)) * 0.1).astype(np.float32)
+    _, tgt = synth.tokens(B, S, V, seed=2)
+    tgt = np.where(rng.random((B, S)) < 0.15, tgt, -1).astype(np.int32)     # 15 % of the positions are scored
+    assert 0 < (tgt >= 0).sum() < B * S
+    scale = 1.0 / (tgt >= 0).sum()
+    loss = torch.zeros(1, device=DEV)
+    d_dx = torch.empty((B, S, H), dtype=tdtype(dtype), device=DEV)
+    d_gf, d_bf = torch.full((H,), float("nan"), device=DEV), torch.full((H,), float("nan"), device=DEV)
+    d_wh = torch.full((V, H), float("nan"), device=DEV)
+    wsb = pb.head_workspace_bytes(cfg, B)
+    ws = scratch(wsb)
+    ctx.head_loss_fwd_bwd(B, to_dev(x, dtype), to_dev(tgt.reshape(-1)), to_dev(gf, dtype), to_dev(bf, dtype), to_dev(wh, dtype), scale,
+                          loss, d_dx, d_gf, d_bf, d_wh, 0, ws, wsb)
+    sync()
+    xq, gq, bq, wq = quantize(x, dtype), quantize(gf, dtype), quantize(bf, dtype), quantize(wh, dtype)
+    hf, nc = otr.layernorm_fwd(xq, gq, bq)
+    logits = hf.reshape(-1, H) @ wq.T
+    r_loss, dlog = otr.xent_fwd_bwd(logits, tgt.reshape(-1), scale)
+    r_dwh = dlog.T @ hf.reshape(-1, H)
+    r_dx, r_dg, r_db = otr.layernorm_bwd((dlog @ wq).reshape(hf.shape), gq, nc)
+    tol = TOL[dtype]
+    assert abs(loss.item() - r_loss) <= (5e-3 if dtype == "bf16" else 1e-5) * abs(r_loss)
+    assert rel_l2(to_np(d_dx), r_dx) <= tol
+    assert rel_l2(to_np(d_gf), r_dg) <= tol and rel_l2(to_np(d_bf), r_db) <= tol
+    assert rel_l2(to_np(d_wh), r_dwh) <= tol

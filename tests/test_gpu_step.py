@@ -281,3 +281,36 @@ def test_accum_step_errors():
         rk.ctx.accum_step(1, [2], 0)
     sync()
     assert torch.equal(before, rk.master)
+
+
+# ---- a bidirectional model with a masked-language-model loss (the BERT-shaped workload) ----------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("stage", [1, 3])
+def test_bidirectional_masked_lm_step_matches_oracle(stage, dtype):
+    model, B, world, rank = MODELS["gpt"], 3, 4, 1
+    rk = Rank(model, dtype, stage, world, rank, max_batch=B)
+    cfg = pb.make_cfg(**model, dtype=dtype, world=world, rank=rank, zero_stage=stage, causal=False)
+    ctx = pb.Context(cfg)
+    rng = np.random.default_rng(5)
+    tgt = np.where(rng.random((B, model["S"])) < 0.15, rk.tgt[:B], -1).astype(np.int32)
+    n_scored = int((tgt >= 0).sum())
+    assert 0 < n_scored < B * model["S"]
+    d_tgt = to_dev(tgt)
+    ctx.bind_state(rk.params, rk.master, rk.m, rk.v, rk.grads, rk.tokens, B, rk.ws, rk.wsb, rk.loss, own_shard=rk.own,
+                   adam_t=1, lr=HP["lr"], beta1=HP["b1"], beta2=HP["b2"], eps=HP["eps"], targets=d_tgt)
+    prof = ctx.profile_step(stage, B)
+    sync()
+    # profile_step weights every token by 1 / (B S), scored or not
+    scale = 1.0 / (B * model["S"])
+    loss, grad, _ = otr.model_fwd_bwd(model, quantize(rk.flat, dtype), rk.tok[:B], tgt, scale, causal=False)
+    assert abs(prof["loss"] - loss) <= (5e-3 if dtype == "bf16" else 1e-5) * abs(loss)
+    got = to_np(rk.grads)
+    sl = slice(rk.off, rk.off + rk.valid)
+    ref = grad if stage < 2 else grad[sl]
+    got = got if stage < 2 else got[:rk.valid]
+    assert rel_l2(got, ref) <= TOL[dtype]
+    # without the mask the gradient is a different one
+    _, grad_c, _ = otr.model_fwd_bwd(model, quantize(rk.flat, dtype), rk.tok[:B], tgt, scale, causal=True)
+    assert rel_l2(grad_c if stage < 2 else grad_c[sl], ref) > 10 * TOL[dtype]
+    assert prof["flops"] == B * (model["L"] * (6 * model["S"] * (4 * model["H"] ** 2 + 2 * model["H"] * model["F"])
+                                               + 14 * model["S"] ** 2 * model["H"]) + 6 * model["S"] * model["H"] * model["V"])

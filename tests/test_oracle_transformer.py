@@ -212,6 +212,31 @@ def test_cross_entropy_closed_forms():
     np.testing.assert_allclose(dl.sum(-1), 0.0, atol=1e-15)
 
 
+def test_cross_entropy_skips_positions_without_a_target():
+    """Negative targets: against torch's ignore_index (loss and its autograd gradient), and by restriction
+    to the scored rows."""
+    rng = np.random.default_rng(11)
+    T, V = 9, 17
+    lg = rng.standard_normal((T, V)) * 2
+    tgt = rng.integers(0, V, T)
+    tgt[[1, 4, 5]] = -1
+    loss, dl = tr.xent_fwd_bwd(lg, tgt, 0.25)
+    tl = torch.tensor(lg, requires_grad=True)
+    tt = torch.tensor(np.where(tgt < 0, -100, tgt))
+    ref = 0.25 * F.cross_entropy(tl, tt, ignore_index=-100, reduction="sum")
+    ref.backward()
+    assert abs(loss - ref.item()) < 1e-12
+    np.testing.assert_allclose(dl, tl.grad.numpy(), atol=1e-14)
+    assert np.all(dl[[1, 4, 5]] == 0)
+    keep = tgt >= 0
+    loss_k, dl_k = tr.xent_fwd_bwd(lg[keep], tgt[keep], 0.25)
+    assert abs(loss - loss_k) < 1e-13
+    np.testing.assert_array_equal(dl[keep], dl_k)
+    # nothing scored: zero loss, zero gradient
+    loss0, dl0 = tr.xent_fwd_bwd(lg, np.full(T, -1), 1.0)
+    assert loss0 == 0 and not dl0.any()
+
+
 def test_gelu_and_silu_values():
     # tanh-form GeLU at 1: 0.5*(1+tanh(sqrt(2/pi)*1.044715))
     assert abs(tr.gelu_fwd(np.array(1.0)) - 0.8411919906082768) < 1e-15
