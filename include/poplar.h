@@ -72,6 +72,9 @@ typedef struct poplar_model_cfg {
   int32_t zero_stage;  /* 0..3, default stage of the context */
   int32_t causal;      /* 1: causal mask (decoder) */
   int64_t cap_bytes;   /* emulated device memory in bytes, 0 = no cap */
+  int32_t checkpoint;  /* 1: whole steps keep one activation stash instead of L and run every layer's forward pass
+                          again inside the backward pass (a memory-for-compute knob next to the ZeRO stage: Section
+                          "Heterogeneity Aware" only asks for the largest batch that fits) */
 } poplar_model_cfg;
 
 typedef struct poplar_ctx poplar_ctx;
@@ -300,6 +303,15 @@ int poplar_accum_step(poplar_ctx* ctx, int32_t stage, int32_t n_micro, const int
  * batch 1 does not fit at this stage. */
 int poplar_search_mbs(poplar_ctx* ctx, int32_t stage, int32_t* mbs,
                       poplar_profile* samples, int32_t max_samples, int32_t* n_samples);
+
+/* Section "Heterogeneity Aware": when not even one sample fits at a ZeRO stage,
+ * the search moves to the next stage, which holds less model state per device.
+ * Runs poplar_search_mbs at first_stage, first_stage + 1, ... 3 and stops at the
+ * first stage whose mbs is positive: *stage is that stage (-1 if none fits),
+ * *mbs and the samples are that stage's.  The bound state must serve every
+ * stage tried (gradient buffer of P floats, own_shard for stage 3). */
+int poplar_search_stage(poplar_ctx* ctx, int32_t first_stage, int32_t* stage, int32_t* mbs,
+                        poplar_profile* samples, int32_t max_samples, int32_t* n_samples);
 
 /* ---- offline analysis (host only, double precision, deterministic) --------- */
 

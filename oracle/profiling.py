@@ -76,3 +76,15 @@ def search_mbs(bytes_now, forward, step, total_memory):
         samples.append((mid, t))
         lo = mid
     return lo, samples
+
+
+def search_stage(first_stage, search):
+    """Section "Heterogeneity Aware": a stage at which not even one sample fits
+    (mbs = 0) is given up for the next one.  search(stage) -> (mbs, samples).
+    Returns (stage, mbs, samples) of the first stage >= first_stage with
+    mbs > 0, or (-1, 0, []) when none has."""
+    for stage in range(first_stage, 4):
+        mbs, samples = search(stage)
+        if mbs > 0:
+            return stage, mbs, samples
+    return -1, 0, []

@@ -34,7 +34,7 @@ class ModelCfg(C.Structure):
     _fields_ = [("arch", C.c_int32), ("n_layer", C.c_int32), ("hidden", C.c_int32), ("n_head", C.c_int32),
                 ("ffn", C.c_int32), ("seq", C.c_int32), ("vocab", C.c_int32), ("dtype", C.c_int32),
                 ("world", C.c_int32), ("rank", C.c_int32), ("zero_stage", C.c_int32), ("causal", C.c_int32),
-                ("cap_bytes", C.c_int64)]
+                ("cap_bytes", C.c_int64), ("checkpoint", C.c_int32)]
 
 
 class State(C.Structure):
@@ -71,7 +71,7 @@ EXPORTS = [
     "poplar_layer_fwd", "poplar_layer_bwd", "poplar_embed_fwd", "poplar_embed_bwd", "poplar_head_workspace_bytes",
     "poplar_head_loss_fwd_bwd", "poplar_adam_shard", "poplar_zero2_reduce_local", "poplar_zero3_gather_local",
     "poplar_bind_state", "poplar_step_workspace_bytes", "poplar_step_accounted_bytes", "poplar_profile_step",
-    "poplar_accum_step", "poplar_search_mbs", "poplar_comm_model", "poplar_speed_curve", "poplar_allocate", "poplar_set_kernel_timing", "poplar_device_info",
+    "poplar_accum_step", "poplar_search_mbs", "poplar_search_stage", "poplar_comm_model", "poplar_speed_curve", "poplar_allocate", "poplar_set_kernel_timing", "poplar_device_info",
     "poplar_gemm",
 ]
 
@@ -117,6 +117,7 @@ def _declare(L):
         "poplar_profile_step": [vp, i32, i32, C.POINTER(Profile)],
         "poplar_accum_step": [vp, i32, i32, C.POINTER(i32), i32, C.POINTER(Profile)],
         "poplar_search_mbs": [vp, i32, C.POINTER(i32), C.POINTER(Profile), i32, C.POINTER(i32)],
+        "poplar_search_stage": [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(Profile), i32, C.POINTER(i32)],
         "poplar_set_kernel_timing": [vp, i32],
         "poplar_device_info": [C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)],
         "poplar_gemm": [vp, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, f32],
@@ -148,9 +149,9 @@ def _ptr(t):
 
 
 def make_cfg(arch="gpt", L=1, H=256, nh=4, F=1024, S=128, V=1, dtype="bf16", world=1, rank=0, zero_stage=1,
-             causal=True, cap_bytes=0):
+             causal=True, cap_bytes=0, checkpoint=False):
     return ModelCfg(ARCH_GPT if arch == "gpt" else ARCH_LLAMA, L, H, nh, F, S, V, BF16 if dtype == "bf16" else F32,
-                    world, rank, zero_stage, int(causal), cap_bytes)
+                    world, rank, zero_stage, int(causal), cap_bytes, int(checkpoint))
 
 
 # ---- host-only queries --------------------------------------------------------
@@ -346,6 +347,12 @@ class Context:
         out = Profile()
         _check(lib().poplar_accum_step(self._h, stage, len(micro_batches), arr, loss_batch, C.byref(out)))
         return out.as_dict()
+
+    def search_stage(self, first_stage, max_samples=64):
+        stage, mbs, n = C.c_int32(), C.c_int32(), C.c_int32()
+        arr = (Profile * max_samples)()
+        _check(lib().poplar_search_stage(self._h, first_stage, C.byref(stage), C.byref(mbs), arr, max_samples, C.byref(n)))
+        return stage.value, mbs.value, [arr[i].as_dict() for i in range(n.value)]
 
     def search_mbs(self, stage, max_samples=64):
         mbs, n = C.c_int32(), C.c_int32()

@@ -67,7 +67,7 @@ static StepPlan step_plan(const poplar_model_cfg& c, int stage, int B) {
   auto take = [&](int64_t bytes) { int64_t r = at; at += round_up(bytes, 256); return r; };
   p.xs = take((int64_t)(c.n_layer + 1) * round_up(T * H * es, 256));
   p.saved_each = saved_plan(c, B).bytes;
-  p.saved = take(p.saved_each * c.n_layer);
+  p.saved = take(p.saved_each * (c.checkpoint ? 1 : c.n_layer));
   p.shared = take(std::max(head_plan(c, B).bytes, bwd_plan(c, B).bytes));
   p.dxa = take(T * H * es);
   p.dxb = take(T * H * es);
@@ -95,7 +95,7 @@ static int64_t accounted_bytes(const poplar_model_cfg& c, int stage, int B, int 
   if (B == 0) return state_bytes(c, stage);
   const int64_t T = (int64_t)B * c.seq, H = c.hidden, es = elt_size(c.dtype);
   const HeadPlan hp = head_plan(c, B);
-  int64_t act = (int64_t)(c.n_layer + 1) * round_up(T * H * es, 256) + saved_plan(c, B).bytes * c.n_layer + (int64_t)B * (c.seq + 1) * 4;
+  int64_t act = (int64_t)(c.n_layer + 1) * round_up(T * H * es, 256) + saved_plan(c, B).bytes * (c.checkpoint ? 1 : c.n_layer) + (int64_t)B * (c.seq + 1) * 4;
   if (forward_only) act += hp.dhf;  // hf, stats, logits, row_loss (everything before dhf)
   else act += std::max(hp.bytes, bwd_plan(c, B).bytes) + 2 * round_up(T * H * es, 256);
   return state_bytes(c, stage) + act;
@@ -195,7 +195,8 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   char* ws = (char*)st.workspace;
   const int64_t xstride = round_up(T * H * es, 256);
   auto X = [&](int l) -> void* { return ws + sp.xs + (int64_t)l * xstride; };
-  auto SV = [&](int l) -> void* { return ws + sp.saved + (int64_t)l * sp.saved_each; };
+  // with checkpointing every layer uses the one stash: the forward pass leaves nothing but the layer inputs X(l)
+  auto SV = [&](int l) -> void* { return ws + sp.saved + (c.checkpoint ? 0 : (int64_t)l * sp.saved_each); };
   void* shared = ws + sp.shared;
   void* dx_cur = ws + sp.dxa;
   void* dx_nxt = ws + sp.dxb;
@@ -293,6 +294,9 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
       const int64_t lo = u.layer0 + (int64_t)l * u.lc;
       POPLAR_TRY(params_at(lo, lo + u.lc, gbuf, sp_gb, &p_l));
       float* gl = unit_grads(lo);
+      // checkpointing: the layer's forward pass again, from its kept input, to refill the stash (X(l+1) is
+      // rewritten with the values it already holds)
+      if (c.checkpoint) POPLAR_TRY(layer_fwd_impl(ctx, B, X(l), p_l, X(l + 1), SV(l)));
       POPLAR_TRY(layer_bwd_impl(ctx, B, X(l), dx_cur, p_l, SV(l), dx_nxt, gl, stage < 2 ? acc : 0, shared));
       POPLAR_TRY(reduce_unit(gl, lo, lo + u.lc));
       std::swap(dx_cur, dx_nxt);
@@ -461,5 +465,17 @@ extern "C" int poplar_search_mbs(poplar_ctx* ctx, int32_t stage, int32_t* mbs, p
     if (fits) lo = mid; else hi = mid - 1;
   }
   *mbs = (int32_t)lo;
+  return POPLAR_OK;
+}
+
+extern "C" int poplar_search_stage(poplar_ctx* ctx, int32_t first_stage, int32_t* stage, int32_t* mbs, poplar_profile* samples,
+                                   int32_t max_samples, int32_t* n_samples) {
+  if (!ctx || !stage || !mbs || !n_samples) return poplar_fail(POPLAR_ERR_INVALID, "null argument");
+  if (first_stage < 0 || first_stage > 3) return poplar_fail(POPLAR_ERR_INVALID, "first_stage %d outside 0..3", first_stage);
+  *stage = -1; *mbs = 0; *n_samples = 0;
+  for (int s = first_stage; s <= 3; ++s) {
+    POPLAR_TRY(poplar_search_mbs(ctx, s, mbs, samples, max_samples, n_samples));
+    if (*mbs > 0) { *stage = s; return POPLAR_OK; }
+  }
   return POPLAR_OK;
 }

@@ -314,3 +314,63 @@ def test_bidirectional_masked_lm_step_matches_oracle(stage, dtype):
     assert rel_l2(grad_c if stage < 2 else grad_c[sl], ref) > 10 * TOL[dtype]
     assert prof["flops"] == B * (model["L"] * (6 * model["S"] * (4 * model["H"] ** 2 + 2 * model["H"] * model["F"])
                                                + 14 * model["S"] ** 2 * model["H"]) + 6 * model["S"] * model["H"] * model["V"])
+
+
+# ---- memory knobs of the search: activation checkpointing, moving to the next ZeRO stage ---------------------------
+def test_checkpointed_step_is_the_same_step_in_less_memory():
+    model, B = MODELS["gpt"], 3
+    a = Rank(model, "f32", 1, 4, 3, max_batch=B)
+    b = Rank(model, "f32", 1, 4, 3, max_batch=B)
+    cfg = pb.make_cfg(**model, dtype="f32", world=4, rank=3, zero_stage=1, checkpoint=True)
+    ctx = pb.Context(cfg)
+    wsb = pb.step_workspace_bytes(cfg, 1, B)
+    assert wsb < b.wsb
+    ctx.bind_state(b.params, b.master, b.m, b.v, b.grads, b.tokens, B, b.ws, wsb, b.loss, adam_t=1, lr=HP["lr"], beta1=HP["b1"],
+                   beta2=HP["b2"], eps=HP["eps"])
+    pa = a.ctx.profile_step(1, B)
+    pc = ctx.profile_step(1, B)
+    sync()
+    V, H = model["V"], model["H"]
+    assert a.off >= V * H          # this shard holds no part of wte, whose gradient collects atomics in free order
+    assert pa["loss"] == pc["loss"]
+    assert torch.equal(a.grads[V * H:], b.grads[V * H:]) and torch.equal(a.master, b.master)
+    assert pc["accounted_bytes"] < pa["accounted_bytes"] and pc["flops"] == pa["flops"]
+
+
+def test_checkpointing_raises_the_largest_batch_under_the_same_cap():
+    model, world, stage = dict(MODELS["gpt"], L=6), 4, 1
+    plain = pb.make_cfg(**model, dtype="bf16", world=world, zero_stage=stage)
+    cap = pb.step_accounted_bytes(plain, stage, 4) + 100     # room for 4 samples with a stash per layer
+    got = {}
+    for ck in (False, True):
+        cfg = pb.make_cfg(**model, dtype="bf16", world=world, zero_stage=stage, cap_bytes=cap, checkpoint=ck)
+        rk = Rank(model, "bf16", stage, world, 0, max_batch=16)
+        ctx = pb.Context(cfg)
+        ctx.bind_state(rk.params, rk.master, rk.m, rk.v, rk.grads, rk.tokens, 16, rk.ws, rk.wsb, rk.loss, adam_t=1)
+        mbs, samples = ctx.search_mbs(stage)
+        assert mbs == max(b for b in range(0, 17) if pb.step_accounted_bytes(cfg, stage, b) <= cap)
+        got[ck] = mbs
+    assert got[False] == 4 and got[True] > 4
+
+
+def test_search_moves_to_the_next_stage_when_nothing_fits():
+    model, world = dict(MODELS["gpt"], L=8), 4      # deep enough for the model states to outweigh the staging bucket
+    probe = pb.make_cfg(**model, dtype="bf16", world=world, zero_stage=1)
+    need = [pb.step_accounted_bytes(probe, s, 1) for s in range(4)]
+    assert need[0] > need[1] > need[2] > need[3]
+    cap = need[2] + 10                                                        # stage 2 holds one sample, stage 1 none
+    assert cap < need[1] and cap < pb.step_accounted_bytes(probe, 2, 2)
+    rk = Rank(model, "bf16", 3, world, 0, max_batch=8, cap_bytes=cap)          # built for stage 3: has own_shard
+    grads = torch.zeros(rk.P, device=DEV)                                      # a gradient buffer that serves every stage
+    rk.ctx.bind_state(rk.params, rk.master, rk.m, rk.v, grads, rk.tokens, 8, rk.ws, rk.wsb, rk.loss, own_shard=rk.own, adam_t=1)
+    stage, mbs, samples = rk.ctx.search_stage(0)
+
+    def search(s):
+        fits = max([b for b in range(0, 9) if pb.step_accounted_bytes(rk.cfg, s, b) <= cap], default=0)
+        return fits, [None] * fits
+    o_stage, o_mbs, _ = opf.search_stage(0, search)
+    assert (stage, mbs) == (o_stage, o_mbs) == (2, 1)
+    assert [s["batch"] for s in samples] == [1] and all(s["stage"] == 2 for s in samples)
+    # nothing fits anywhere
+    tiny = Rank(model, "bf16", 3, world, 0, max_batch=2, cap_bytes=1000)
+    assert tiny.ctx.search_stage(1) == (-1, 0, [])

@@ -145,3 +145,18 @@ def test_config_validation_and_byte_queries():
     c = pb.make_cfg(**CFGS[2], world=4)
     st = [pb.step_accounted_bytes(c, s, 0) for s in range(4)]
     assert st[0] > st[1] > st[2] > st[3]
+
+
+def test_checkpointing_keeps_one_stash_instead_of_one_per_layer():
+    base = dict(arch="gpt", L=6, H=128, nh=2, F=256, S=64, V=211, dtype="bf16", world=4, zero_stage=1)
+    plain, ckpt = pb.make_cfg(**base), pb.make_cfg(**base, checkpoint=True)
+    for stage in range(4):
+        for B in (1, 3, 8):
+            saved = pb.layer_saved_bytes(plain, B)
+            assert pb.step_accounted_bytes(plain, stage, B) - pb.step_accounted_bytes(ckpt, stage, B) == 5 * saved
+            assert pb.step_workspace_bytes(plain, stage, B) - pb.step_workspace_bytes(ckpt, stage, B) == 5 * saved
+        assert pb.step_accounted_bytes(plain, stage, 0) == pb.step_accounted_bytes(ckpt, stage, 0)
+    with pytest.raises(pb.PoplarError):
+        bad = pb.make_cfg(**base)
+        bad.checkpoint = 2
+        pb.model_param_count(bad)

@@ -73,3 +73,17 @@ def test_search_returns_zero_when_one_sample_does_not_fit():
     dev = FakeDevice(total=1000, state=900, fwd_per_sample=50, step_extra_per_sample=100)
     mbs, samples = pf.search_mbs(dev.bytes_now, dev.forward, dev.step, dev.total)
     assert mbs == 0 and samples == []
+
+
+def test_stage_escalation_stops_at_the_first_stage_that_fits():
+    # Section "Heterogeneity Aware": mbs = 0 at a stage sends the search to the next one
+    table = {0: (0, []), 1: (0, []), 2: (5, [(1, .1), (2, .2), (4, .4), (5, .5)]), 3: (9, [(1, .1)])}
+    seen = []
+
+    def search(stage):
+        seen.append(stage)
+        return table[stage]
+    assert pf.search_stage(0, search) == (2, 5, table[2][1]) and seen == [0, 1, 2]
+    seen.clear()
+    assert pf.search_stage(3, search) == (3, 9, table[3][1]) and seen == [3]
+    assert pf.search_stage(0, lambda s: (0, [])) == (-1, 0, [])
