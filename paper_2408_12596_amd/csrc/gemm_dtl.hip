@@ -198,6 +198,36 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
     for (int l = 0; l < NL; ++l) load_one(st, l);
   };
 
+  // Second operand of the epilogue (the stashed pre-activation for GeLU', or the residual; the launcher admits
+  // one of the two), 16 bytes per lane for each 16-row group of the wave tile.  The first TMC tile rows are
+  // fetched here, before the K loop, the rest at the start of the epilogue behind the first chunk's work: the
+  // epilogue then never waits on memory for them.
+  constexpr int SW = TN * 32 + 4;
+  constexpr int GROUPS = TN * 4;
+  constexpr int ITS = 16 * GROUPS / 64;
+  constexpr int TMC = TM >= 4 ? 2 : TM;
+  static_assert(TM == TMC || TM == 2 * TMC, "one or two chunks");
+  const int64_t n_ext = (p.N + 7) / 8 * 8;
+  const bf16* extra = p.act == ACT_GELU_BWD ? p.aux : p.residual;
+  const int64_t ldx = p.act == ACT_GELU_BWD ? p.ldaux : p.ldc;
+  uint4 pre[2][TMC][2][ITS];
+  auto prefetch = [&](int c) __attribute__((always_inline)) {
+    if (!extra) return;
+#pragma unroll
+    for (int i = 0; i < TMC; ++i)
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+          const int gid = lane + it * 64;
+          const int64_t m = m0 + wm + (c * TMC + i) * 32 + half * 16 + gid / GROUPS;
+          const int64_t n = n0 + wn + (gid % GROUPS) * 8;
+          pre[c][i][half][it] = make_uint4(0, 0, 0, 0);
+          if (m < p.M && n < n_ext) pre[c][i][half][it] = *reinterpret_cast<const uint4*>(extra + m * ldx + n);
+        }
+  };
+  if (!ATOMIC) prefetch(0);
+
   floatx16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -295,71 +325,82 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
     }
     return;
   }
-  // epilogue through a per-wave float staging area (see gemm_mfma.hip)
-  constexpr int SW = TN * 32 + 4;
-  constexpr int GROUPS = TN * 4;
+  // Epilogue through a per-wave float staging area (see gemm_mfma.hip).  The bias depends on the column only
+  // and is read once.
   float* stage = reinterpret_cast<float*>(stage0) + wave * (16 * SW);
-  const int64_t n_ext = (p.N + 7) / 8 * 8;
+  uint4 bias_raw[ITS];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+  for (int it = 0; it < ITS; ++it) {
+    const int64_t n = n0 + wn + ((lane + it * 64) % GROUPS) * 8;
+    bias_raw[it] = make_uint4(0, 0, 0, 0);
+    if (p.bias && n < n_ext) bias_raw[it] = *reinterpret_cast<const uint4*>(p.bias + n);
+  }
+  if (TM > TMC) prefetch(1);
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
+  for (int ic = 0; ic < TM; ic += TMC) {
+    const int c = ic / TMC;
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+    for (int ii = 0; ii < TMC; ++ii) {
+      const int i = ic + ii;
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-          stage[((q >> 2) * 8 + lk * 4 + (q & 3)) * SW + j * 32 + lr] = acc[i][j][half * 8 + q];
-      wave_lds_sync();
+      for (int half = 0; half < 2; ++half) {
 #pragma unroll
-      for (int it = 0; it < 16 * GROUPS / 64; ++it) {
-        const int gid = lane + it * 64;
-        const int row = gid / GROUPS, cg = gid % GROUPS;
-        const int64_t m = m0 + wm + i * 32 + half * 16 + row;
-        const int64_t n = n0 + wn + cg * 8;
-        float v[8];
-        {
-          const float4 lo = *reinterpret_cast<const float4*>(stage + row * SW + cg * 8);
-          const float4 hi = *reinterpret_cast<const float4*>(stage + row * SW + cg * 8 + 4);
-          v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
-        }
-        if (m < p.M && n < n_ext) {
-          Vec<bf16> t;
-          float f[8];
-          if (p.bias) {
-            t.load(p.bias + n); t.unpack(f);
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] += f[k];
+          for (int q = 0; q < 8; ++q)
+            stage[((q >> 2) * 8 + lk * 4 + (q & 3)) * SW + j * 32 + lr] = acc[i][j][half * 8 + q];
+        wave_lds_sync();
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+          const int gid = lane + it * 64;
+          const int row = gid / GROUPS, cg = gid % GROUPS;
+          const int64_t m = m0 + wm + i * 32 + half * 16 + row;
+          const int64_t n = n0 + wn + cg * 8;
+          float v[8];
+          {
+            const float4 lo = *reinterpret_cast<const float4*>(stage + row * SW + cg * 8);
+            const float4 hi = *reinterpret_cast<const float4*>(stage + row * SW + cg * 8 + 4);
+            v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
           }
-          if (p.act == ACT_GELU) {
-            t.pack(v); t.store(p.aux + m * p.ldaux + n);
+          if (m < p.M && n < n_ext) {
+            Vec<bf16> t;
+            float f[8];
+            if (p.bias) {
+              t.raw = bias_raw[it]; t.unpack(f);
 #pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = gelu_tanh_fast(v[k]);
-          } else if (p.act == ACT_GELU_BWD) {
-            t.load(p.aux + m * p.ldaux + n); t.unpack(f);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] *= gelu_tanh_grad_fast(f[k]);
-          }
-          if (p.residual) {
-            t.load(p.residual + m * p.ldc + n); t.unpack(f);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] += f[k];
-          }
-          if (p.c_float) {
-            float* c = reinterpret_cast<float*>(p.C) + m * p.ldc + n;
-            float4 lo = make_float4(v[0], v[1], v[2], v[3]), hi = make_float4(v[4], v[5], v[6], v[7]);
-            if (p.beta != 0.f) {
-              const float4 ol = *reinterpret_cast<const float4*>(c), oh = *reinterpret_cast<const float4*>(c + 4);
-              lo.x += p.beta * ol.x; lo.y += p.beta * ol.y; lo.z += p.beta * ol.z; lo.w += p.beta * ol.w;
-              hi.x += p.beta * oh.x; hi.y += p.beta * oh.y; hi.z += p.beta * oh.z; hi.w += p.beta * oh.w;
+              for (int k = 0; k < 8; ++k) v[k] += f[k];
             }
-            *reinterpret_cast<float4*>(c) = lo;
-            *reinterpret_cast<float4*>(c + 4) = hi;
-          } else {
-            t.pack(v); t.store(reinterpret_cast<bf16*>(p.C) + m * p.ldc + n);
+            if (p.act == ACT_GELU) {
+              t.pack(v); t.store(p.aux + m * p.ldaux + n);
+#pragma unroll
+              for (int k = 0; k < 8; ++k) v[k] = gelu_tanh_fast(v[k]);
+            } else if (p.act == ACT_GELU_BWD) {
+              t.raw = pre[c][ii][half][it]; t.unpack(f);
+#pragma unroll
+              for (int k = 0; k < 8; ++k) v[k] *= gelu_tanh_grad_fast(f[k]);
+            }
+            if (p.residual) {   // never together with GeLU' (the launcher refuses that pair): pre holds the residual
+              t.raw = pre[c][ii][half][it]; t.unpack(f);
+#pragma unroll
+              for (int k = 0; k < 8; ++k) v[k] += f[k];
+            }
+            if (p.c_float) {
+              float* c = reinterpret_cast<float*>(p.C) + m * p.ldc + n;
+              float4 lo = make_float4(v[0], v[1], v[2], v[3]), hi = make_float4(v[4], v[5], v[6], v[7]);
+              if (p.beta != 0.f) {
+                const float4 ol = *reinterpret_cast<const float4*>(c), oh = *reinterpret_cast<const float4*>(c + 4);
+                lo.x += p.beta * ol.x; lo.y += p.beta * ol.y; lo.z += p.beta * ol.z; lo.w += p.beta * ol.w;
+                hi.x += p.beta * oh.x; hi.y += p.beta * oh.y; hi.z += p.beta * oh.z; hi.w += p.beta * oh.w;
+              }
+              *reinterpret_cast<float4*>(c) = lo;
+              *reinterpret_cast<float4*>(c + 4) = hi;
+            } else {
+              t.pack(v); t.store(reinterpret_cast<bf16*>(p.C) + m * p.ldc + n);
+            }
           }
         }
+        wave_lds_sync();
       }
-      wave_lds_sync();
     }
   }
 }
@@ -382,6 +423,7 @@ static int dtl_prepare(const GemmArgs& a, DtlGemmParams& p) {
   const bool a_tail_ok = a.layout == GEMM_NN && a.a_k_pad_zero && a.lda >= round_up(a.K, DTL_BK);
   if (a.layout != GEMM_TN && a.K % DTL_BK && !a_tail_ok) return POPLAR_ERR_UNIMPLEMENTED;
   if (a.K < DTL_BK) return POPLAR_ERR_UNIMPLEMENTED;
+  if (a.act == ACT_GELU_BWD && a.residual) return POPLAR_ERR_UNIMPLEMENTED;   // the epilogue prefetches one extra operand
   if (a.lda % 8 || a.ldb % 8 || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15)) return POPLAR_ERR_UNIMPLEMENTED;
   if (a.ldc % 8 || a.ldc < round_up(a.N, 8) || ((uintptr_t)a.C & 15) || (a.aux && (a.ldaux % 8 || ((uintptr_t)a.aux & 15))) ||
       (a.bias && ((uintptr_t)a.bias & 15)) || (a.residual && ((uintptr_t)a.residual & 15)))
