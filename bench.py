@@ -93,6 +93,52 @@ def curve_report(pb, ctx, P, max_b, reps=5):
     return out
 
 
+LAYER_SHAPES = {   # one decoder layer of the larger configurations, at the batches their parity tests use
+    "gpt-1.3B (H 2048, 16 heads of 128, F 8192, S 2048)": (dict(arch="gpt", L=1, H=2048, nh=16, F=8192, S=2048, V=64), (1, 2, 4, 8)),
+    "llama-7B (H 4096, 32 heads of 128, F 11008, S 2048)": (dict(arch="llama", L=1, H=4096, nh=32, F=11008, S=2048, V=64), (1, 2, 4)),
+}
+
+
+def layer_report(pb, torch, iters=5):
+    """Forward and backward of ONE layer at the shapes of the larger configurations (their whole models need
+    more than a bench run should take): milliseconds and algorithmic TFLOP/s, causal attention at half density."""
+    dev, out = "cuda:0", {}
+    for name, (case, batches) in LAYER_SHAPES.items():
+        cfg = pb.make_cfg(**case, dtype="bf16")
+        ctx = pb.Context(cfg, torch.cuda.current_stream().cuda_stream)
+        n, H, S, F = pb.layer_param_count(cfg), case["H"], case["S"], case["F"]
+        params = (torch.randn(n, device=dev) * 0.02).to(torch.bfloat16)
+        grads = torch.zeros(n, device=dev)
+        rows = []
+        for B in batches:
+            x = torch.randn(B * S, H, device=dev).to(torch.bfloat16)
+            dy = torch.randn(B * S, H, device=dev).to(torch.bfloat16)
+            y, dx = torch.empty_like(x), torch.empty_like(x)
+            saved = torch.empty(pb.layer_saved_bytes(cfg, B) + 256, dtype=torch.uint8, device=dev)
+            wsb = pb.layer_workspace_bytes(cfg, B)
+            ws = torch.empty(wsb + 256, dtype=torch.uint8, device=dev)
+            ctx.layer_fwd(B, x, params, y, saved)
+            ctx.layer_bwd(B, x, dy, params, saved, dx, grads, 0, ws, wsb)
+            torch.cuda.synchronize()
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record()
+            for _ in range(iters):
+                ctx.layer_fwd(B, x, params, y, saved)
+            e[1].record()
+            for _ in range(iters):
+                ctx.layer_bwd(B, x, dy, params, saved, dx, grads, 0, ws, wsb)
+            e[2].record()
+            torch.cuda.synchronize()
+            tf, tb = e[0].elapsed_time(e[1]) / iters, e[1].elapsed_time(e[2]) / iters
+            gemm = 2 * S * (4 * H * H + (3 if case["arch"] == "llama" else 2) * H * F)
+            ff, fb = B * (gemm + 2 * S * S * H), B * (2 * gemm + 5 * S * S * H)
+            rows.append({"batch": B, "fwd_ms": tf, "bwd_ms": tb, "fwd_tflops": ff / tf / 1e9, "bwd_tflops": fb / tb / 1e9,
+                         "tflops": (ff + fb) / (tf + tb) / 1e9})
+            del x, dy, y, dx, saved, ws
+        out[name] = rows
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +148,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--curve-report", action="store_true", help="add the dense-sweep / spline / Algorithm 2 report to the line")
+    ap.add_argument("--layer-report", action="store_true", help="add one-layer timings at the larger configurations' shapes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one rank on ONE GPU (the ZeRO world is simulated by shard offsets); --gpus must be 1", file=sys.stderr)
@@ -189,6 +236,8 @@ def main():
         out["sweep"] = sweep
     if args.curve_report:
         out["curve_report"] = curve_report(pb, ctx, P, max_b)
+    if args.layer_report:
+        out["layer_report"] = layer_report(pb, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(model, flat, tok, tgt)
     print(json.dumps(out))
