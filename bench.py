@@ -93,6 +93,24 @@ def curve_report(pb, ctx, P, max_b, reps=5):
     return out
 
 
+def adam_large(pb, ctx, torch, elems=128 * 1024 * 1024, iters=5):
+    """Adam on a shard far larger than the 256 MB Infinity Cache (30 bytes per element: 4 GB at the default size)."""
+    dev = "cuda:0"
+    p, m, v = (torch.zeros(elems, device=dev) for _ in range(3))
+    g = torch.full((elems,), 1e-3, device=dev)
+    low = torch.empty(elems, dtype=torch.bfloat16, device=dev)
+    ctx.adam_shard(p, m, v, g, low, elems, 1, 1e-3, 0.9, 0.999, 1e-8)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for t in range(iters):
+        ctx.adam_shard(p, m, v, g, low, elems, t + 2, 1e-3, 0.9, 0.999, 1e-8)
+    e1.record()
+    torch.cuda.synchronize()
+    gbs = 30.0 * elems * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return {"achieved": gbs, "unit": "GB/s", "peak": PEAK_HBM_GBS, "frac": gbs / PEAK_HBM_GBS, "bytes_per_elem": 30, "elems": elems}
+
+
 LAYER_SHAPES = {   # one decoder layer of the larger configurations, at the batches their parity tests use
     "gpt-1.3B (H 2048, 16 heads of 128, F 8192, S 2048)": (dict(arch="gpt", L=1, H=2048, nh=16, F=8192, S=2048, V=64), (1, 2, 4, 8)),
     "llama-7B (H 4096, 32 heads of 128, F 11008, S 2048)": (dict(arch="llama", L=1, H=4096, nh=32, F=11008, S=2048, V=64), (1, 2, 4)),
@@ -223,6 +241,7 @@ def main():
                       "frac": (f_attn / t_attn / 1e12 / PEAK_BF16_TFLOPS) if t_attn > 0 else 0.0},
         "adam": {"achieved": adam_gbs, "unit": "GB/s", "peak": PEAK_HBM_GBS, "frac": adam_gbs / PEAK_HBM_GBS,
                  "bytes_per_elem": 30, "elems": valid},
+        "adam_4GB": adam_large(pb, ctx, torch),
         "loss": profs[-1]["loss"],
         "device": device_info(pb, torch),
     }
