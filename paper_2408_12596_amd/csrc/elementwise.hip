@@ -276,7 +276,7 @@ template <typename T, bool RMS>
 static int norm_fwd_launch(hipStream_t s, int64_t rows, int H, const T* x, const T* g, const T* b, T* y, float* stats) {
   constexpr int VN = Vec<T>::N;
   int need = (int)cdiv(H, 64 * VN);
-  int grid = grid_for(rows, 4, 256 * 8);
+  int grid = grid_for(rows, 4);
 #define NORM_FWD_CASE(NVV) \
   hipLaunchKernelGGL((norm_fwd_kernel<T, NVV, RMS>), dim3(grid), dim3(256), 0, s, x, g, b, y, stats, rows, H)
   if (need <= 1) NORM_FWD_CASE(1);
@@ -321,8 +321,26 @@ __global__ void __launch_bounds__(256) norm_bwd_kernel(const T* __restrict__ dy,
     for (int k = 0; k < VN; ++k) { accg[i][k] = 0.f; accb[i][k] = 0.f; gam[i][k] = 0.f; }
     if (c < H) { Vec<T> v; v.load(g + c); v.unpack(gam[i]); }
   }
+  // The row after the current one is fetched before the current one is worked on: a wave has a handful of
+  // rows, each 1-3 KB, and would otherwise sit through two memory round trips per row.
+  struct RowRaw { Vec<T> x[NV], dy[NV], rs[NV]; float mean, rstd; };
+  auto fetch = [&](int64_t r, RowRaw& q) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (i * 64 + lane) * VN;
+      if (c < H) {
+        q.x[i].load(x + r * H + c);
+        q.dy[i].load(dy + r * H + c);
+        if (dres) q.rs[i].load(dres + r * H + c);
+      }
+    }
+    q.mean = stats[2 * r]; q.rstd = stats[2 * r + 1];
+  };
+  RowRaw cur, nxt;
+  if (wave < rows) fetch(wave, cur);
   for (int64_t r = wave; r < rows; r += nwaves) {
-    const float mean = stats[2 * r], rstd = stats[2 * r + 1];
+    if (r + nwaves < rows) fetch(r + nwaves, nxt);
+    const float mean = cur.mean, rstd = cur.rstd;
     float xh[NV][VN], dxh[NV][VN];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -330,8 +348,8 @@ __global__ void __launch_bounds__(256) norm_bwd_kernel(const T* __restrict__ dy,
       int c = (i * 64 + lane) * VN;
       if (c < H) {
         float xv[VN], dv[VN];
-        Vec<T> v; v.load(x + r * H + c); v.unpack(xv);
-        v.load(dy + r * H + c); v.unpack(dv);
+        cur.x[i].unpack(xv);
+        cur.dy[i].unpack(dv);
 #pragma unroll
         for (int k = 0; k < VN; ++k) {
           xh[i][k] = (xv[k] - mean) * rstd;
@@ -351,12 +369,13 @@ __global__ void __launch_bounds__(256) norm_bwd_kernel(const T* __restrict__ dy,
       if (c < H) {
         float o[VN], rs[VN];
         Vec<T> v;
-        if (dres) { v.load(dres + r * H + c); v.unpack(rs); }
+        if (dres) cur.rs[i].unpack(rs);
 #pragma unroll
         for (int k = 0; k < VN; ++k) o[k] = rstd * (dxh[i][k] - s1 - xh[i][k] * s2) + (dres ? rs[k] : 0.f);
         v.pack(o); v.store(dx + r * H + c);
       }
     }
+    cur = nxt;
   }
   // block reduction of the per-wave column sums
   extern __shared__ float lds[];  // [4][2][H]
