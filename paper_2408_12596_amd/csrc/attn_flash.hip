@@ -30,6 +30,7 @@
 // Forward and dQ work on S^T = K Q^T (lane = query), which keeps the running
 // max / sum / rescale of a query inside one lane (plus one exchange between the
 // two lane halves).  dK/dV works on S = Q K^T (lane = key).
+#include <hip/hip_ext.h>
 #include "device_utils.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -600,33 +601,35 @@ static int check_flash(int B, int S, int nh, int d, const void* qkv) {
   return POPLAR_OK;
 }
 
-int attn_fwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const void* qkv, void* o, float* lse) {
+int attn_fwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const void* qkv, void* o, float* lse,
+                   hipEvent_t ev_start, hipEvent_t ev_stop) {
   POPLAR_TRY(check_flash(B, S, nh, d, qkv));
   if (B == 0 || S == 0) return POPLAR_OK;
   const float scale = 1.0f / sqrtf((float)d);
   dim3 grid((unsigned)((int64_t)B * nh * ((S + 127) / 128)));
-  if (d == 64) hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, B, S, nh, causal, scale);
-  else hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, B, S, nh, causal, scale);
+  if (d == 64) hipExtLaunchKernelGGL(flash_fwd_kernel<64>, grid, dim3(256), 0, s, ev_start, ev_stop, 0, (const bf16*)qkv, (bf16*)o, lse, B, S, nh, causal, scale);
+  else hipExtLaunchKernelGGL(flash_fwd_kernel<128>, grid, dim3(256), 0, s, ev_start, ev_stop, 0, (const bf16*)qkv, (bf16*)o, lse, B, S, nh, causal, scale);
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }
 
 int attn_bwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const void* qkv, const void* o, const void* dout,
-                   const float* lse, void* dqkv, float* delta) {
+                   const float* lse, void* dqkv, float* delta, hipEvent_t ev_start, hipEvent_t ev_stop) {
   POPLAR_TRY(check_flash(B, S, nh, d, qkv));
   if (B == 0 || S == 0) return POPLAR_OK;
   const float scale = 1.0f / sqrtf((float)d);
   const int64_t rows = (int64_t)B * S * nh;
-  hipLaunchKernelGGL(flash_delta_kernel, dim3((unsigned)cdiv(rows * (d / 8), 256)), dim3(256), 0, s, (const bf16*)o, (const bf16*)dout, delta,
-                     rows, S, nh, d);
+  // the first launch carries the start event, the last one the stop event
+  hipExtLaunchKernelGGL(flash_delta_kernel, dim3((unsigned)cdiv(rows * (d / 8), 256)), dim3(256), 0, s, ev_start, nullptr, 0, (const bf16*)o,
+                        (const bf16*)dout, delta, rows, S, nh, d);
   POPLAR_LAUNCH_CHECK();
   dim3 grid((unsigned)((int64_t)B * nh * ((S + 127) / 128)));
   if (d == 64) {
     hipLaunchKernelGGL(flash_bwd_dkv_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
-    hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
+    hipExtLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, dim3(256), 0, s, nullptr, ev_stop, 0, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
   } else {
     hipLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
-    hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
+    hipExtLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, dim3(256), 0, s, nullptr, ev_stop, 0, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
   }
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;

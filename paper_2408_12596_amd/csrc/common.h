@@ -42,6 +42,8 @@ struct poplar_ctx {
 };
 // record the next pooled event on the context's stream
 int ctx_mark(poplar_ctx* ctx, hipEvent_t* e);
+// hand out the next pooled event without recording it (a launcher records it with the kernel it brackets)
+int ctx_take(poplar_ctx* ctx, hipEvent_t* e);
 
 static inline int64_t elt_size(int dtype) { return dtype == POPLAR_BF16 ? 2 : 4; }
 static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -78,6 +80,9 @@ struct GemmArgs {
   int act;                // ACT_GELU: aux <- pre-activation, C <- gelu;  ACT_GELU_BWD: C <- acc * gelu'(aux)
   void* aux; int64_t ldaux;
   int a_k_pad_zero;       // NN only: A's rows hold zeros from column K up to K rounded up to 64 (lda covers them)
+  // Optional: events that receive the start and the end of the kernel itself (hipExtLaunchKernelGGL), without the
+  // barrier packets a recorded event puts between kernels.  Honoured by the direct-to-LDS kernel only.
+  hipEvent_t ev_start, ev_stop;
 };
 int gemm_simple(hipStream_t s, int dtype, const GemmArgs& a);
 int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a);
@@ -90,9 +95,12 @@ int gemm(hipStream_t s, int dtype, const GemmArgs& a);
 int attn_fwd_simple(hipStream_t s, int dtype, int B, int S, int nh, int d, int causal, const void* qkv, void* o, float* lse);
 int attn_bwd_simple(hipStream_t s, int dtype, int B, int S, int nh, int d, int causal, const void* qkv, const void* o,
                     const void* dout, const float* lse, void* dqkv, float* delta);
-int attn_fwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const void* qkv, void* o, float* lse);
+// ev_start / ev_stop (optional): receive the start of the first and the end of the last kernel launched
+int attn_fwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const void* qkv, void* o, float* lse,
+                   hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 int attn_bwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const void* qkv, const void* o,
-                   const void* dout, const float* lse, void* dqkv, float* delta);
+                   const void* dout, const float* lse, void* dqkv, float* delta, hipEvent_t ev_start = nullptr,
+                   hipEvent_t ev_stop = nullptr);
 
 // row-wise / elementwise kernels (elementwise.hip)
 int layernorm_fwd(hipStream_t s, int dtype, int64_t T, int H, const void* x, const void* g, const void* b, void* y, float* stats, int rms);

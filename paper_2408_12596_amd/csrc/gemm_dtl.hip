@@ -26,6 +26,7 @@
 // Preconditions checked by the launcher: K a multiple of 64 unless both operands
 // are k-strided (their K tail is out of range, hence zero), operand extents
 // below 4 GiB (32-bit buffer offsets).
+#include <hip/hip_ext.h>
 #include "device_utils.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -406,12 +407,13 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
 }
 
 template <int WM, int WN, int TM, int TN, bool ATOMIC>
-static void launch_dtl(hipStream_t s, int layout, dim3 grid, const DtlGroupParams& gp) {
+static void launch_dtl(hipStream_t s, int layout, dim3 grid, const DtlGroupParams& gp, hipEvent_t e0, hipEvent_t e1) {
   dim3 block(64 * WM * WN);
+  // with events the launch itself carries them: they receive the kernel's own start and end
   switch (layout) {
-    case GEMM_NT: hipLaunchKernelGGL((gemm_dtl_kernel<GEMM_NT, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, gp); break;
-    case GEMM_NN: hipLaunchKernelGGL((gemm_dtl_kernel<GEMM_NN, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, gp); break;
-    default: hipLaunchKernelGGL((gemm_dtl_kernel<GEMM_TN, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, gp); break;
+    case GEMM_NT: hipExtLaunchKernelGGL((gemm_dtl_kernel<GEMM_NT, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, e0, e1, 0, gp); break;
+    case GEMM_NN: hipExtLaunchKernelGGL((gemm_dtl_kernel<GEMM_NN, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, e0, e1, 0, gp); break;
+    default: hipExtLaunchKernelGGL((gemm_dtl_kernel<GEMM_TN, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, e0, e1, 0, gp); break;
   }
 }
 
@@ -516,14 +518,14 @@ int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n) {
   }
   dim3 grid((unsigned)tiles, (unsigned)splits);
   if (pick == 0) {
-    if (atomic) launch_dtl<2, 4, 4, 2, true>(s, a[0].layout, grid, gp);
-    else launch_dtl<2, 4, 4, 2, false>(s, a[0].layout, grid, gp);
+    if (atomic) launch_dtl<2, 4, 4, 2, true>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
+    else launch_dtl<2, 4, 4, 2, false>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
   } else if (pick == 1) {
-    if (atomic) launch_dtl<4, 2, 2, 3, true>(s, a[0].layout, grid, gp);
-    else launch_dtl<4, 2, 2, 3, false>(s, a[0].layout, grid, gp);
+    if (atomic) launch_dtl<4, 2, 2, 3, true>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
+    else launch_dtl<4, 2, 2, 3, false>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
   } else {
-    if (atomic) launch_dtl<2, 2, 2, 2, true>(s, a[0].layout, grid, gp);
-    else launch_dtl<2, 2, 2, 2, false>(s, a[0].layout, grid, gp);
+    if (atomic) launch_dtl<2, 2, 2, 2, true>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
+    else launch_dtl<2, 2, 2, 2, false>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
   }
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;

@@ -12,44 +12,61 @@ int gemm(hipStream_t s, int dtype, const GemmArgs& a) {
   return gemm_simple(s, dtype, a);
 }
 
-// Launch wrappers that, inside a profiled step with kernel timing on, bracket
-// the launch with two events and note its algorithmic flop count.
+// Launch wrappers that, inside a profiled step with kernel timing on, time each GEMM / attention launch and
+// note its algorithmic flop count.  The tuned kernels take the two events with the launch itself
+// (hipExtLaunchKernelGGL: the events receive the kernel's own start and end, nothing is put between kernels);
+// launches that go to another kernel are bracketed by two recorded events instead.
 struct LaunchTimer {
   poplar_ctx* ctx;
   bool on;
   TimedLaunch tl;
+  // hands out the two events, unrecorded
   int begin(int kind, double flops) {
     on = ctx->kernel_timing && ctx->in_step;
+    tl.a = nullptr; tl.b = nullptr;
     if (!on) return POPLAR_OK;
     tl.kind = kind; tl.flops = flops;
-    return ctx_mark(ctx, &tl.a);
+    POPLAR_TRY(ctx_take(ctx, &tl.a));
+    return ctx_take(ctx, &tl.b);
   }
-  int end() {
-    if (!on) return POPLAR_OK;
-    POPLAR_TRY(ctx_mark(ctx, &tl.b));
-    ctx->launches.push_back(tl);
+  int record_start() { return on ? (hipEventRecord(tl.a, ctx->stream) == hipSuccess ? POPLAR_OK : poplar_fail(POPLAR_ERR_HIP, "hipEventRecord")) : POPLAR_OK; }
+  int record_stop() { return on ? (hipEventRecord(tl.b, ctx->stream) == hipSuccess ? POPLAR_OK : poplar_fail(POPLAR_ERR_HIP, "hipEventRecord")) : POPLAR_OK; }
+  int done() {
+    if (on) ctx->launches.push_back(tl);
     return POPLAR_OK;
   }
 };
 static int gemm(poplar_ctx* ctx, const GemmArgs& a) {
   LaunchTimer t{ctx};
   POPLAR_TRY(t.begin(KIND_GEMM, 2.0 * (double)a.M * (double)a.N * (double)a.K));
-  POPLAR_TRY(gemm(ctx->stream, ctx->cfg.dtype, a));
-  return t.end();
+  if (ctx->cfg.dtype == POPLAR_BF16) {
+    GemmArgs b = a;
+    b.ev_start = t.tl.a; b.ev_stop = t.tl.b;
+    const int r = gemm_bf16_dtl(ctx->stream, b);
+    if (r == POPLAR_OK) return t.done();
+    if (r != POPLAR_ERR_UNIMPLEMENTED) return r;
+  }
+  POPLAR_TRY(t.record_start());
+  POPLAR_TRY(ctx->cfg.dtype == POPLAR_BF16 ? gemm_bf16_mfma(ctx->stream, a) : gemm_simple(ctx->stream, ctx->cfg.dtype, a));
+  POPLAR_TRY(t.record_stop());
+  return t.done();
 }
 
 // Several independent GEMMs: one grouped launch where the direct-to-LDS kernel takes the group (the weight
 // gradients of a layer: too few tiles each to fill the chip, enough together), one launch each otherwise.
 static int gemm_group(poplar_ctx* ctx, const GemmArgs* a, int n) {
-  if (ctx->cfg.dtype == POPLAR_BF16 && n > 1) {
+  if (ctx->cfg.dtype == POPLAR_BF16 && n > 1 && n <= 4) {
     double flops = 0.0;
     for (int i = 0; i < n; ++i) flops += 2.0 * (double)a[i].M * (double)a[i].N * (double)a[i].K;
     LaunchTimer t{ctx};
     POPLAR_TRY(t.begin(KIND_GEMM, flops));
-    const int r = gemm_bf16_dtl_group(ctx->stream, a, n);
-    if (r == POPLAR_OK) return t.end();
+    GemmArgs b[4];
+    for (int i = 0; i < n; ++i) b[i] = a[i];
+    b[0].ev_start = t.tl.a; b[0].ev_stop = t.tl.b;
+    const int r = gemm_bf16_dtl_group(ctx->stream, b, n);
+    if (r == POPLAR_OK) return t.done();
     if (r != POPLAR_ERR_UNIMPLEMENTED) return r;
-    // nothing was launched: the pair of events recorded by begin() is simply not used
+    // nothing was launched: the two events handed out are simply not used
   }
   for (int i = 0; i < n; ++i) POPLAR_TRY(gemm(ctx, a[i]));
   return POPLAR_OK;
@@ -65,9 +82,14 @@ static int attn_fwd(poplar_ctx* ctx, int B, const void* qkv, void* o, float* lse
   const int d = c.hidden / c.n_head;
   LaunchTimer t{ctx};
   POPLAR_TRY(t.begin(KIND_ATTN, attn_flops(c, B, 2.0)));
-  if (c.dtype == POPLAR_BF16) POPLAR_TRY(attn_fwd_flash(s, B, c.seq, c.n_head, d, c.causal, qkv, o, lse));
-  else POPLAR_TRY(attn_fwd_simple(s, c.dtype, B, c.seq, c.n_head, d, c.causal, qkv, o, lse));
-  return t.end();
+  if (c.dtype == POPLAR_BF16) {
+    POPLAR_TRY(attn_fwd_flash(s, B, c.seq, c.n_head, d, c.causal, qkv, o, lse, t.tl.a, t.tl.b));
+    return t.done();
+  }
+  POPLAR_TRY(t.record_start());
+  POPLAR_TRY(attn_fwd_simple(s, c.dtype, B, c.seq, c.n_head, d, c.causal, qkv, o, lse));
+  POPLAR_TRY(t.record_stop());
+  return t.done();
 }
 static int attn_bwd(poplar_ctx* ctx, int B, const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv,
                     float* delta) {
@@ -76,9 +98,14 @@ static int attn_bwd(poplar_ctx* ctx, int B, const void* qkv, const void* o, cons
   const int d = c.hidden / c.n_head;
   LaunchTimer t{ctx};
   POPLAR_TRY(t.begin(KIND_ATTN, attn_flops(c, B, 5.0)));
-  if (c.dtype == POPLAR_BF16) POPLAR_TRY(attn_bwd_flash(s, B, c.seq, c.n_head, d, c.causal, qkv, o, dout, lse, dqkv, delta));
-  else POPLAR_TRY(attn_bwd_simple(s, c.dtype, B, c.seq, c.n_head, d, c.causal, qkv, o, dout, lse, dqkv, delta));
-  return t.end();
+  if (c.dtype == POPLAR_BF16) {
+    POPLAR_TRY(attn_bwd_flash(s, B, c.seq, c.n_head, d, c.causal, qkv, o, dout, lse, dqkv, delta, t.tl.a, t.tl.b));
+    return t.done();
+  }
+  POPLAR_TRY(t.record_start());
+  POPLAR_TRY(attn_bwd_simple(s, c.dtype, B, c.seq, c.n_head, d, c.causal, qkv, o, dout, lse, dqkv, delta));
+  POPLAR_TRY(t.record_stop());
+  return t.done();
 }
 
 static GemmArgs gemm_args(int layout, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb,
@@ -87,7 +114,7 @@ static GemmArgs gemm_args(int layout, int64_t M, int64_t N, int64_t K, const voi
   g.layout = layout; g.M = M; g.N = N; g.K = K;
   g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
   g.c_float = 0; g.beta = 0.f; g.bias = nullptr; g.residual = nullptr; g.act = ACT_NONE; g.aux = nullptr; g.ldaux = 0;
-  g.a_k_pad_zero = 0;
+  g.a_k_pad_zero = 0; g.ev_start = nullptr; g.ev_stop = nullptr;
   return g;
 }
 

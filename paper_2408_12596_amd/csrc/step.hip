@@ -123,13 +123,19 @@ static double step_flops(const poplar_model_cfg& c, int B) {
 }
 
 // ---- event pool --------------------------------------------------------------
-int ctx_mark(poplar_ctx* ctx, hipEvent_t* e) {
+int ctx_take(poplar_ctx* ctx, hipEvent_t* e) {
   if (ctx->ev_next == ctx->events.size()) {
     hipEvent_t ne;
-    POPLAR_CHECK_HIP(hipEventCreate(&ne));
+    // device-scope release: a default event flushes the caches to system scope each time it is recorded,
+    // which costs microseconds between kernels and evicts what the next kernel would have found in L2
+    POPLAR_CHECK_HIP(hipEventCreateWithFlags(&ne, hipEventReleaseToDevice));
     ctx->events.push_back(ne);
   }
   *e = ctx->events[ctx->ev_next++];
+  return POPLAR_OK;
+}
+int ctx_mark(poplar_ctx* ctx, hipEvent_t* e) {
+  POPLAR_TRY(ctx_take(ctx, e));
   POPLAR_CHECK_HIP(hipEventRecord(*e, ctx->stream));
   return POPLAR_OK;
 }
