@@ -113,7 +113,7 @@ def test_embedding_fwd_bwd(arch, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("arch,V", [("gpt", 211), ("llama", 256), ("gpt", 1031)])
+@pytest.mark.parametrize("arch,V", [("gpt", 211), ("llama", 256), ("gpt", 1031), ("llama", 20011), ("gpt", 50257)])
 def test_head_loss_fwd_bwd(arch, V, dtype):
     B, S, H = 2, 48, 128
     cfg = pb.make_cfg(arch=arch, L=1, H=H, nh=2, F=128, S=S, V=V, dtype=dtype)
