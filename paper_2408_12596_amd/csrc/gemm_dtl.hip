@@ -485,8 +485,10 @@ int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n) {
     for (int sp : cand) {
       if (sp > 1 && (!plain || ksteps / sp < 8)) break;
       const double rounds = ceil((double)(t * sp) / tc.slots);
-      const double cost = rounds * ((double)cdiv(ksteps, sp) * tc.step + (sp > 1 ? tc.epi_atomic : tc.epi)) +
-                          (sp > 1 ? 3.0 + 2.7e-6 * (double)sp * mn : 0.0);
+      // two 128x128 blocks that really share a CU slow each other down a little more (measured)
+      const double step = (cfg == 2 && t * sp > 256) ? 0.68 : tc.step;
+      const double cost = rounds * ((double)cdiv(ksteps, sp) * step + (sp > 1 ? tc.epi_atomic : tc.epi)) +
+                          (sp > 1 ? 3.0 * n + 2.7e-6 * (double)sp * mn : 0.0);   // one zero fill per problem, atomics
       if (cost < best) { best = cost; pick = cfg; splits = sp; }
     }
   }
