@@ -467,17 +467,19 @@ int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n) {
 
   // Tile shape and K split by a small cost model, in units of one K step of a 256x256 tile on its CU.
   // 256x256 and 256x192 tiles run one block per CU, 128x128 tiles two per CU (each step a quarter of the
-  // work at ~80% of the efficiency); the epilogue costs a few K steps; the launch takes
-  // ceil(blocks / slots) rounds.  The 256x192 tile exists for the block count: widths such as 768 or
+  // work at ~80% of the efficiency), 64x64 tiles four per CU (latency-bound steps: they only pay when the
+  // larger tiles would leave most CUs idle, i.e. few rows and a narrow output); the epilogue costs a few
+  // K steps; the launch takes ceil(blocks / slots) rounds.  The 256x192 tile exists for the block count: widths such as 768 or
   // 2304 give whole rounds with it where 256-wide tiles leave a quarter of the CUs idle.  A split adds a
   // zero fill and float atomics, which the chip retires at a fixed rate (about 250 G/s measured)
   // whatever the tile shape: that term is what keeps the split count low.
   struct TileCfg { int bm, bn; double slots, step, epi, epi_atomic; };
-  static const TileCfg cfgs[3] = {{256, 256, 256.0, 1.0, 4.0, 6.0}, {256, 192, 256.0, 0.84, 3.0, 5.0}, {128, 128, 512.0, 0.6, 1.2, 2.0}};
+  static const TileCfg cfgs[4] = {{256, 256, 256.0, 1.0, 4.0, 6.0}, {256, 192, 256.0, 0.84, 3.0, 5.0}, {128, 128, 512.0, 0.6, 1.2, 2.0},
+                                  {64, 64, 1024.0, 0.36, 0.5, 0.8}};
   const int64_t K = a[0].K, ksteps = cdiv(K, DTL_BK);
   int pick = 0, splits = 1;
   double best = 1e300;
-  for (int cfg = 0; cfg < 3; ++cfg) {
+  for (int cfg = 0; cfg < 4; ++cfg) {
     const TileCfg& tc = cfgs[cfg];
     int64_t t = 0;
     for (int i = 0; i < n; ++i) t += cdiv(a[i].M, tc.bm) * cdiv(a[i].N, tc.bn);
@@ -485,8 +487,9 @@ int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n) {
     for (int sp : cand) {
       if (sp > 1 && (!plain || ksteps / sp < 8)) break;
       const double rounds = ceil((double)(t * sp) / tc.slots);
-      // two 128x128 blocks that really share a CU slow each other down a little more (measured)
-      const double step = (cfg == 2 && t * sp > 256) ? 0.68 : tc.step;
+      // two 128x128 blocks that really share a CU slow each other down a little more
+      // (measured; likewise the 64x64 blocks as a CU fills up)
+      const double step = cfg == 2 ? (t * sp > 256 ? 0.68 : tc.step) : cfg == 3 ? (t * sp > 768 ? 0.45 : t * sp > 256 ? 0.40 : tc.step) : tc.step;
       const double cost = rounds * ((double)cdiv(ksteps, sp) * step + (sp > 1 ? tc.epi_atomic : tc.epi)) +
                           (sp > 1 ? 3.0 * n + 2.7e-6 * (double)sp * mn : 0.0);   // one zero fill per problem, atomics
       if (cost < best) { best = cost; pick = cfg; splits = sp; }
@@ -525,9 +528,12 @@ int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n) {
   } else if (pick == 1) {
     if (atomic) launch_dtl<4, 2, 2, 3, true>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
     else launch_dtl<4, 2, 2, 3, false>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
-  } else {
+  } else if (pick == 2) {
     if (atomic) launch_dtl<2, 2, 2, 2, true>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
     else launch_dtl<2, 2, 2, 2, false>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
+  } else {
+    if (atomic) launch_dtl<2, 2, 1, 1, true>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
+    else launch_dtl<2, 2, 1, 1, false>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
   }
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;

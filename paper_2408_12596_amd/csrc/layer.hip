@@ -358,6 +358,12 @@ HeadPlan head_plan(const poplar_model_cfg& c, int B) {
   p.logits = take(T * p.ldl * es);
   p.row_loss = take(T * 4);
   p.dhf = take(T * H * es);
+  // Few rows: the input gradient of the head is a small matrix behind a contraction over the whole vocabulary,
+  // too few tiles to fill the chip.  It is then formed in float, which lets the GEMM split the vocabulary
+  // between blocks, and cast afterwards.  The float copy is reserved at every batch (the workspace stays
+  // affine in the batch) and used only at the small ones.
+  p.dhf32 = take(T * H * 4);
+  p.dhf_split = c.dtype == POPLAR_BF16 && cdiv(T, 256) * cdiv(H, 256) < 128;
   p.scratch = take(scratch_floats(c) * 4);
   p.bytes = at;
   return p;
@@ -404,7 +410,13 @@ int head_bwd_part(poplar_ctx* ctx, int B, const void* x, const void* gf, const v
   POPLAR_TRY(gemm(ctx, ga));
   ga = gemm_args(GEMM_NN, T, H, V, logits, hp.ldl, whead, H, dhf, H);
   ga.a_k_pad_zero = 1;   // the loss kernel zeroed columns V .. ldl of every row
-  POPLAR_TRY(gemm(ctx, ga));
+  if (hp.dhf_split) {
+    ga.C = ws + hp.dhf32; ga.c_float = 1;
+    POPLAR_TRY(gemm(ctx, ga));
+    POPLAR_TRY(cast_f32_to_lowp(s, c.dtype, (const float*)(ws + hp.dhf32), dhf, T * H));
+  } else {
+    POPLAR_TRY(gemm(ctx, ga));
+  }
   POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, dhf, x, gf, stats, nullptr, dx, d_gf, d_bf, accumulate, scratch, scratch_floats(c), llama));
   return POPLAR_OK;
 }

@@ -6,7 +6,7 @@
 
 struct SavedPlan { int64_t stats1, a, qkv, o, lse, x1, stats2, m, h, g, bytes; };
 struct BwdPlan { int64_t dh, dg, dm, dx1, dob, dqkv, da, delta, scratch, bytes; };
-struct HeadPlan { int64_t ldl, hf, stats, logits, row_loss, dhf, scratch, bytes; };
+struct HeadPlan { int64_t ldl, hf, stats, logits, row_loss, dhf, dhf32, scratch, bytes; bool dhf_split; };
 
 SavedPlan saved_plan(const poplar_model_cfg& c, int B);
 BwdPlan bwd_plan(const poplar_model_cfg& c, int B);
