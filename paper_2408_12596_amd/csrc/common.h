@@ -107,6 +107,19 @@ int layernorm_fwd(hipStream_t s, int dtype, int64_t T, int H, const void* x, con
 // dx = (dres ? dres : 0) + norm_bwd(dy); partial dgamma/dbeta to `partials` (float [nblk, 2, H]); then reduced into dg/db
 int layernorm_bwd(hipStream_t s, int dtype, int64_t T, int H, const void* dy, const void* x, const void* g, const float* stats,
                   const void* dres, void* dx, float* dg, float* db, int accumulate, float* partials, int64_t partials_elems, int rms);
+// Deferred second pass of the two-pass column reductions: out[j] (+)= sum over nchunks rows of partials
+// (row stride `stride`); columns [0, n0) go to out0, [n0, n) to out1.  n == 0: nothing to do.
+struct ReduceJob { const float* partials; int nchunks; int64_t stride; float* out0; float* out1; int64_t n0, n; };
+#define REDUCE_MAX_JOBS 8
+int reduce_group(hipStream_t s, const ReduceJob* jobs, int n, int accumulate);   // one launch for all jobs
+// as layernorm_bwd, but leaves the reduction of dgamma / dbeta to the caller (*job)
+int layernorm_bwd_partial(hipStream_t s, int dtype, int64_t T, int H, const void* dy, const void* x, const void* g, const float* stats,
+                          const void* dres, void* dx, float* dg, float* db, float* partials, int64_t partials_elems, int rms, ReduceJob* job);
+struct ColsumProblem { const void* x; int64_t ldx, N; float* out; };
+#define COLSUM_MAX_GROUP 4
+// first pass of up to four column sums over matrices of T rows in one launch; jobs[i] finishes problem i
+int colsum_partial(hipStream_t s, int dtype, int64_t T, const ColsumProblem* p, int n, float* partials, int64_t partials_elems,
+                   ReduceJob* jobs);
 int colsum(hipStream_t s, int dtype, int64_t T, int64_t N, const void* x, int64_t ldx, float* out, int accumulate,
            float* partials, int64_t partials_elems);
 int swiglu_fwd(hipStream_t s, int dtype, int64_t T, int F, const void* hgu, void* g);

@@ -396,28 +396,51 @@ __global__ void __launch_bounds__(256) norm_bwd_kernel(const T* __restrict__ dy,
     outp[j] = lds[j] + lds[2 * H + j] + lds[4 * H + j] + lds[6 * H + j];
 }
 
-// out[j] (+)= sum_c partials[c * stride + j]
+// out[j] (+)= sum_c partials[c * stride + j], for up to REDUCE_MAX_JOBS independent jobs in one launch.
 // 1024 threads = 32 columns x 32 chunk lanes: a block sums all chunks of its 32
 // columns (128-byte reads), the 32 lanes of a column meet in LDS in a fixed
-// order.  Columns [0, n0) go to out0, columns [n0, n) to out1 (dgamma | dbeta).
-__global__ void __launch_bounds__(1024) reduce_partials_kernel(const float* __restrict__ partials, int nchunks, int64_t stride,
-                                                                float* __restrict__ out0, float* __restrict__ out1, int64_t n0,
-                                                                int64_t n, int accumulate) {
+// order.  Columns [0, n0) of a job go to out0, columns [n0, n) to out1 (dgamma | dbeta).
+struct ReduceGroup { ReduceJob j[REDUCE_MAX_JOBS]; int block0[REDUCE_MAX_JOBS + 1]; int n; };
+__global__ void __launch_bounds__(1024) reduce_group_kernel(ReduceGroup g, int accumulate) {
+  int ji = 0;
+#pragma unroll
+  for (int i = 1; i < REDUCE_MAX_JOBS; ++i)
+    if (i < g.n && (int)blockIdx.x >= g.block0[i]) ji = i;
+  const ReduceJob& jb = g.j[ji];
   const int col = threadIdx.x & 31, cl = threadIdx.x >> 5;
-  const int64_t j = (int64_t)blockIdx.x * 32 + col;
+  const int64_t j = (int64_t)((int)blockIdx.x - g.block0[ji]) * 32 + col;
   float acc = 0.f;
-  if (j < n)
-    for (int c = cl; c < nchunks; c += 32) acc += partials[c * stride + j];
+  if (j < jb.n)
+    for (int c = cl; c < jb.nchunks; c += 32) acc += jb.partials[c * jb.stride + j];
   __shared__ float red[32][33];
   red[cl][col] = acc;
   __syncthreads();
-  if (cl == 0 && j < n) {
+  if (cl == 0 && j < jb.n) {
     float t = 0.f;
 #pragma unroll
     for (int k = 0; k < 32; ++k) t += red[k][col];
-    float* o = j < n0 ? out0 + j : out1 + (j - n0);
+    float* o = j < jb.n0 ? jb.out0 + j : jb.out1 + (j - jb.n0);
     *o = accumulate ? *o + t : t;
   }
+}
+
+int reduce_group(hipStream_t s, const ReduceJob* jobs, int n, int accumulate) {
+  if (n < 1) return POPLAR_OK;
+  if (n > REDUCE_MAX_JOBS) return poplar_fail(POPLAR_ERR_INVALID, "at most %d reductions per launch", REDUCE_MAX_JOBS);
+  ReduceGroup g;
+  int blocks = 0;
+  for (int i = 0; i < n; ++i) {
+    g.j[i] = jobs[i];
+    g.block0[i] = blocks;
+    blocks += (int)cdiv(jobs[i].n, 32);
+  }
+  for (int i = n; i < REDUCE_MAX_JOBS; ++i) g.j[i] = jobs[0];
+  for (int i = n; i <= REDUCE_MAX_JOBS; ++i) g.block0[i] = blocks;
+  g.n = n;
+  if (blocks == 0) return POPLAR_OK;
+  hipLaunchKernelGGL(reduce_group_kernel, dim3(blocks), dim3(1024), 0, s, g, accumulate);
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
 }
 
 static int norm_bwd_blocks(int64_t rows) {
@@ -445,8 +468,9 @@ static int norm_bwd_launch(hipStream_t s, int64_t rows, int H, const T* dy, cons
   return POPLAR_OK;
 }
 
-int layernorm_bwd(hipStream_t s, int dtype, int64_t T_, int H, const void* dy, const void* x, const void* g, const float* stats,
-                  const void* dres, void* dx, float* dg, float* db, int accumulate, float* partials, int64_t partials_elems, int rms) {
+int layernorm_bwd_partial(hipStream_t s, int dtype, int64_t T_, int H, const void* dy, const void* x, const void* g, const float* stats,
+                          const void* dres, void* dx, float* dg, float* db, float* partials, int64_t partials_elems, int rms, ReduceJob* job) {
+  job->n = 0;
   if (T_ == 0) return POPLAR_OK;
   int grid = norm_bwd_blocks(T_);
   if ((int64_t)grid * 2 * H > partials_elems) return poplar_fail(POPLAR_ERR_OOM, "norm backward scratch too small");
@@ -455,24 +479,37 @@ int layernorm_bwd(hipStream_t s, int dtype, int64_t T_, int H, const void* dy, c
     if (rms) POPLAR_TRY((norm_bwd_launch<T, true>(s, T_, H, (const T*)dy, (const T*)x, (const T*)g, stats, (const T*)dres, (T*)dx, partials, grid)));
     else POPLAR_TRY((norm_bwd_launch<T, false>(s, T_, H, (const T*)dy, (const T*)x, (const T*)g, stats, (const T*)dres, (T*)dx, partials, grid)));
   });
-  // dgamma = partials[:, 0, :], dbeta = partials[:, 1, :]: one launch covers both
-  const int64_t ncols = rms ? H : 2 * (int64_t)H;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((int)cdiv(ncols, 32)), dim3(1024), 0, s, partials, grid, (int64_t)2 * H, dg, db, (int64_t)H,
-                     ncols, accumulate);
-  POPLAR_LAUNCH_CHECK();
+  // dgamma = partials[:, 0, :], dbeta = partials[:, 1, :]: one job covers both
+  job->partials = partials; job->nchunks = grid; job->stride = (int64_t)2 * H;
+  job->out0 = dg; job->out1 = db; job->n0 = H; job->n = rms ? H : 2 * (int64_t)H;
   return POPLAR_OK;
+}
+
+int layernorm_bwd(hipStream_t s, int dtype, int64_t T_, int H, const void* dy, const void* x, const void* g, const float* stats,
+                  const void* dres, void* dx, float* dg, float* db, int accumulate, float* partials, int64_t partials_elems, int rms) {
+  ReduceJob job;
+  POPLAR_TRY(layernorm_bwd_partial(s, dtype, T_, H, dy, x, g, stats, dres, dx, dg, db, partials, partials_elems, rms, &job));
+  return job.n ? reduce_group(s, &job, 1, accumulate) : POPLAR_OK;
 }
 
 // ---------------------------------------------------------------------------
 // Column sums (bias gradients): out[n] (+)= sum_t x[t, n].
 // grid = (column strips of 64*VN, row chunks); 4 waves split the chunk's rows.
 // ---------------------------------------------------------------------------
+struct ColsumGroup { ColsumProblem p[COLSUM_MAX_GROUP]; int strip0[COLSUM_MAX_GROUP + 1]; int64_t col0[COLSUM_MAX_GROUP]; int n; int64_t ncat; };
+// Up to COLSUM_MAX_GROUP matrices of one row count in a launch; partials[chunk][ncat] holds their columns side by side.
 template <typename T>
-__global__ void __launch_bounds__(256) colsum_kernel(const T* __restrict__ x, int64_t ldx, int64_t rows, int64_t N, int rows_per_chunk,
-                                                      float* __restrict__ partials) {
+__global__ void __launch_bounds__(256) colsum_kernel(ColsumGroup g, int64_t rows, int rows_per_chunk, float* __restrict__ partials) {
   constexpr int VN = Vec<T>::N;
+  int pi = 0;
+#pragma unroll
+  for (int i = 1; i < COLSUM_MAX_GROUP; ++i)
+    if (i < g.n && (int)blockIdx.x >= g.strip0[i]) pi = i;
+  const T* __restrict__ x = (const T*)g.p[pi].x;
+  const int64_t ldx = g.p[pi].ldx, N = g.p[pi].N;
+  const int strip = (int)blockIdx.x - g.strip0[pi];
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * VN;
+  const int64_t c = ((int64_t)strip * 64 + lane) * VN;
   const int64_t r0 = (int64_t)blockIdx.y * rows_per_chunk;
   int64_t r1 = r0 + rows_per_chunk;
   if (r1 > rows) r1 = rows;
@@ -492,28 +529,54 @@ __global__ void __launch_bounds__(256) colsum_kernel(const T* __restrict__ x, in
   for (int k = 0; k < VN; ++k) lds[wv][lane * VN + k] = acc[k];
   __syncthreads();
   for (int j = threadIdx.x; j < 64 * VN; j += 256) {
-    int64_t col = (int64_t)blockIdx.x * 64 * VN + j;
-    if (col < N) partials[(int64_t)blockIdx.y * N + col] = lds[0][j] + lds[1][j] + lds[2][j] + lds[3][j];
+    int64_t col = (int64_t)strip * 64 * VN + j;
+    if (col < N) partials[(int64_t)blockIdx.y * g.ncat + g.col0[pi] + col] = lds[0][j] + lds[1][j] + lds[2][j] + lds[3][j];
   }
 }
 
-int colsum(hipStream_t s, int dtype, int64_t T_, int64_t N, const void* x, int64_t ldx, float* out, int accumulate,
-           float* partials, int64_t partials_elems) {
-  if (T_ == 0 || N == 0) return POPLAR_OK;
+// first pass only: jobs[i] receives the reduction that finishes problem i
+int colsum_partial(hipStream_t s, int dtype, int64_t T_, const ColsumProblem* p, int n, float* partials, int64_t partials_elems,
+                   ReduceJob* jobs) {
+  if (n < 1 || n > COLSUM_MAX_GROUP) return poplar_fail(POPLAR_ERR_INVALID, "1 to %d column sums per launch", COLSUM_MAX_GROUP);
+  for (int i = 0; i < n; ++i) jobs[i].n = 0;
+  if (T_ == 0) return POPLAR_OK;
   const int VN = dtype == POPLAR_BF16 ? 8 : 4;
-  if (N % VN) return poplar_fail(POPLAR_ERR_INVALID, "colsum needs N %% %d == 0", VN);
-  int strips = (int)cdiv(N, 64 * VN);
+  ColsumGroup g;
+  int strips = 0;
+  int64_t ncat = 0;
+  for (int i = 0; i < n; ++i) {
+    if (p[i].N % VN) return poplar_fail(POPLAR_ERR_INVALID, "colsum needs N %% %d == 0", VN);
+    g.p[i] = p[i];
+    g.strip0[i] = strips; g.col0[i] = ncat;
+    strips += (int)cdiv(p[i].N, 64 * VN);
+    ncat += p[i].N;
+  }
+  for (int i = n; i < COLSUM_MAX_GROUP; ++i) { g.p[i] = p[0]; g.col0[i] = 0; }
+  for (int i = n; i <= COLSUM_MAX_GROUP; ++i) g.strip0[i] = strips;
+  g.n = n; g.ncat = ncat;
+  if (strips == 0) return POPLAR_OK;
   int chunks = (int)cdiv(2048, strips);
   if (chunks > cdiv(T_, 32)) chunks = (int)cdiv(T_, 32);
   if (chunks < 1) chunks = 1;
   int rpc = (int)cdiv(T_, chunks);
   chunks = (int)cdiv(T_, rpc);
-  if ((int64_t)chunks * N > partials_elems) return poplar_fail(POPLAR_ERR_OOM, "colsum scratch too small");
-  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(colsum_kernel<T>, dim3(strips, chunks), dim3(256), 0, s, (const T*)x, ldx, T_, N, rpc, partials));
+  if ((int64_t)chunks * ncat > partials_elems) return poplar_fail(POPLAR_ERR_OOM, "colsum scratch too small");
+  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(colsum_kernel<T>, dim3(strips, chunks), dim3(256), 0, s, g, T_, rpc, partials));
   POPLAR_LAUNCH_CHECK();
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((int)cdiv(N, 32)), dim3(1024), 0, s, partials, chunks, N, out, out, N, N, accumulate);
-  POPLAR_LAUNCH_CHECK();
+  for (int i = 0; i < n; ++i) {
+    jobs[i].partials = partials + g.col0[i]; jobs[i].nchunks = chunks; jobs[i].stride = ncat;
+    jobs[i].out0 = p[i].out; jobs[i].out1 = p[i].out; jobs[i].n0 = p[i].N; jobs[i].n = p[i].N;
+  }
   return POPLAR_OK;
+}
+
+int colsum(hipStream_t s, int dtype, int64_t T_, int64_t N, const void* x, int64_t ldx, float* out, int accumulate,
+           float* partials, int64_t partials_elems) {
+  if (T_ == 0 || N == 0) return POPLAR_OK;
+  ColsumProblem p = {x, ldx, N, out};
+  ReduceJob job;
+  POPLAR_TRY(colsum_partial(s, dtype, T_, &p, 1, partials, partials_elems, &job));
+  return reduce_group(s, &job, 1, accumulate);
 }
 
 // ---------------------------------------------------------------------------

@@ -138,6 +138,14 @@ SavedPlan saved_plan(const poplar_model_cfg& c, int B) {
   return p;
 }
 
+// The layer's backward pass keeps the partial sums of both norms and of the bias gradients until one
+// reduction at its end finishes them all: two norm regions, then one for the grouped column sums.
+static int64_t norm_scratch_floats(const poplar_model_cfg& c) { return (int64_t)512 * 2 * c.hidden; }   // <= 512 blocks x 2 x H
+static int64_t colsum_scratch_floats(const poplar_model_cfg& c) {
+  // chunks <= 2048 / strips + 1 and columns <= strips * 512: chunks x columns <= 2048 * 512 + columns
+  return (int64_t)2048 * 512 + 5 * (int64_t)c.hidden + c.ffn;
+}
+
 int64_t scratch_floats(const poplar_model_cfg& c) {
   // norm backward: <= 512 blocks x 2 x H; column sums: <= (2048/strips + 1) chunks x N
   const int64_t H = c.hidden, F = c.ffn;
@@ -161,7 +169,7 @@ BwdPlan bwd_plan(const poplar_model_cfg& c, int B) {
   p.dqkv = take(T * 3 * H * es);
   p.da = take(T * H * es);
   p.delta = take((int64_t)B * c.n_head * c.seq * 4);
-  p.scratch = take(scratch_floats(c) * 4);
+  p.scratch = take((2 * norm_scratch_floats(c) + colsum_scratch_floats(c)) * 4);
   p.bytes = at;
   return p;
 }
@@ -241,19 +249,28 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
   const void *a = sv + sp.a, *qkv = sv + sp.qkv, *o = sv + sp.o, *x1 = sv + sp.x1, *m = sv + sp.m, *h = sv + sp.h, *g = sv + sp.g;
   void *dh = ws + bp.dh, *dm = ws + bp.dm, *dx1 = ws + bp.dx1, *dob = ws + bp.dob, *dqkv = ws + bp.dqkv, *da = ws + bp.da;
   float* delta = (float*)(ws + bp.delta);
-  float* scratch = (float*)(ws + bp.scratch);
-  const int64_t scratch_n = scratch_floats(c);
+  const int64_t norm_n = norm_scratch_floats(c), cs_n = colsum_scratch_floats(c);
+  float *scratch_n2 = (float*)(ws + bp.scratch), *scratch_n1 = scratch_n2 + norm_n, *scratch_cs = scratch_n1 + norm_n;
   const float beta = accumulate ? 1.f : 0.f;
   GemmArgs ga;
+  // Bias gradients (column sums of dy, dh, dx1, dqkv) are taken in one launch at the end, when all four
+  // matrices exist; their reductions and those of the two norms' gamma / beta gradients share one more.
+  ColsumProblem cs[COLSUM_MAX_GROUP];
+  int ncs = 0;
+  ReduceJob jobs[REDUCE_MAX_JOBS];
+  int njobs = 0;
+  const bool dy_is_dx = dy == dx;   // allowed by the interface: dy is then gone at the end, so what reads it cannot wait
 
   // MLP down projection: out = x1 + g W2^T + bm2
-  if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, H, dy, H, G(lo.bm2), accumulate, scratch, scratch_n));
+  if (!llama) {
+    if (dy_is_dx) POPLAR_TRY(colsum(s, c.dtype, T, H, dy, H, G(lo.bm2), accumulate, scratch_cs, cs_n));
+    else cs[ncs++] = ColsumProblem{dy, H, H, G(lo.bm2)};
+  }
   // the four weight-gradient GEMMs are collected and run as one group at the end: their operands (dy, dh,
   // dx1, dqkv and the stashed activations) all stay valid until then
   GemmArgs dw[4];
   dw[0] = gemm_args(GEMM_TN, H, F, T, dy, H, g, F, G(lo.w2), F);
   dw[0].c_float = 1; dw[0].beta = beta;
-  const bool dy_is_dx = dy == dx;   // allowed by the interface: dy is then gone at the end, so its GEMM cannot wait
   if (dy_is_dx) POPLAR_TRY(gemm(ctx, dw[0]));
   if (llama) {
     void* dg = ws + bp.dg;
@@ -264,16 +281,16 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
     ga = gemm_args(GEMM_NN, T, F, H, dy, H, P(lo.w2), F, dh, F);
     ga.act = ACT_GELU_BWD; ga.aux = const_cast<void*>(h); ga.ldaux = F;
     POPLAR_TRY(gemm(ctx, ga));
-    POPLAR_TRY(colsum(s, c.dtype, T, F, dh, F, G(lo.bm1), accumulate, scratch, scratch_n));
+    cs[ncs++] = ColsumProblem{dh, F, F, G(lo.bm1)};
   }
   // MLP up projection
   dw[1] = gemm_args(GEMM_TN, hw, H, T, dh, hw, m, H, G(lo.w1), H);
   ga = gemm_args(GEMM_NN, T, H, hw, dh, hw, P(lo.w1), H, dm, H);
   POPLAR_TRY(gemm(ctx, ga));
   // second norm; dx1 = dy + norm_bwd(dm)
-  POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, dm, x1, P(lo.g2), stats2, dy, dx1, G(lo.g2), G(lo.b2), accumulate, scratch, scratch_n, llama));
+  POPLAR_TRY(layernorm_bwd_partial(s, c.dtype, T, (int)H, dm, x1, P(lo.g2), stats2, dy, dx1, G(lo.g2), G(lo.b2), scratch_n2, norm_n, llama, &jobs[njobs++]));
   // attention output projection: x1 = x + o Wo^T + bo
-  if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, H, dx1, H, G(lo.bo), accumulate, scratch, scratch_n));
+  if (!llama) cs[ncs++] = ColsumProblem{dx1, H, H, G(lo.bo)};
   dw[2] = gemm_args(GEMM_TN, H, H, T, dx1, H, o, H, G(lo.wo), H);
   ga = gemm_args(GEMM_NN, T, H, H, dx1, H, P(lo.wo), H, dob, H);
   POPLAR_TRY(gemm(ctx, ga));
@@ -281,12 +298,17 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
   POPLAR_TRY(attn_bwd(ctx, B, qkv, o, dob, lse, dqkv, delta));
   if (llama) POPLAR_TRY(rope_inplace(s, c.dtype, B, c.seq, c.n_head, (int)(H / c.n_head), dqkv, 3 * H, -1.0f));
   // QKV projection
-  if (!llama) POPLAR_TRY(colsum(s, c.dtype, T, 3 * H, dqkv, 3 * H, G(lo.bqkv), accumulate, scratch, scratch_n));
+  if (!llama) cs[ncs++] = ColsumProblem{dqkv, 3 * H, 3 * H, G(lo.bqkv)};
   dw[3] = gemm_args(GEMM_TN, 3 * H, H, T, dqkv, 3 * H, a, H, G(lo.wqkv), H);
   ga = gemm_args(GEMM_NN, T, H, 3 * H, dqkv, 3 * H, P(lo.wqkv), H, da, H);
   POPLAR_TRY(gemm(ctx, ga));
   // first norm; dx = dx1 + norm_bwd(da)
-  POPLAR_TRY(layernorm_bwd(s, c.dtype, T, (int)H, da, x_in, P(lo.g1), stats1, dx1, dx, G(lo.g1), G(lo.b1), accumulate, scratch, scratch_n, llama));
+  POPLAR_TRY(layernorm_bwd_partial(s, c.dtype, T, (int)H, da, x_in, P(lo.g1), stats1, dx1, dx, G(lo.g1), G(lo.b1), scratch_n1, norm_n, llama, &jobs[njobs++]));
+  if (ncs) {
+    POPLAR_TRY(colsum_partial(s, c.dtype, T, cs, ncs, scratch_cs, cs_n, jobs + njobs));
+    njobs += ncs;
+  }
+  POPLAR_TRY(reduce_group(s, jobs, njobs, accumulate));
   for (int i = 1; i < 4; ++i) { dw[i].c_float = 1; dw[i].beta = beta; }
   return dy_is_dx ? gemm_group(ctx, dw + 1, 3) : gemm_group(ctx, dw, 4);
 }
