@@ -819,6 +819,118 @@ __global__ void __launch_bounds__(256) xent_kernel(T* __restrict__ logits, int64
   }
 }
 
+// The same operation with each row held in registers between the two passes, so that the logits cross the
+// memory system once in each direction (the two-pass kernel above reads them twice: a row of 100 KB times the
+// rows in flight is far beyond the L2).  One block of 1024 threads per CU walks rows blockIdx.x, + gridDim.x, ...;
+// a thread owns vectors tid, tid + 1024, ... of the row (at most NV).  The next row's loads are issued before
+// the block-wide reduction of the current one and stay in flight through its second pass.
+template <typename T, int NV>
+__global__ void __launch_bounds__(1024) xent_row_kernel(T* __restrict__ logits, int64_t ld, int V, int64_t rows,
+                                                         const int32_t* __restrict__ targets, int64_t tgt_ld, int S,
+                                                         float loss_scale, float* __restrict__ row_loss) {
+  constexpr int VN = Vec<T>::N;
+  const int nvec = (int)(ld / VN);
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  __shared__ float smx[2][16], ssum[2][16], stl[2];
+  Vec<T> cur[NV], nxt[NV];
+  auto fetch = [&](Vec<T>* dst, int64_t t) __attribute__((always_inline)) {
+    const T* row = logits + t * ld;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int i = threadIdx.x + j * 1024;
+      if (i < nvec) dst[j].load(row + (int64_t)i * VN);
+    }
+  };
+  int64_t t = blockIdx.x;
+  if (t < rows) fetch(cur, t);
+  for (int par = 0; t < rows; t += gridDim.x, par ^= 1) {
+    T* row = logits + t * ld;
+    const int tgt = targets[(t / S) * tgt_ld + (t % S)];
+    // this thread's share of max and sum; exponentials in the base-2 domain (one fma + v_exp_f32 each); only a
+    // row's last vectors can hold padding columns, the others skip the column test
+    constexpr float L2E = 1.4426950408889634f;
+    float mx = -INFINITY, sum = 0.f;
+    if (tgt >= 0) {
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int i = threadIdx.x + j * 1024;
+        if (i < nvec) {
+          float f[VN];
+          cur[j].unpack(f);
+          if (i * VN + VN <= V) {
+#pragma unroll
+            for (int k = 0; k < VN; ++k) mx = fmaxf(mx, f[k]);
+          } else {
+#pragma unroll
+            for (int k = 0; k < VN; ++k) if (i * VN + k < V) mx = fmaxf(mx, f[k]);
+          }
+        }
+      }
+      const float m2 = mx * L2E;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int i = threadIdx.x + j * 1024;
+        if (i < nvec) {
+          float f[VN];
+          cur[j].unpack(f);
+          if (i * VN + VN <= V) {
+#pragma unroll
+            for (int k = 0; k < VN; ++k) sum += __builtin_amdgcn_exp2f(fmaf(f[k], L2E, -m2));
+          } else {
+#pragma unroll
+            for (int k = 0; k < VN; ++k) if (i * VN + k < V) sum += __builtin_amdgcn_exp2f(fmaf(f[k], L2E, -m2));
+          }
+        }
+      }
+    }
+    const int64_t tn = t + gridDim.x;
+    if (tn < rows) fetch(nxt, tn);
+    const float wm = wave_max(mx);
+    sum = (mx == -INFINITY) ? 0.f : sum * __expf(mx - wm);
+    sum = wave_sum(sum);
+    if (lane == 0) { smx[par][wv] = wm; ssum[par][wv] = sum; }
+    // the target logit is read (and has arrived) before the barrier, its owner overwrites it after
+    if (threadIdx.x == 0) stl[par] = tgt >= 0 ? to_float<T>(row[tgt]) : 0.f;
+    __syncthreads();   // one barrier per row: the LDS slots alternate, a wave two rows ahead is impossible
+    float lse = 0.f;
+    if (tgt >= 0) {
+      float bm = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) bm = fmaxf(bm, smx[par][w]);
+      float bs = 0.f;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) bs += (smx[par][w] == -INFINITY) ? 0.f : ssum[par][w] * __expf(smx[par][w] - bm);
+      lse = bm + logf(bs);
+    }
+    if (threadIdx.x == 0) row_loss[t] = tgt >= 0 ? lse - stl[par] : 0.f;
+    const float l2 = lse * L2E;
+    const float scale = tgt >= 0 ? loss_scale : 0.f;   // a row without a prediction gets zeros
+    const int tv = tgt >= 0 ? tgt / VN : -1;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int i = threadIdx.x + j * 1024;
+      if (i < nvec) {
+        float f[VN];
+        cur[j].unpack(f);
+        if (i * VN + VN <= V) {
+#pragma unroll
+          for (int k = 0; k < VN; ++k) f[k] = __builtin_amdgcn_exp2f(fmaf(f[k], L2E, -l2)) * scale;
+        } else {
+#pragma unroll
+          for (int k = 0; k < VN; ++k) f[k] = i * VN + k < V ? __builtin_amdgcn_exp2f(fmaf(f[k], L2E, -l2)) * scale : 0.f;
+        }
+        if (i == tv) {
+#pragma unroll
+          for (int k = 0; k < VN; ++k) if (k == tgt % VN) f[k] -= scale;
+        }
+        Vec<T> o; o.pack(f); o.store(row + (int64_t)i * VN);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
+  }
+}
+
 __global__ void __launch_bounds__(256) loss_sum_kernel(const float* __restrict__ row_loss, int64_t n, float scale, float* __restrict__ loss) {
   float acc = 0.f;
   for (int64_t i = threadIdx.x; i < n; i += 256) acc += row_loss[i];
@@ -834,7 +946,22 @@ int xent_fwd_bwd(hipStream_t s, int dtype, int64_t T_, int V, int64_t ld, void* 
   if (T_ == 0) return POPLAR_OK;
   const int VN = dtype == POPLAR_BF16 ? 8 : 4;
   if (ld % VN || ld < V) return poplar_fail(POPLAR_ERR_INVALID, "logit row stride %lld invalid for V=%d", (long long)ld, V);
-  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(xent_kernel<T>, dim3((unsigned)T_), dim3(256), 0, s, (T*)logits, ld, V, targets, tgt_ld, S, loss_scale, row_loss));
+  const int64_t nvec = ld / VN;
+  if (dtype == POPLAR_BF16 && nvec <= 8 * 1024) {
+    static int cus = 0;   // one block per CU (1024 threads with the row in registers fill it)
+    if (!cus) {
+      int dev = 0;
+      POPLAR_CHECK_HIP(hipGetDevice(&dev));
+      POPLAR_CHECK_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    }
+    const dim3 grid((unsigned)std::min<int64_t>(T_, cus));
+    if (nvec <= 4 * 1024)
+      hipLaunchKernelGGL((xent_row_kernel<bf16, 4>), grid, dim3(1024), 0, s, (bf16*)logits, ld, V, T_, targets, tgt_ld, S, loss_scale, row_loss);
+    else
+      hipLaunchKernelGGL((xent_row_kernel<bf16, 8>), grid, dim3(1024), 0, s, (bf16*)logits, ld, V, T_, targets, tgt_ld, S, loss_scale, row_loss);
+  } else {
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(xent_kernel<T>, dim3((unsigned)T_), dim3(256), 0, s, (T*)logits, ld, V, targets, tgt_ld, S, loss_scale, row_loss));
+  }
   POPLAR_LAUNCH_CHECK();
   hipLaunchKernelGGL(loss_sum_kernel, dim3(1), dim3(256), 0, s, row_loss, T_, loss_scale, loss);
   POPLAR_LAUNCH_CHECK();
