@@ -249,8 +249,8 @@ typedef struct poplar_profile {
   int64_t accounted_bytes;      /* poplar_step_accounted_bytes(stage, batch) */
   double flops;                 /* algorithmic flop of forward + backward */
   float loss;
-  /* filled only with poplar_set_kernel_timing(ctx, 1): every GEMM / attention
-   * launch of the step bracketed by two events on the context's stream */
+  /* filled only after poplar_set_kernel_timing: every selected GEMM / attention
+   * launch of the step carries two events on the context's stream */
   double t_gemm, gemm_flops;    /* summed launch durations (s) and algorithmic flop 2*M*N*K of the GEMM launches */
   double t_attn, attn_flops;    /* same for the attention kernels: 2 S^2 H fwd, 5 S^2 H bwd per sample (causal) */
   int32_t n_gemm, n_attn;       /* launches counted */
@@ -266,6 +266,8 @@ int poplar_device_info(int32_t* compute_units, int32_t* clock_khz, int64_t* memo
  * records wall time per step because no single operation explains it (Section
  * "Time Consumed Estimation"); this switch adds the per-kernel view needed to
  * place the GEMM and attention kernels against the matrix-core roofline. */
+/* on: 0 none, 1 the GEMM launches, 2 the attention launches, 3 both (each timed
+ * launch costs a few microseconds of step time); anything else ERR_INVALID. */
 int poplar_set_kernel_timing(poplar_ctx* ctx, int32_t on);
 
 /* model.step(local_batch) of Algorithm 1 at a ZeRO stage, timed:

@@ -36,7 +36,7 @@ struct poplar_ctx {
   bool bound;
   std::vector<hipEvent_t> events;  // pool reused by every profiled step
   size_t ev_next;                  // next unused event of the pool in the running step
-  bool kernel_timing;              // bracket every GEMM / attention launch with events
+  int kernel_timing;               // bit 0: time every GEMM launch with events, bit 1: every attention launch
   bool in_step;                    // a profiled step is being enqueued
   std::vector<TimedLaunch> launches;
 };

@@ -22,7 +22,7 @@ struct LaunchTimer {
   TimedLaunch tl;
   // hands out the two events, unrecorded
   int begin(int kind, double flops) {
-    on = ctx->kernel_timing && ctx->in_step;
+    on = ((ctx->kernel_timing >> kind) & 1) && ctx->in_step;
     tl.a = nullptr; tl.b = nullptr;
     if (!on) return POPLAR_OK;
     tl.kind = kind; tl.flops = flops;

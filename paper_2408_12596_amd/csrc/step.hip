@@ -14,7 +14,7 @@ extern "C" int poplar_create(const poplar_model_cfg* cfg, void* hip_stream, popl
   memset(&c->st, 0, sizeof c->st);
   c->bound = false;
   c->ev_next = 0;
-  c->kernel_timing = false;
+  c->kernel_timing = 0;
   c->in_step = false;
   *out = c;
   return POPLAR_OK;
@@ -165,7 +165,8 @@ extern "C" int poplar_device_info(int32_t* compute_units, int32_t* clock_khz, in
 
 extern "C" int poplar_set_kernel_timing(poplar_ctx* ctx, int32_t on) {
   if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
-  ctx->kernel_timing = on != 0;
+  if (on < 0 || on > 3) return poplar_fail(POPLAR_ERR_INVALID, "kernel timing selector %d: 0 off, 1 GEMM, 2 attention, 3 both", on);
+  ctx->kernel_timing = on;
   return POPLAR_OK;
 }
 

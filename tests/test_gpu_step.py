@@ -374,3 +374,38 @@ def test_search_moves_to_the_next_stage_when_nothing_fits():
     # nothing fits anywhere
     tiny = Rank(model, "bf16", 3, world, 0, max_batch=2, cap_bytes=1000)
     assert tiny.ctx.search_stage(1) == (-1, 0, [])
+
+
+def test_kernel_timing_selects_and_counts_the_launches():
+    """Per-launch timing inside a profiled step: what is selected is counted with its algorithmic flop, the rest is not,
+    and the summed kernel time fits inside the step's forward + backward time."""
+    model = dict(arch="gpt", L=2, H=128, nh=2, F=256, S=64, V=211)
+    B = 3
+    r = Rank(model, "bf16", 1, 2, 0, B)
+    L, H, F, S, V = model["L"], model["H"], model["F"], model["S"], model["V"]
+    T = B * S
+    gemm_flop = 3 * (L * 2 * T * (4 * H * H + 2 * H * F) + 2 * T * H * V)
+    attn_flop = L * B * 7 * S * S * H                     # causal: 2 S^2 H forward + 5 S^2 H backward per sample
+    p = r.ctx.profile_step(1, B)
+    assert p["n_gemm"] == 0 and p["n_attn"] == 0 and p["t_gemm"] == 0.0
+    for sel in (1, 2, 3):
+        r.ctx.set_kernel_timing(sel)
+        p = r.ctx.profile_step(1, B)
+        if sel & 1:
+            # forward 4, backward 4 input gradients + the weight gradients as one grouped launch or four; head 3
+            assert p["n_gemm"] in (L * 9 + 3, L * 12 + 3)
+            assert p["gemm_flops"] == pytest.approx(gemm_flop, rel=1e-12)
+            assert 0.0 < p["t_gemm"] < p["t_fwd"] + p["t_bwd"]
+        else:
+            assert p["n_gemm"] == 0 and p["t_gemm"] == 0.0
+        if sel & 2:
+            assert p["n_attn"] == 2 * L
+            assert p["attn_flops"] == pytest.approx(attn_flop, rel=1e-12)
+            assert 0.0 < p["t_attn"] < p["t_fwd"] + p["t_bwd"]
+        else:
+            assert p["n_attn"] == 0 and p["t_attn"] == 0.0
+    with pytest.raises(pb.PoplarError):
+        r.ctx.set_kernel_timing(4)
+    r.ctx.set_kernel_timing(0)
+    p = r.ctx.profile_step(1, B)
+    assert p["n_gemm"] == 0 and p["n_attn"] == 0
