@@ -135,8 +135,8 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
   __shared__ __attribute__((aligned(1024))) char stage1[STAGE];
 
   // XCD-aware renumbering over the tiles of the whole group (blocks are dealt round-robin to the 8 XCDs; each
-  // XCD gets a contiguous run of tiles), then the problem the tile belongs to, then bands of 8 tile rows with
-  // the column index fastest inside a band
+  // XCD gets a contiguous run of tiles), then the problem the tile belongs to, then bands of 8 tile rows
+  // (order inside a band: see below)
   int id = blockIdx.x;
   {
     const int per = gp.start[DTL_MAX_GROUP] / 8;
@@ -152,8 +152,13 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
   const int band_id = id / band;
   const int rows_in_band = min(8, p.tiles_m - band_id * 8);
   const int in_band = id - band_id * band;
-  const int tile_m = band_id * 8 + in_band % rows_in_band;
-  const int tile_n = in_band / rows_in_band;
+  // Order inside a band: the tiles that run on an XCD at one time (32 CUs, one or two blocks each) should share as
+  // few operand panels as possible, i.e. form a near-square patch.  With many tile columns the row index runs
+  // fastest (8 rows x 4-8 columns at a time); with up to 8 columns the column index does (whole tile rows: 4-9 rows x
+  // all columns), which also keeps a row's tiles in the same round when a band is smaller than a round.
+  const bool n_fast = p.tiles_n <= 8;
+  const int tile_m = band_id * 8 + (n_fast ? in_band / p.tiles_n : in_band % rows_in_band);
+  const int tile_n = n_fast ? in_band % p.tiles_n : in_band / rows_in_band;
   const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
   const int64_t kbeg = (int64_t)blockIdx.y * p.k_per_split;
   const int64_t kend = min(p.K, kbeg + p.k_per_split);
