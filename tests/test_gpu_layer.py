@@ -73,6 +73,14 @@ def test_layer_fwd_bwd_matches_oracle(case, dtype):
     sync()
     assert rel_l2(to_np(grads), 2 * got) <= 1e-6
 
+    # dx may share dy's buffer (the interface allows it): same results
+    d_io = d_dy.clone()
+    grads2 = torch.full((n,), float("nan"), device=DEV)
+    ctx.layer_bwd(B, d_x, d_io, d_params, saved, d_io, grads2, 0, ws, wsb)
+    sync()
+    assert rel_l2(to_np(d_io), to_np(d_dx)) <= 1e-6
+    assert rel_l2(to_np(grads2), got) <= 1e-5
+
 
 def test_layer_bwd_rejects_small_workspace():
     case = LAYER_CASES[0]
@@ -113,7 +121,7 @@ def test_embedding_fwd_bwd(arch, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("arch,V", [("gpt", 211), ("llama", 256), ("gpt", 1031), ("llama", 20011), ("gpt", 50257)])
+@pytest.mark.parametrize("arch,V", [("gpt", 211), ("llama", 256), ("gpt", 1031), ("llama", 20011), ("gpt", 50257), ("llama", 70001)])
 def test_head_loss_fwd_bwd(arch, V, dtype):
     B, S, H = 2, 48, 128
     cfg = pb.make_cfg(arch=arch, L=1, H=H, nh=2, F=128, S=S, V=V, dtype=dtype)
