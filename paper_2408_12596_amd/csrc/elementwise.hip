@@ -410,8 +410,19 @@ __global__ void __launch_bounds__(1024) reduce_group_kernel(ReduceGroup g, int a
   const int col = threadIdx.x & 31, cl = threadIdx.x >> 5;
   const int64_t j = (int64_t)((int)blockIdx.x - g.block0[ji]) * 32 + col;
   float acc = 0.f;
-  if (j < jb.n)
-    for (int c = cl; c < jb.nchunks; c += 32) acc += jb.partials[c * jb.stride + j];
+  if (j < jb.n) {
+    // eight independent partial sums: eight loads in flight per thread instead of a chain of dependent ones
+    float a[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a[u] = 0.f;
+    int c = cl;
+    for (; c + 7 * 32 < jb.nchunks; c += 8 * 32) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) a[u] += jb.partials[(c + u * 32) * jb.stride + j];
+    }
+    for (; c < jb.nchunks; c += 32) a[0] += jb.partials[c * jb.stride + j];
+    acc = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+  }
   __shared__ float red[32][33];
   red[cl][col] = acc;
   __syncthreads();
@@ -444,8 +455,8 @@ int reduce_group(hipStream_t s, const ReduceJob* jobs, int n, int accumulate) {
 }
 
 static int norm_bwd_blocks(int64_t rows) {
-  int64_t b = cdiv(rows, 16);  // at least 4 rows per wave
-  if (b > 512) b = 512;
+  int64_t b = cdiv(rows, 16);  // at least 4 rows per wave; at most three blocks per CU of a 256-CU chip (what its registers allow: whole rounds)
+  if (b > 768) b = 768;
   if (b < 1) b = 1;
   return (int)b;
 }

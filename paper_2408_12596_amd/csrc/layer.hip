@@ -140,17 +140,17 @@ SavedPlan saved_plan(const poplar_model_cfg& c, int B) {
 
 // The layer's backward pass keeps the partial sums of both norms and of the bias gradients until one
 // reduction at its end finishes them all: two norm regions, then one for the grouped column sums.
-static int64_t norm_scratch_floats(const poplar_model_cfg& c) { return (int64_t)512 * 2 * c.hidden; }   // <= 512 blocks x 2 x H
+static int64_t norm_scratch_floats(const poplar_model_cfg& c) { return (int64_t)768 * 2 * c.hidden; }   // <= 768 blocks x 2 x H
 static int64_t colsum_scratch_floats(const poplar_model_cfg& c) {
   // chunks <= 2048 / strips + 1 and columns <= strips * 512: chunks x columns <= 2048 * 512 + columns
   return (int64_t)2048 * 512 + 5 * (int64_t)c.hidden + c.ffn;
 }
 
 int64_t scratch_floats(const poplar_model_cfg& c) {
-  // norm backward: <= 512 blocks x 2 x H; column sums: <= (2048/strips + 1) chunks x N
+  // norm backward: <= 768 blocks x 2 x H; column sums: <= (2048/strips + 1) chunks x N
   const int64_t H = c.hidden, F = c.ffn;
   const int64_t maxN = std::max<int64_t>(3 * H, 2 * F);
-  const int64_t a = 512 * 2 * H;
+  const int64_t a = 768 * 2 * H;
   const int64_t b = 2048 * 64 * 8 + 2 * maxN;
   return std::max(a, b);
 }
