@@ -2,6 +2,7 @@
 on one MI355X, through libpoplar's C ABI.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B]
+                    [--curve-report] [--layer-report] [--model-report]
 
 A step is poplar_profile_step(stage 1, B): embedding, 12 layers forward, head
 and loss, backward, Adam on the rank's 1/8 shard, all on synthetic inputs that
@@ -157,6 +158,98 @@ def layer_report(pb, torch, iters=5):
     return out
 
 
+MODEL_CONFIGS = {   # the larger configurations: (model, world, ZeRO stage, local batches)
+    "gpt-1.3B, ZeRO-2 on a 1/4 shard": (dict(arch="gpt", L=24, H=2048, nh=16, F=8192, S=2048, V=50257), 4, 2, (1, 2, 4, 8)),
+    "llama-7B, ZeRO-3 on a 1/16 shard": (dict(arch="llama", L=32, H=4096, nh=32, F=11008, S=2048, V=32000), 16, 3, (1, 2, 4)),
+}
+
+
+class DeviceRank:
+    """One simulated rank whose state is drawn on the device (same recipe as synth.init_params: matrices N(0, 0.02),
+    gains 1, biases 0; seed 0), for models too large to draw on the host in a bench run."""
+
+    def __init__(self, pb, torch, model, world, stage, max_b, cap_bytes=0):
+        dev = "cuda:0"
+        self.cfg = pb.make_cfg(**model, dtype="bf16", world=world, rank=0, zero_stage=stage, cap_bytes=cap_bytes)
+        self.P = pb.model_param_count(self.cfg)
+        off, ln, valid = (0, self.P, self.P) if stage == 0 else pb.shard_range(self.P, world, 0)
+        self.valid = valid
+        g = torch.Generator(device=dev).manual_seed(0)
+        flat = torch.zeros(max(self.P, off + ln), device=dev)
+        for name, shape, o in pb.model_spec(self.cfg):
+            n = int(np.prod(shape))
+            if len(shape) == 2:
+                flat[o:o + n].normal_(0.0, 0.02, generator=g)
+            elif name.split(".")[-1] in ("g1", "g2", "gf"):
+                flat[o:o + n] = 1.0
+        params = flat[:self.P].to(torch.bfloat16)
+        master = flat[off:off + ln].clone()
+        own = master.to(torch.bfloat16) if stage == 3 else None
+        del flat
+        m, v = torch.zeros(ln, device=dev), torch.zeros(ln, device=dev)
+        grads = torch.zeros(self.P if stage < 2 else ln, device=dev)
+        tok = torch.randint(0, model["V"], (max_b, model["S"] + 1), generator=g, device=dev, dtype=torch.int32)
+        self.wsb = pb.step_workspace_bytes(self.cfg, stage, max_b)
+        ws = torch.empty(self.wsb + 256, dtype=torch.uint8, device=dev)
+        loss = torch.zeros(1, device=dev)
+        self.ctx = pb.Context(self.cfg, torch.cuda.current_stream().cuda_stream)
+        self.ctx.bind_state(params, master, m, v, grads, tok, max_b, ws, self.wsb, loss, own_shard=own, adam_t=1, lr=1e-4)
+
+
+def model_report(pb, torch):
+    """Whole steps of the larger configurations (1.3 B parameters at ZeRO-2, the Llama-7B shape at ZeRO-3) over their
+    local-batch sweeps, then the allocation stress on the 1.3 B model: odd local batches, Algorithm 1 under an
+    emulated cap of 40 GiB at stages 1-3, and Algorithm 2 over four devices whose step times are the measured curve
+    times 1, 1.5, 2 and 3, to a global batch of 64."""
+    out = {}
+    for name, (model, world, stage, batches) in MODEL_CONFIGS.items():
+        r = DeviceRank(pb, torch, model, world, stage, max(batches))
+        rows = []
+        for B in batches:
+            r.ctx.profile_step(stage, B)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            profs = [r.ctx.profile_step(stage, B) for _ in range(2)]
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / 2
+            p = profs[-1]
+            rows.append({"local_batch": B, "ms_per_step": dt * 1e3, "samples_per_s": B / dt, "tflops": p["flops"] / dt / 1e12,
+                         "frac_mfma_peak": p["flops"] / dt / 1e12 / PEAK_BF16_TFLOPS, "t_consumed_ms": p["t_consumed"] * 1e3,
+                         "t_adam_ms": p["t_adam"] * 1e3, "adam_gbs": 30.0 * r.valid / p["t_adam"] / 1e9,
+                         "t_reduce_ms": p["t_reduce_bwd"] * 1e3, "t_gather_ms": (p["t_gather_fwd"] + p["t_gather_bwd"]) * 1e3,
+                         "accounted_gib": p["accounted_bytes"] / 2**30, "loss": p["loss"]})
+        out[name] = {"params": r.P, "shard_elems": r.valid, "sweep": rows}
+        del r
+        torch.cuda.empty_cache()
+    model, world = MODEL_CONFIGS["gpt-1.3B, ZeRO-2 on a 1/4 shard"][0], 4
+    cap = 40 * 2**30
+    stress = {"cap_bytes": cap, "stages": {}}
+    for stage in (1, 2, 3):
+        r = DeviceRank(pb, torch, model, world, stage, 16, cap_bytes=cap)
+        mbs, samples = r.ctx.search_mbs(stage)
+        pts = {p["batch"]: p["t_consumed"] for p in samples}
+        entry = {"mbs": mbs, "visited": sorted(pts), "t_consumed_ms": [pts[b] * 1e3 for b in sorted(pts)]}
+        if stage == 2:
+            odd = {}
+            for b in (3, 5, 7, 13):
+                if b <= mbs:
+                    r.ctx.profile_step(stage, b)
+                    pr = r.ctx.profile_step(stage, b)
+                    odd[str(b)] = {"t_consumed_ms": pr["t_consumed"] * 1e3, "tflops": pr["flops"] / pr["t_consumed"] / 1e12}
+            entry["odd_batches"] = odd
+        bs = sorted(pts)
+        curves = [(bs, [pts[b] * k for b in bs], mbs) for k in (1.0, 1.5, 2.0, 3.0)]
+        cm = pb.comm_model(r.P, 4, stage, 2.0, 4.0, 7 * 153e9) if stage >= 2 else {"t_micro": 0.0}
+        al = pb.allocate(stage, 64, curves, cm["t_micro"])
+        entry["allocate_gbs64"] = {"t_comm_ms": cm["t_micro"] * 1e3, "gmbs": al["gmbs"], "b": al["b"], "gas": al["gas"], "lbs": al["lbs"],
+                                   "T_ms": al["T"] * 1e3}
+        stress["stages"][str(stage)] = entry
+        del r
+        torch.cuda.empty_cache()
+    out["allocation stress, gpt-1.3B, cap 40 GiB, devices 1 : 1.5 : 2 : 3, gbs 64"] = stress
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -167,6 +260,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--curve-report", action="store_true", help="add the dense-sweep / spline / Algorithm 2 report to the line")
     ap.add_argument("--layer-report", action="store_true", help="add one-layer timings at the larger configurations' shapes")
+    ap.add_argument("--model-report", action="store_true", help="add whole-model steps of the 1.3B and Llama-7B-shaped configurations "
+                    "and the allocation stress under an emulated 40 GiB cap (a few minutes, about 120 GB of HBM)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one rank on ONE GPU (the ZeRO world is simulated by shard offsets); --gpus must be 1", file=sys.stderr)
@@ -260,6 +355,8 @@ def main():
         out["curve_report"] = curve_report(pb, ctx, P, max_b)
     if args.layer_report:
         out["layer_report"] = layer_report(pb, torch)
+    if args.model_report:
+        out["model_report"] = model_report(pb, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(model, flat, tok, tgt)
     print(json.dumps(out))
