@@ -396,6 +396,98 @@ __global__ void __launch_bounds__(256) norm_bwd_kernel(const T* __restrict__ dy,
     outp[j] = lds[j] + lds[2 * H + j] + lds[4 * H + j] + lds[6 * H + j];
 }
 
+// The same for wide rows (hidden above 1024), where a row no longer fits one wave's registers: a block of four
+// waves per row, thread t owning vectors t, t + 256, ... (at most NVW); the two row sums cross the waves through
+// LDS (one barrier per row, slots alternating); every column belongs to one thread, so the block's gamma / beta
+// partial sums go straight from registers to `partials` [nblocks, 2, H] (beta half unused for RMSNorm).
+template <typename T, int NVW, bool RMS>
+__global__ void __launch_bounds__(256) norm_bwd_wide_kernel(const T* __restrict__ dy, const T* __restrict__ x, const T* __restrict__ g,
+                                                             const float* __restrict__ stats, const T* __restrict__ dres,
+                                                             T* __restrict__ dx, float* __restrict__ partials, int64_t rows, int H) {
+  constexpr int VN = Vec<T>::N;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  float accg[NVW][VN], accb[NVW][VN], gam[NVW][VN];
+#pragma unroll
+  for (int i = 0; i < NVW; ++i) {
+    const int c = (i * 256 + threadIdx.x) * VN;
+#pragma unroll
+    for (int k = 0; k < VN; ++k) { accg[i][k] = 0.f; accb[i][k] = 0.f; gam[i][k] = 0.f; }
+    if (c < H) { Vec<T> v; v.load(g + c); v.unpack(gam[i]); }
+  }
+  struct RowRaw { Vec<T> x[NVW], dy[NVW], rs[NVW]; float mean, rstd; };
+  auto fetch = [&](int64_t r, RowRaw& q) {
+#pragma unroll
+    for (int i = 0; i < NVW; ++i) {
+      const int c = (i * 256 + threadIdx.x) * VN;
+      if (c < H) {
+        q.x[i].load(x + r * H + c);
+        q.dy[i].load(dy + r * H + c);
+        if (dres) q.rs[i].load(dres + r * H + c);
+      }
+    }
+    q.mean = stats[2 * r]; q.rstd = stats[2 * r + 1];
+  };
+  __shared__ float red[2][2][4];
+  RowRaw cur, nxt;
+  int64_t r = blockIdx.x;
+  if (r < rows) fetch(r, cur);
+  for (int par = 0; r < rows; r += gridDim.x, par ^= 1) {
+    if (r + gridDim.x < rows) fetch(r + gridDim.x, nxt);
+    const float mean = cur.mean, rstd = cur.rstd;
+    float xh[NVW][VN], dxh[NVW][VN];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NVW; ++i) {
+      const int c = (i * 256 + threadIdx.x) * VN;
+      if (c < H) {
+        float xv[VN], dv[VN];
+        cur.x[i].unpack(xv);
+        cur.dy[i].unpack(dv);
+#pragma unroll
+        for (int k = 0; k < VN; ++k) {
+          xh[i][k] = (xv[k] - mean) * rstd;
+          dxh[i][k] = dv[k] * gam[i][k];
+          accg[i][k] += dv[k] * xh[i][k];
+          if (!RMS) accb[i][k] += dv[k];
+          s1 += dxh[i][k];
+          s2 += dxh[i][k] * xh[i][k];
+        }
+      }
+    }
+    s1 = RMS ? 0.f : wave_sum(s1);
+    s2 = wave_sum(s2);
+    if (lane == 0) { red[par][0][wv] = s1; red[par][1][wv] = s2; }
+    __syncthreads();   // a wave cannot be two rows ahead of another: the slots of a parity are free again when it writes them
+    s1 = (red[par][0][0] + red[par][0][1] + red[par][0][2] + red[par][0][3]) / H;
+    s2 = (red[par][1][0] + red[par][1][1] + red[par][1][2] + red[par][1][3]) / H;
+#pragma unroll
+    for (int i = 0; i < NVW; ++i) {
+      const int c = (i * 256 + threadIdx.x) * VN;
+      if (c < H) {
+        float o[VN], rs[VN];
+        Vec<T> v;
+        if (dres) cur.rs[i].unpack(rs);
+#pragma unroll
+        for (int k = 0; k < VN; ++k) o[k] = rstd * (dxh[i][k] - s1 - xh[i][k] * s2) + (dres ? rs[k] : 0.f);
+        v.pack(o); v.store(dx + r * H + c);
+      }
+    }
+    cur = nxt;
+  }
+  float* outp = partials + (int64_t)blockIdx.x * 2 * H;
+#pragma unroll
+  for (int i = 0; i < NVW; ++i) {
+    const int c = (i * 256 + threadIdx.x) * VN;
+    if (c < H) {
+#pragma unroll
+      for (int k = 0; k < VN; ++k) {
+        outp[c + k] = accg[i][k];
+        if (!RMS) outp[H + c + k] = accb[i][k];
+      }
+    }
+  }
+}
+
 // out[j] (+)= sum_c partials[c * stride + j], for up to REDUCE_MAX_JOBS independent jobs in one launch.
 // 1024 threads = 32 columns x 32 chunk lanes: a block sums all chunks of its 32
 // columns (128-byte reads), the 32 lanes of a column meet in LDS in a fixed
@@ -454,6 +546,9 @@ int reduce_group(hipStream_t s, const ReduceJob* jobs, int n, int accumulate) {
   return POPLAR_OK;
 }
 
+// wide rows: a block per row at a time; two blocks per CU keep enough loads in flight, more would only add partials
+static int norm_bwd_wide_blocks(int64_t rows) { return (int)std::min<int64_t>(rows, 512); }
+
 static int norm_bwd_blocks(int64_t rows) {
   int64_t b = cdiv(rows, 16);  // at least 4 rows per wave; at most three blocks per CU of a 256-CU chip (what its registers allow: whole rounds)
   if (b > 768) b = 768;
@@ -466,14 +561,23 @@ static int norm_bwd_launch(hipStream_t s, int64_t rows, int H, const T* dy, cons
                            T* dx, float* partials, int grid) {
   constexpr int VN = Vec<T>::N;
   int need = (int)cdiv(H, 64 * VN);
+  if (need > 2) {   // the row-per-wave kernel would run out of registers
+    const int needw = (int)cdiv(H, 256 * VN);
+#define NORM_BWD_WIDE(NVW) \
+  hipLaunchKernelGGL((norm_bwd_wide_kernel<T, NVW, RMS>), dim3(grid), dim3(256), 0, s, dy, x, g, stats, dres, dx, partials, rows, H)
+    if (needw <= 1) NORM_BWD_WIDE(1);
+    else if (needw <= 2) NORM_BWD_WIDE(2);
+    else if (needw <= 4) NORM_BWD_WIDE(4);
+    else return poplar_fail(POPLAR_ERR_INVALID, "hidden %d too large for the norm backward kernel", H);
+#undef NORM_BWD_WIDE
+    POPLAR_LAUNCH_CHECK();
+    return POPLAR_OK;
+  }
   size_t lds = (size_t)8 * H * sizeof(float);
 #define NORM_BWD_CASE(NVV) \
   hipLaunchKernelGGL((norm_bwd_kernel<T, NVV, RMS>), dim3(grid), dim3(256), lds, s, dy, x, g, stats, dres, dx, partials, rows, H)
   if (need <= 1) NORM_BWD_CASE(1);
-  else if (need <= 2) NORM_BWD_CASE(2);
-  else if (need <= 4) NORM_BWD_CASE(4);
-  else if (need <= 8) NORM_BWD_CASE(8);
-  else return poplar_fail(POPLAR_ERR_INVALID, "hidden %d too large for the norm backward kernel", H);
+  else NORM_BWD_CASE(2);
 #undef NORM_BWD_CASE
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
@@ -483,9 +587,9 @@ int layernorm_bwd_partial(hipStream_t s, int dtype, int64_t T_, int H, const voi
                           const void* dres, void* dx, float* dg, float* db, float* partials, int64_t partials_elems, int rms, ReduceJob* job) {
   job->n = 0;
   if (T_ == 0) return POPLAR_OK;
-  int grid = norm_bwd_blocks(T_);
+  const bool wide = cdiv(H, 64 * (dtype == POPLAR_BF16 ? 8 : 4)) > 2;
+  int grid = wide ? norm_bwd_wide_blocks(T_) : norm_bwd_blocks(T_);
   if ((int64_t)grid * 2 * H > partials_elems) return poplar_fail(POPLAR_ERR_OOM, "norm backward scratch too small");
-  if ((size_t)8 * H * sizeof(float) > 160 * 1024) return poplar_fail(POPLAR_ERR_INVALID, "hidden %d too large for the norm backward kernel", H);
   DISPATCH_DTYPE(dtype, {
     if (rms) POPLAR_TRY((norm_bwd_launch<T, true>(s, T_, H, (const T*)dy, (const T*)x, (const T*)g, stats, (const T*)dres, (T*)dx, partials, grid)));
     else POPLAR_TRY((norm_bwd_launch<T, false>(s, T_, H, (const T*)dy, (const T*)x, (const T*)g, stats, (const T*)dres, (T*)dx, partials, grid)));

@@ -22,6 +22,9 @@ LAYER_CASES = [
     # ragged: tokens and widths that are not multiples of the GEMM tiles
     dict(arch="gpt", L=1, H=192, nh=3, F=328, S=77, V=1, B=3),
     dict(arch="llama", L=1, H=256, nh=2, F=1000, S=130, V=1, B=1),
+    # wide rows (the norm backward takes a block per row above hidden 1024 in bf16, 512 in fp32), not a multiple of its 256 lanes
+    dict(arch="gpt", L=1, H=1536, nh=12, F=512, S=40, V=1, B=2),
+    dict(arch="llama", L=1, H=1152, nh=9, F=256, S=33, V=1, B=1),
 ]
 
 
