@@ -427,52 +427,65 @@ __global__ void __launch_bounds__(256) norm_bwd_wide_kernel(const T* __restrict_
     }
     q.mean = stats[2 * r]; q.rstd = stats[2 * r + 1];
   };
+  // PF rows are in flight per block: one row's arithmetic is far shorter than a memory round trip
+  constexpr int PF = NVW == 1 ? 4 : NVW == 2 ? 3 : 2;
   __shared__ float red[2][2][4];
-  RowRaw cur, nxt;
-  int64_t r = blockIdx.x;
-  if (r < rows) fetch(r, cur);
-  for (int par = 0; r < rows; r += gridDim.x, par ^= 1) {
-    if (r + gridDim.x < rows) fetch(r + gridDim.x, nxt);
-    const float mean = cur.mean, rstd = cur.rstd;
-    float xh[NVW][VN], dxh[NVW][VN];
-    float s1 = 0.f, s2 = 0.f;
+  RowRaw q[PF];
+  const int64_t r0 = blockIdx.x, step = gridDim.x;
 #pragma unroll
-    for (int i = 0; i < NVW; ++i) {
-      const int c = (i * 256 + threadIdx.x) * VN;
-      if (c < H) {
-        float xv[VN], dv[VN];
-        cur.x[i].unpack(xv);
-        cur.dy[i].unpack(dv);
+  for (int j = 0; j < PF; ++j)
+    if (r0 + j * step < rows) fetch(r0 + j * step, q[j]);
+  int par = 0;
+  for (int64_t rb = r0; rb < rows; rb += PF * step) {
 #pragma unroll
-        for (int k = 0; k < VN; ++k) {
-          xh[i][k] = (xv[k] - mean) * rstd;
-          dxh[i][k] = dv[k] * gam[i][k];
-          accg[i][k] += dv[k] * xh[i][k];
-          if (!RMS) accb[i][k] += dv[k];
-          s1 += dxh[i][k];
-          s2 += dxh[i][k] * xh[i][k];
+    for (int j = 0; j < PF; ++j) {
+      const int64_t r = rb + j * step;
+      if (r < rows) {   // uniform over the block
+        RowRaw& cur = q[j];
+        const float mean = cur.mean, rstd = cur.rstd;
+        float xh[NVW][VN], dxh[NVW][VN], rs[NVW][VN];
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < NVW; ++i) {
+          const int c = (i * 256 + threadIdx.x) * VN;
+          if (c < H) {
+            float xv[VN], dv[VN];
+            cur.x[i].unpack(xv);
+            cur.dy[i].unpack(dv);
+            if (dres) cur.rs[i].unpack(rs[i]);
+#pragma unroll
+            for (int k = 0; k < VN; ++k) {
+              xh[i][k] = (xv[k] - mean) * rstd;
+              dxh[i][k] = dv[k] * gam[i][k];
+              accg[i][k] += dv[k] * xh[i][k];
+              if (!RMS) accb[i][k] += dv[k];
+              s1 += dxh[i][k];
+              s2 += dxh[i][k] * xh[i][k];
+            }
+          }
+        }
+        // the buffer is free again: fetch the row PF steps ahead before waiting on anything
+        if (r + PF * step < rows) fetch(r + PF * step, q[j]);
+        s1 = RMS ? 0.f : wave_sum(s1);
+        s2 = wave_sum(s2);
+        if (lane == 0) { red[par][0][wv] = s1; red[par][1][wv] = s2; }
+        __syncthreads();   // a wave cannot be two rows ahead of another: the slots of a parity are free again when it writes them
+        s1 = (red[par][0][0] + red[par][0][1] + red[par][0][2] + red[par][0][3]) / H;
+        s2 = (red[par][1][0] + red[par][1][1] + red[par][1][2] + red[par][1][3]) / H;
+        par ^= 1;
+#pragma unroll
+        for (int i = 0; i < NVW; ++i) {
+          const int c = (i * 256 + threadIdx.x) * VN;
+          if (c < H) {
+            float o[VN];
+            Vec<T> v;
+#pragma unroll
+            for (int k = 0; k < VN; ++k) o[k] = rstd * (dxh[i][k] - s1 - xh[i][k] * s2) + (dres ? rs[i][k] : 0.f);
+            v.pack(o); v.store(dx + r * H + c);
+          }
         }
       }
     }
-    s1 = RMS ? 0.f : wave_sum(s1);
-    s2 = wave_sum(s2);
-    if (lane == 0) { red[par][0][wv] = s1; red[par][1][wv] = s2; }
-    __syncthreads();   // a wave cannot be two rows ahead of another: the slots of a parity are free again when it writes them
-    s1 = (red[par][0][0] + red[par][0][1] + red[par][0][2] + red[par][0][3]) / H;
-    s2 = (red[par][1][0] + red[par][1][1] + red[par][1][2] + red[par][1][3]) / H;
-#pragma unroll
-    for (int i = 0; i < NVW; ++i) {
-      const int c = (i * 256 + threadIdx.x) * VN;
-      if (c < H) {
-        float o[VN], rs[VN];
-        Vec<T> v;
-        if (dres) cur.rs[i].unpack(rs);
-#pragma unroll
-        for (int k = 0; k < VN; ++k) o[k] = rstd * (dxh[i][k] - s1 - xh[i][k] * s2) + (dres ? rs[k] : 0.f);
-        v.pack(o); v.store(dx + r * H + c);
-      }
-    }
-    cur = nxt;
   }
   float* outp = partials + (int64_t)blockIdx.x * 2 * H;
 #pragma unroll
@@ -547,7 +560,9 @@ int reduce_group(hipStream_t s, const ReduceJob* jobs, int n, int accumulate) {
 }
 
 // wide rows: a block per row at a time; two blocks per CU keep enough loads in flight, more would only add partials
-static int norm_bwd_wide_blocks(int64_t rows) { return (int)std::min<int64_t>(rows, 512); }
+static int norm_bwd_wide_blocks(int64_t rows, int vectors_per_thread) {
+  return (int)std::min<int64_t>(rows, vectors_per_thread == 1 ? 768 : 512);   // thin threads: a third block per CU for the loads in flight
+}
 
 static int norm_bwd_blocks(int64_t rows) {
   int64_t b = cdiv(rows, 16);  // at least 4 rows per wave; at most three blocks per CU of a 256-CU chip (what its registers allow: whole rounds)
@@ -588,7 +603,7 @@ int layernorm_bwd_partial(hipStream_t s, int dtype, int64_t T_, int H, const voi
   job->n = 0;
   if (T_ == 0) return POPLAR_OK;
   const bool wide = cdiv(H, 64 * (dtype == POPLAR_BF16 ? 8 : 4)) > 2;
-  int grid = wide ? norm_bwd_wide_blocks(T_) : norm_bwd_blocks(T_);
+  int grid = wide ? norm_bwd_wide_blocks(T_, (int)cdiv(H, 256 * (dtype == POPLAR_BF16 ? 8 : 4))) : norm_bwd_blocks(T_);
   if ((int64_t)grid * 2 * H > partials_elems) return poplar_fail(POPLAR_ERR_OOM, "norm backward scratch too small");
   DISPATCH_DTYPE(dtype, {
     if (rms) POPLAR_TRY((norm_bwd_launch<T, true>(s, T_, H, (const T*)dy, (const T*)x, (const T*)g, stats, (const T*)dres, (T*)dx, partials, grid)));
