@@ -69,6 +69,18 @@ __device__ inline void fa_load_kib(__amdgpu_buffer_rsrc_t rsrc, char* dst, uint3
 }
 
 // ---- LDS image of 64 rows x D values ----------------------------------------------------------
+// 16-byte chunk c of row r lies at chunk position c ^ fa_swz<D>(r) of the row.  The LDS serves 64 banks of
+// 4 bytes per cycle (counters: with a swizzle built for 32 banks half of the LDS cycles were bank conflicts), so a
+// 16-byte read is conflict-free when 16 consecutive rows land on the 16 chunk slots of a 256-byte window, and a
+// transposing read (four rows x 64 bytes per 32 lanes) when rows R .. R+3 land on its four 64-byte slots.
+//   D = 64 (128-byte rows: the row's parity is address bit 7): position bit 2 <- row bit 1, bits 1, 0 <- row bits 2, 3
+//   D = 128 (256-byte rows): position bits 3, 2 <- row bits 1, 0; bits 1, 0 <- row bits 3, 2
+template <int D>
+__device__ inline int fa_swz(int row) {
+  if (D == 64) return (((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1);
+  return ((row & 3) << 2) | ((row >> 2) & 3);
+}
+
 template <int D>
 struct Rows64 {
   static constexpr int ROWB = D * 2;            // 128 or 256 bytes
@@ -81,30 +93,32 @@ struct Rows64 {
   // byte offset, relative to row 0 of the tile, of the 16 bytes that belong at LDS position idx*1024 + lane*16
   __device__ static uint32_t lane_offset(int idx, int lane, int64_t ld) {
     const int row = idx * RPL + lane / CPR;
-    const int c = (lane % CPR) ^ (row & 7);
+    const int c = (lane % CPR) ^ fa_swz<D>(row);
     return (uint32_t)(((int64_t)row * ld + c * 8) * 2);
   }
   // A fragment, rows as M index: row `row` of the tile, k-slice s (16 columns), lane half g
   __device__ static bf16x8 frag(const char* lds, int row, int s, int g) {
-    return *reinterpret_cast<const bf16x8*>(lds + row * ROWB + (((2 * s + g) ^ (row & 7)) << 4));
+    return *reinterpret_cast<const bf16x8*>(lds + row * ROWB + (((2 * s + g) ^ fa_swz<D>(row)) << 4));
   }
-  // per-lane base of the transposed fragments of column tile ct (32 columns)
-  __device__ static int tr_base(int ct, int lane) {
+  // per-lane bases of the transposed fragments of column tile ct (32 columns): first read (rows 0-7 of a
+  // 16-row chunk) in .x, second read (rows 8-15) in .y
+  __device__ static int2 tr_base(int ct, int lane) {
     const int l16 = lane & 15, gi = (lane >> 4) & 1, g = lane >> 5;
     const int row = 4 * g + (l16 >> 2);                       // row inside the 16-row chunk (first read)
     const int chunk = ct * 4 + gi * 2 + ((l16 & 3) >> 1);     // logical 16-byte chunk of the lane's 4 values
-    return row * ROWB + ((chunk ^ (row & 7)) << 4) + (l16 & 1) * 8;
+    return make_int2(row * ROWB + ((chunk ^ fa_swz<D>(row)) << 4) + (l16 & 1) * 8,
+                     (row + 8) * ROWB + ((chunk ^ fa_swz<D>(row + 8)) << 4) + (l16 & 1) * 8);
   }
   // A fragment, rows as reduction index: 16-row chunk j, k-slots in probability order.
   // Written as assembly: the compiler would make the builtin form wait for every global -> LDS load in
   // flight (it cannot tell the stage being filled from the one being read).  It does not see these reads
   // complete either: the caller waits with fa_wait_lds() before it uses the fragment.
-  __device__ static bf16x8 frag_tr(const char* lds, int base, int j) {
-    const char* q = lds + base + j * 16 * ROWB;
-    const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)q;
+  __device__ static bf16x8 frag_tr(const char* lds, int2 base, int j) {
+    const uint32_t a0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)(lds + base.x + j * 16 * ROWB);
+    const uint32_t a1 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)(lds + base.y + j * 16 * ROWB);
     intx2 lo, hi;
-    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
-    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(addr + 8 * ROWB));
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a0));
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(a1));
     intx4 f = {lo[0], lo[1], hi[0], hi[1]};
     return __builtin_bit_cast(bf16x8, f);
   }
@@ -195,7 +209,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const b
   bf16x8 qf[D / 16];
   load_row_frags<D>(qf, base, ld, q, S, g);
   floatx16 oacc[D / 32];
-  int trb[D / 32];
+  int2 trb[D / 32];
 #pragma unroll
   for (int ct = 0; ct < D / 32; ++ct) { zero_acc(oacc[ct]); trb[ct] = Img::tr_base(ct, lane); }
   float m_run = -INFINITY, l_run = 0.f;
@@ -371,7 +385,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(cons
   const float lse2 = q < S ? lse[stat] : 0.f;
   const float dl = q < S ? delta[stat] : 0.f;
   floatx16 dq[D / 32];
-  int trb[D / 32];
+  int2 trb[D / 32];
 #pragma unroll
   for (int ct = 0; ct < D / 32; ++ct) { zero_acc(dq[ct]); trb[ct] = Img::tr_base(ct, lane); }
   const int kv_end = causal ? min(S, q0 + 128) : S;
@@ -497,7 +511,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 2 : 1) flash_bwd_dkv_kernel(con
   load_row_frags<D>(kf, qp + H, ld, kv, S, g);
   load_row_frags<D>(vf, qp + 2 * H, ld, kv, S, g);
   floatx16 dk[D / 32], dv[D / 32];
-  int trb[D / 32];
+  int2 trb[D / 32];
 #pragma unroll
   for (int ct = 0; ct < D / 32; ++ct) { zero_acc(dk[ct]); zero_acc(dv[ct]); trb[ct] = Img::tr_base(ct, lane); }
   const float c2 = scale * LOG2E;
