@@ -79,6 +79,8 @@ struct GemmArgs {
   const void* residual;   // lowp [M,N] (ldc) or null, added after activation
   int act;                // ACT_GELU: aux <- pre-activation, C <- gelu;  ACT_GELU_BWD: C <- acc * gelu'(aux)
   void* aux; int64_t ldaux;
+  float* a_rowsum;        // TN only, or null: a_rowsum[m] (+)= sum_k A(k, m), the bias gradient next to a weight gradient;
+  int a_rowsum_accumulate;  //   honoured by the direct-to-LDS kernel only (ask gemm_bf16_dtl_accepts first)
   int a_k_pad_zero;       // NN only: A's rows hold zeros from column K up to K rounded up to 64 (lda covers them)
   // Optional: events that receive the start and the end of the kernel itself (hipExtLaunchKernelGGL), without the
   // barrier packets a recorded event puts between kernels.  Honoured by the direct-to-LDS kernel only.
@@ -89,6 +91,7 @@ int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a);
 int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a);   // POPLAR_ERR_UNIMPLEMENTED when the shape is outside its preconditions
 // up to four problems of one layout and one K in a single launch; POPLAR_ERR_UNIMPLEMENTED (nothing launched) when it cannot
 int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n);
+bool gemm_bf16_dtl_accepts(const GemmArgs* a, int n);   // preconditions only, nothing launched
 int gemm(hipStream_t s, int dtype, const GemmArgs& a);
 
 // attention on the fused qkv activation [B*S, 3H]; o [B*S, H]; lse float [B, nh, S]

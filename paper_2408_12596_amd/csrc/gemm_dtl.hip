@@ -44,6 +44,8 @@ struct DtlGemmParams {
   int c_float, act;
   float beta;
   int tiles_m, tiles_n, k_per_split;
+  float* rowsum;        // TN only, may be null: rowsum[m] (+)= sum_k A(k, m)
+  int rowsum_accumulate;
 };
 
 // Up to four problems of one layout, tile shape and K extent in a single launch: the block index runs
@@ -242,6 +244,14 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
+  // Row sums of A (the bias gradient that belongs to a weight gradient): the waves on the first column of tiles
+  // also add up their A fragments, lane by lane (a lane holds 8 k-values of one row: four two-element dot
+  // products with ones); the two k-halves of a row meet in the epilogue.
+  const bool do_rs = LAYOUT == GEMM_TN && p.rowsum != nullptr && tile_n == 0 && wn == 0;
+  float rs[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) rs[i] = 0.f;
+
   // Fragments of k-slice kk of a stage; f = 0 .. TM+TN-1 in the order the MFMAs first need them
   bf16x8 fa[2][TM], fb[2][TN];
   auto read_frag = [&](const char* st, int kk, int buf, int f) __attribute__((always_inline)) {
@@ -270,6 +280,19 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
       for (int l = 0; l < nload; ++l)
         if (l * NM / nload == x) load_one(lst, l);
       __builtin_amdgcn_sched_barrier(0);
+    }
+    if (LAYOUT == GEMM_TN && do_rs) {
+      typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+      const bf16x2_t one2 = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const bf16x8 a8 = fa[buf][i];
+        const bf16x2_t a01 = {a8[0], a8[1]}, a23 = {a8[2], a8[3]}, a45 = {a8[4], a8[5]}, a67 = {a8[6], a8[7]};
+        rs[i] = __builtin_amdgcn_fdot2_f32_bf16(a01, one2, rs[i], false);
+        rs[i] = __builtin_amdgcn_fdot2_f32_bf16(a23, one2, rs[i], false);
+        rs[i] = __builtin_amdgcn_fdot2_f32_bf16(a45, one2, rs[i], false);
+        rs[i] = __builtin_amdgcn_fdot2_f32_bf16(a67, one2, rs[i], false);
+      }
     }
   };
 
@@ -316,6 +339,19 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
 #pragma unroll
   for (int j = 0; j < TN; ++j) asm volatile("" ::"v"(fb[0][j]));
   __syncthreads();
+
+  if (LAYOUT == GEMM_TN && do_rs) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const float v = rs[i] + __shfl_xor(rs[i], 32, 64);   // lanes l and l + 32 hold the two k-halves of row l
+      const int64_t m = m0 + wm + i * 32 + lr;
+      if (lk == 0 && m < p.M) {
+        float* o = p.rowsum + m;
+        if (ATOMIC) unsafeAtomicAdd(o, v);
+        else *o = p.rowsum_accumulate ? *o + v : v;
+      }
+    }
+  }
 
   if (ATOMIC) {
 #pragma unroll
@@ -450,7 +486,18 @@ static int dtl_prepare(const GemmArgs& a, DtlGemmParams& p) {
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc; p.ldaux = a.ldaux;
   p.a_records = (uint32_t)a_bytes; p.b_records = (uint32_t)b_bytes;
   p.c_float = a.c_float; p.act = a.act; p.beta = a.beta;
+  if (a.a_rowsum && a.layout != GEMM_TN) return POPLAR_ERR_UNIMPLEMENTED;
+  p.rowsum = a.a_rowsum; p.rowsum_accumulate = a.a_rowsum_accumulate;
   return POPLAR_OK;
+}
+
+// true when the direct-to-LDS kernel takes these problems as one launch (n > 1) or one each (n == 1)
+bool gemm_bf16_dtl_accepts(const GemmArgs* a, int n) {
+  if (n < 1 || n > DTL_MAX_GROUP) return false;
+  DtlGemmParams p;
+  for (int i = 0; i < n; ++i)
+    if (a[i].layout != a[0].layout || a[i].K != a[0].K || dtl_prepare(a[i], p) != POPLAR_OK) return false;
+  return true;
 }
 
 // Up to DTL_MAX_GROUP problems of one layout and one K in a single launch (a plain GEMM is a group of one).
@@ -517,6 +564,8 @@ int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n) {
   for (int i = n; i <= DTL_MAX_GROUP; ++i) gp.start[i] = (int)tiles;
   for (int i = n; i < DTL_MAX_GROUP; ++i) gp.g[i] = gp.g[0];
   if (atomic) {
+    for (int i = 0; i < n; ++i)
+      if (a[i].a_rowsum && !a[i].a_rowsum_accumulate) POPLAR_TRY(fill_zero(s, a[i].a_rowsum, a[i].M * 4));
     for (int i = 0; i < n; ++i) {
       if (a[i].beta != 0.f) continue;
       if (a[i].ldc != a[i].N) {

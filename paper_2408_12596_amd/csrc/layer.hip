@@ -46,6 +46,7 @@ static int gemm(poplar_ctx* ctx, const GemmArgs& a) {
     if (r == POPLAR_OK) return t.done();
     if (r != POPLAR_ERR_UNIMPLEMENTED) return r;
   }
+  if (a.a_rowsum) return poplar_fail(POPLAR_ERR_UNIMPLEMENTED, "row sums are produced by the direct-to-LDS GEMM only");
   POPLAR_TRY(t.record_start());
   POPLAR_TRY(ctx->cfg.dtype == POPLAR_BF16 ? gemm_bf16_mfma(ctx->stream, a) : gemm_simple(ctx->stream, ctx->cfg.dtype, a));
   POPLAR_TRY(t.record_stop());
@@ -114,7 +115,7 @@ static GemmArgs gemm_args(int layout, int64_t M, int64_t N, int64_t K, const voi
   g.layout = layout; g.M = M; g.N = N; g.K = K;
   g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
   g.c_float = 0; g.beta = 0.f; g.bias = nullptr; g.residual = nullptr; g.act = ACT_NONE; g.aux = nullptr; g.ldaux = 0;
-  g.a_k_pad_zero = 0; g.ev_start = nullptr; g.ev_stop = nullptr;
+  g.a_k_pad_zero = 0; g.ev_start = nullptr; g.ev_stop = nullptr; g.a_rowsum = nullptr; g.a_rowsum_accumulate = 0;
   return g;
 }
 
@@ -253,25 +254,31 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
   float *scratch_n2 = (float*)(ws + bp.scratch), *scratch_n1 = scratch_n2 + norm_n, *scratch_cs = scratch_n1 + norm_n;
   const float beta = accumulate ? 1.f : 0.f;
   GemmArgs ga;
-  // Bias gradients (column sums of dy, dh, dx1, dqkv) are taken in one launch at the end, when all four
-  // matrices exist; their reductions and those of the two norms' gamma / beta gradients share one more.
+  // Bias gradients = column sums of dy, dh, dx1, dqkv, each the transposed operand of a weight-gradient GEMM:
+  // the direct-to-LDS GEMM forms them on the way (one more MFMA per fragment on its first column of tiles).
+  // Where that kernel does not take the problems, one column-sum launch at the end covers them, when all four
+  // matrices exist; its reductions and those of the two norms' gamma / beta gradients share one more launch.
   ColsumProblem cs[COLSUM_MAX_GROUP];
+  int cs_dw[COLSUM_MAX_GROUP];   // the weight-gradient GEMM each belongs to
   int ncs = 0;
   ReduceJob jobs[REDUCE_MAX_JOBS];
   int njobs = 0;
   const bool dy_is_dx = dy == dx;   // allowed by the interface: dy is then gone at the end, so what reads it cannot wait
 
   // MLP down projection: out = x1 + g W2^T + bm2
-  if (!llama) {
-    if (dy_is_dx) POPLAR_TRY(colsum(s, c.dtype, T, H, dy, H, G(lo.bm2), accumulate, scratch_cs, cs_n));
-    else cs[ncs++] = ColsumProblem{dy, H, H, G(lo.bm2)};
-  }
+  if (!llama && !dy_is_dx) { cs_dw[ncs] = 0; cs[ncs++] = ColsumProblem{dy, H, H, G(lo.bm2)}; }
   // the four weight-gradient GEMMs are collected and run as one group at the end: their operands (dy, dh,
   // dx1, dqkv and the stashed activations) all stay valid until then
   GemmArgs dw[4];
   dw[0] = gemm_args(GEMM_TN, H, F, T, dy, H, g, F, G(lo.w2), F);
   dw[0].c_float = 1; dw[0].beta = beta;
-  if (dy_is_dx) POPLAR_TRY(gemm(ctx, dw[0]));
+  if (dy_is_dx) {
+    if (!llama) {
+      if (c.dtype == POPLAR_BF16 && gemm_bf16_dtl_accepts(&dw[0], 1)) { dw[0].a_rowsum = G(lo.bm2); dw[0].a_rowsum_accumulate = accumulate; }
+      else POPLAR_TRY(colsum(s, c.dtype, T, H, dy, H, G(lo.bm2), accumulate, scratch_cs, cs_n));
+    }
+    POPLAR_TRY(gemm(ctx, dw[0]));
+  }
   if (llama) {
     void* dg = ws + bp.dg;
     ga = gemm_args(GEMM_NN, T, F, H, dy, H, P(lo.w2), F, dg, F);
@@ -281,7 +288,7 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
     ga = gemm_args(GEMM_NN, T, F, H, dy, H, P(lo.w2), F, dh, F);
     ga.act = ACT_GELU_BWD; ga.aux = const_cast<void*>(h); ga.ldaux = F;
     POPLAR_TRY(gemm(ctx, ga));
-    cs[ncs++] = ColsumProblem{dh, F, F, G(lo.bm1)};
+    cs_dw[ncs] = 1; cs[ncs++] = ColsumProblem{dh, F, F, G(lo.bm1)};
   }
   // MLP up projection
   dw[1] = gemm_args(GEMM_TN, hw, H, T, dh, hw, m, H, G(lo.w1), H);
@@ -290,7 +297,7 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
   // second norm; dx1 = dy + norm_bwd(dm)
   POPLAR_TRY(layernorm_bwd_partial(s, c.dtype, T, (int)H, dm, x1, P(lo.g2), stats2, dy, dx1, G(lo.g2), G(lo.b2), scratch_n2, norm_n, llama, &jobs[njobs++]));
   // attention output projection: x1 = x + o Wo^T + bo
-  if (!llama) cs[ncs++] = ColsumProblem{dx1, H, H, G(lo.bo)};
+  if (!llama) { cs_dw[ncs] = 2; cs[ncs++] = ColsumProblem{dx1, H, H, G(lo.bo)}; }
   dw[2] = gemm_args(GEMM_TN, H, H, T, dx1, H, o, H, G(lo.wo), H);
   ga = gemm_args(GEMM_NN, T, H, H, dx1, H, P(lo.wo), H, dob, H);
   POPLAR_TRY(gemm(ctx, ga));
@@ -298,19 +305,25 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
   POPLAR_TRY(attn_bwd(ctx, B, qkv, o, dob, lse, dqkv, delta));
   if (llama) POPLAR_TRY(rope_inplace(s, c.dtype, B, c.seq, c.n_head, (int)(H / c.n_head), dqkv, 3 * H, -1.0f));
   // QKV projection
-  if (!llama) cs[ncs++] = ColsumProblem{dqkv, 3 * H, 3 * H, G(lo.bqkv)};
+  if (!llama) { cs_dw[ncs] = 3; cs[ncs++] = ColsumProblem{dqkv, 3 * H, 3 * H, G(lo.bqkv)}; }
   dw[3] = gemm_args(GEMM_TN, 3 * H, H, T, dqkv, 3 * H, a, H, G(lo.wqkv), H);
   ga = gemm_args(GEMM_NN, T, H, 3 * H, dqkv, 3 * H, P(lo.wqkv), H, da, H);
   POPLAR_TRY(gemm(ctx, ga));
   // first norm; dx = dx1 + norm_bwd(da)
   POPLAR_TRY(layernorm_bwd_partial(s, c.dtype, T, (int)H, da, x_in, P(lo.g1), stats1, dx1, dx, G(lo.g1), G(lo.b1), scratch_n1, norm_n, llama, &jobs[njobs++]));
+  for (int i = 1; i < 4; ++i) { dw[i].c_float = 1; dw[i].beta = beta; }
+  GemmArgs* grp = dy_is_dx ? dw + 1 : dw;
+  const int ngrp = dy_is_dx ? 3 : 4;
+  if (ncs && c.dtype == POPLAR_BF16 && gemm_bf16_dtl_accepts(grp, ngrp)) {
+    for (int i = 0; i < ncs; ++i) { dw[cs_dw[i]].a_rowsum = cs[i].out; dw[cs_dw[i]].a_rowsum_accumulate = accumulate; }
+    ncs = 0;
+  }
   if (ncs) {
     POPLAR_TRY(colsum_partial(s, c.dtype, T, cs, ncs, scratch_cs, cs_n, jobs + njobs));
     njobs += ncs;
   }
   POPLAR_TRY(reduce_group(s, jobs, njobs, accumulate));
-  for (int i = 1; i < 4; ++i) { dw[i].c_float = 1; dw[i].beta = beta; }
-  return dy_is_dx ? gemm_group(ctx, dw + 1, 3) : gemm_group(ctx, dw, 4);
+  return gemm_group(ctx, grp, ngrp);
 }
 
 static int check_ctx_batch(poplar_ctx* ctx, int B) {
