@@ -500,35 +500,23 @@ bool gemm_bf16_dtl_accepts(const GemmArgs* a, int n) {
   return true;
 }
 
-// Up to DTL_MAX_GROUP problems of one layout and one K in a single launch (a plain GEMM is a group of one).
-// Returns POPLAR_ERR_UNIMPLEMENTED, with nothing launched, when a problem is outside the kernel's
-// preconditions or the group is not uniform; the caller then runs the problems one by one.
-int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n) {
-  if (n < 1 || n > DTL_MAX_GROUP) return POPLAR_ERR_UNIMPLEMENTED;
-  DtlGroupParams gp;
-  bool plain = true;
-  double mn = 0.0;
-  for (int i = 0; i < n; ++i) {
-    if (a[i].layout != a[0].layout || a[i].K != a[0].K) return POPLAR_ERR_UNIMPLEMENTED;
-    const int st = dtl_prepare(a[i], gp.g[i]);
-    if (st != POPLAR_OK) return st;
-    plain = plain && a[i].c_float && !a[i].bias && !a[i].residual && a[i].act == ACT_NONE;
-    mn += (double)a[i].M * (double)a[i].N;
-  }
-  gp.n = n;
+// Tile shape and K split by a small cost model, in units of one K step of a 256x256 tile on its CU.
+// 256x256 and 256x192 tiles run one block per CU, 128x128 tiles two per CU (each step a quarter of the
+// work at ~80% of the efficiency), 64x64 tiles four per CU (latency-bound steps: they only pay when the
+// larger tiles would leave most CUs idle, i.e. few rows and a narrow output); the epilogue costs a few
+// K steps; the launch takes ceil(blocks / slots) rounds.  The 256x192 tile exists for the block count: widths such as 768 or
+// 2304 give whole rounds with it where 256-wide tiles leave a quarter of the CUs idle.  A split adds a
+// zero fill and float atomics, which the chip retires at a fixed rate (about 250 G/s measured)
+// whatever the tile shape: that term is what keeps the split count low.
+struct TileCfg { int bm, bn; double slots, step, epi, epi_atomic; };
+static const TileCfg cfgs[4] = {{256, 256, 256.0, 1.0, 4.0, 6.0}, {256, 192, 256.0, 0.84, 3.0, 5.0}, {128, 128, 512.0, 0.6, 1.2, 2.0},
+                                {64, 64, 1024.0, 0.36, 0.5, 0.8}};
 
-  // Tile shape and K split by a small cost model, in units of one K step of a 256x256 tile on its CU.
-  // 256x256 and 256x192 tiles run one block per CU, 128x128 tiles two per CU (each step a quarter of the
-  // work at ~80% of the efficiency), 64x64 tiles four per CU (latency-bound steps: they only pay when the
-  // larger tiles would leave most CUs idle, i.e. few rows and a narrow output); the epilogue costs a few
-  // K steps; the launch takes ceil(blocks / slots) rounds.  The 256x192 tile exists for the block count: widths such as 768 or
-  // 2304 give whole rounds with it where 256-wide tiles leave a quarter of the CUs idle.  A split adds a
-  // zero fill and float atomics, which the chip retires at a fixed rate (about 250 G/s measured)
-  // whatever the tile shape: that term is what keeps the split count low.
-  struct TileCfg { int bm, bn; double slots, step, epi, epi_atomic; };
-  static const TileCfg cfgs[4] = {{256, 256, 256.0, 1.0, 4.0, 6.0}, {256, 192, 256.0, 0.84, 3.0, 5.0}, {128, 128, 512.0, 0.6, 1.2, 2.0},
-                                  {64, 64, 1024.0, 0.36, 0.5, 0.8}};
-  const int64_t K = a[0].K, ksteps = cdiv(K, DTL_BK);
+// plain: every problem writes a float matrix with no bias / activation / residual, so K may be split
+static double dtl_plan(const GemmArgs* a, int n, bool plain, int* pick_out, int* splits_out) {
+  const int64_t ksteps = cdiv(a[0].K, DTL_BK);
+  double mn = 0.0;
+  for (int i = 0; i < n; ++i) mn += (double)a[i].M * (double)a[i].N;
   int pick = 0, splits = 1;
   double best = 1e300;
   for (int cfg = 0; cfg < 4; ++cfg) {
@@ -545,6 +533,55 @@ int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n) {
       const double cost = rounds * ((double)cdiv(ksteps, sp) * step + (sp > 1 ? tc.epi_atomic : tc.epi)) +
                           (sp > 1 ? 3.0 * n + 2.7e-6 * (double)sp * mn : 0.0);   // one zero fill per problem, atomics
       if (cost < best) { best = cost; pick = cfg; splits = sp; }
+    }
+  }
+  *pick_out = pick; *splits_out = splits;
+  return best;
+}
+
+static int dtl_group_impl(hipStream_t s, const GemmArgs* a, int n, bool may_cut);
+
+// Up to DTL_MAX_GROUP problems of one layout and one K in a single launch (a plain GEMM is a group of one).
+// Returns POPLAR_ERR_UNIMPLEMENTED, with nothing launched, when a problem is outside the kernel's
+// preconditions or the group is not uniform; the caller then runs the problems one by one.
+int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n) { return dtl_group_impl(s, a, n, true); }
+
+static int dtl_group_impl(hipStream_t s, const GemmArgs* a, int n, bool may_cut) {
+  if (n < 1 || n > DTL_MAX_GROUP) return POPLAR_ERR_UNIMPLEMENTED;
+  DtlGroupParams gp;
+  bool plain = true;
+  for (int i = 0; i < n; ++i) {
+    if (a[i].layout != a[0].layout || a[i].K != a[0].K) return POPLAR_ERR_UNIMPLEMENTED;
+    const int st = dtl_prepare(a[i], gp.g[i]);
+    if (st != POPLAR_OK) return st;
+    plain = plain && a[i].c_float && !a[i].bias && !a[i].residual && a[i].act == ACT_NONE;
+  }
+  gp.n = n;
+  const int64_t K = a[0].K;
+  int pick = 0, splits = 1;
+  const double best = dtl_plan(a, n, plain, &pick, &splits);
+
+  // A lone weight gradient on 256x256 tiles whose last round would be mostly empty (the head: 591 tiles on 256 CUs)
+  // is cut along M: the tile rows that fill whole rounds run as they are, the rest as a problem of its own, for
+  // which the model finds a K split that spreads it over the chip.
+  if (may_cut && n == 1 && plain && a[0].layout == GEMM_TN && pick == 0 && splits == 1) {
+    const int64_t tm = cdiv(a[0].M, 256), tn = cdiv(a[0].N, 256), tiles = tm * tn;
+    const int64_t head_rows = tiles / 256 * 256 / tn;
+    if (tiles > 256 && tiles % 256 != 0 && head_rows >= 1 && head_rows < tm) {
+      GemmArgs h = a[0], t = a[0];
+      h.M = head_rows * 256;
+      t.M = a[0].M - h.M;
+      t.A = (const bf16*)a[0].A + h.M;                     // TN: A is stored [K, M]
+      t.C = (float*)a[0].C + h.M * a[0].ldc;
+      if (a[0].a_rowsum) t.a_rowsum = a[0].a_rowsum + h.M;
+      h.ev_stop = nullptr; t.ev_start = nullptr;
+      int pk, sp;
+      const double cut = dtl_plan(&h, 1, true, &pk, &sp) + dtl_plan(&t, 1, true, &pk, &sp);
+      DtlGemmParams probe;
+      if (cut < 0.95 * best && dtl_prepare(t, probe) == POPLAR_OK) {
+        POPLAR_TRY(dtl_group_impl(s, &h, 1, false));
+        return dtl_group_impl(s, &t, 1, false);
+      }
     }
   }
   const int BM = cfgs[pick].bm, BN = cfgs[pick].bn;
