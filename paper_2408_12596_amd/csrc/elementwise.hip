@@ -968,7 +968,8 @@ __global__ void __launch_bounds__(1024) xent_row_kernel(T* __restrict__ logits, 
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int i = threadIdx.x + j * 1024;
-      if (i < nvec) dst[j].load(row + (int64_t)i * VN);
+      // streamed once in each direction: non-temporal accesses
+      if (i < nvec) dst[j].raw = __builtin_bit_cast(decltype(dst[j].raw), __builtin_nontemporal_load(reinterpret_cast<const nt_f4*>(row + (int64_t)i * VN)));
     }
   };
   int64_t t = blockIdx.x;
@@ -1053,7 +1054,8 @@ __global__ void __launch_bounds__(1024) xent_row_kernel(T* __restrict__ logits, 
 #pragma unroll
           for (int k = 0; k < VN; ++k) if (k == tgt % VN) f[k] -= scale;
         }
-        Vec<T> o; o.pack(f); o.store(row + (int64_t)i * VN);
+        Vec<T> o; o.pack(f);
+        __builtin_nontemporal_store(__builtin_bit_cast(nt_f4, o.raw), reinterpret_cast<nt_f4*>(row + (int64_t)i * VN));
       }
     }
 #pragma unroll
@@ -1061,14 +1063,25 @@ __global__ void __launch_bounds__(1024) xent_row_kernel(T* __restrict__ logits, 
   }
 }
 
-__global__ void __launch_bounds__(256) loss_sum_kernel(const float* __restrict__ row_loss, int64_t n, float scale, float* __restrict__ loss) {
-  float acc = 0.f;
-  for (int64_t i = threadIdx.x; i < n; i += 256) acc += row_loss[i];
-  __shared__ float sw[4];
+__global__ void __launch_bounds__(1024) loss_sum_kernel(const float* __restrict__ row_loss, int64_t n, float scale, float* __restrict__ loss) {
+  // one block: four independent partial sums per thread keep four loads in flight
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  int64_t i = threadIdx.x;
+  for (; i + 3 * 1024 < n; i += 4 * 1024) {
+    a0 += row_loss[i]; a1 += row_loss[i + 1024]; a2 += row_loss[i + 2 * 1024]; a3 += row_loss[i + 3 * 1024];
+  }
+  for (; i < n; i += 1024) a0 += row_loss[i];
+  float acc = (a0 + a1) + (a2 + a3);
+  __shared__ float sw[16];
   acc = wave_sum(acc);
   if ((threadIdx.x & 63) == 0) sw[threadIdx.x >> 6] = acc;
   __syncthreads();
-  if (threadIdx.x == 0) *loss = (sw[0] + sw[1] + sw[2] + sw[3]) * scale;
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) t += sw[w];
+    *loss = t * scale;
+  }
 }
 
 int xent_fwd_bwd(hipStream_t s, int dtype, int64_t T_, int V, int64_t ld, void* logits, const int32_t* targets, int64_t tgt_ld, int S,
@@ -1093,7 +1106,7 @@ int xent_fwd_bwd(hipStream_t s, int dtype, int64_t T_, int V, int64_t ld, void* 
     DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(xent_kernel<T>, dim3((unsigned)T_), dim3(256), 0, s, (T*)logits, ld, V, targets, tgt_ld, S, loss_scale, row_loss));
   }
   POPLAR_LAUNCH_CHECK();
-  hipLaunchKernelGGL(loss_sum_kernel, dim3(1), dim3(256), 0, s, row_loss, T_, loss_scale, loss);
+  hipLaunchKernelGGL(loss_sum_kernel, dim3(1), dim3(1024), 0, s, row_loss, T_, loss_scale, loss);
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }
