@@ -6,7 +6,7 @@ on one MI355X, through libpoplar's C ABI.
 
 A step is poplar_profile_step(stage 1, B): embedding, 12 layers forward, head
 and loss, backward, Adam on the rank's 1/8 shard, all on synthetic inputs that
-already sit in HBM.  Prints ONE JSON line ("Measurement").
+already sit in HBM.  Prints ONE JSON line.
 """
 import argparse
 import json
