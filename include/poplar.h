@@ -173,7 +173,8 @@ int poplar_head_workspace_bytes(const poplar_model_cfg* cfg, int32_t B, int64_t*
  * Analyzing of Configuration").  targets: device int32 [B*S], each in [0, V), or
  * negative for a position that is not predicted (a masked-language-model
  * batch scores only its masked positions): such a position adds nothing to
- * the loss and its gradient is zero. */
+ * the loss and its gradient is zero.  A value of V or more is treated the
+ * same way (no memory outside the row is read). */
 int poplar_head_loss_fwd_bwd(poplar_ctx* ctx, int32_t B, const void* x, const int32_t* targets,
                              const void* gf, const void* bf, const void* whead, float loss_scale,
                              float* loss, void* dx, float* d_gf, float* d_bf, float* d_whead,

@@ -899,7 +899,8 @@ __global__ void __launch_bounds__(256) xent_kernel(T* __restrict__ logits, int64
   const int64_t t = blockIdx.x;
   T* row = logits + t * ld;
   const int nvec = (int)(ld / VN);
-  const int tgt = targets[(t / S) * tgt_ld + (t % S)];
+  int tgt = targets[(t / S) * tgt_ld + (t % S)];
+  if (tgt >= V) tgt = -1;   // a class that does not exist is treated like a position without a prediction, never read
   if (tgt < 0) {   // a position that is not predicted: no loss, zero gradient
     Vec<T> z;
     float f[VN];
@@ -976,7 +977,8 @@ __global__ void __launch_bounds__(1024) xent_row_kernel(T* __restrict__ logits, 
   if (t < rows) fetch(cur, t);
   for (int par = 0; t < rows; t += gridDim.x, par ^= 1) {
     T* row = logits + t * ld;
-    const int tgt = targets[(t / S) * tgt_ld + (t % S)];
+    int tgt = targets[(t / S) * tgt_ld + (t % S)];
+    if (tgt >= V) tgt = -1;   // a class that does not exist is treated like a position without a prediction, never read
     // this thread's share of max and sum; exponentials in the base-2 domain (one fma + v_exp_f32 each); only a
     // row's last vectors can hold padding columns, the others skip the column test
     constexpr float L2E = 1.4426950408889634f;

@@ -223,7 +223,12 @@ def test_head_loss_scores_only_positions_with_a_target(dtype):
     d_wh = torch.full((V, H), float("nan"), device=DEV)
     wsb = pb.head_workspace_bytes(cfg, B)
     ws = scratch(wsb)
-    ctx.head_loss_fwd_bwd(B, to_dev(x, dtype), to_dev(tgt.reshape(-1)), to_dev(gf, dtype), to_dev(bf, dtype), to_dev(wh, dtype), scale,
+    # a class index of V or more counts as "no prediction" too (the kernel never reads outside the row)
+    sent = tgt.reshape(-1).copy()
+    unscored = np.flatnonzero(sent < 0)
+    sent[unscored[::3]] = V
+    sent[unscored[1::3]] = V + 100000
+    ctx.head_loss_fwd_bwd(B, to_dev(x, dtype), to_dev(sent), to_dev(gf, dtype), to_dev(bf, dtype), to_dev(wh, dtype), scale,
                           loss, d_dx, d_gf, d_bf, d_wh, 0, ws, wsb)
     sync()
     xq, gq, bq, wq = quantize(x, dtype), quantize(gf, dtype), quantize(bf, dtype), quantize(wh, dtype)
