@@ -150,8 +150,9 @@ int poplar_gemm(poplar_ctx* ctx, int32_t layout, int64_t M, int64_t N, int64_t K
 /* ---- embedding, head and loss --------------------------------------------- */
 
 /* x[b,s,:] = wte[tok[b,s],:] (+ wpe[s,:] for GPT).  tokens: device int32 [B,S]
- * with ids in [0,V) (not checked on the device; out-of-range ids are the
- * caller's error).  wpe may be NULL for Llama. */
+ * with ids in [0,V); an id outside that range embeds as a zero row and
+ * receives no gradient (the table is never indexed with it).  wpe may be
+ * NULL for Llama. */
 int poplar_embed_fwd(poplar_ctx* ctx, int32_t B, const int32_t* tokens, const void* wte, const void* wpe, void* x);
 
 /* dwte[tok[b,s],:] += dx[b,s,:] (float atomics; summation order not fixed),

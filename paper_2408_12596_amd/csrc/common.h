@@ -128,8 +128,8 @@ int colsum(hipStream_t s, int dtype, int64_t T, int64_t N, const void* x, int64_
 int swiglu_fwd(hipStream_t s, int dtype, int64_t T, int F, const void* hgu, void* g);
 int swiglu_bwd(hipStream_t s, int dtype, int64_t T, int F, const void* dg, const void* hgu, void* dhgu);
 int rope_inplace(hipStream_t s, int dtype, int B, int S, int nh, int d, void* qkv, int64_t ld, float sign);
-int embed_fwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok, int64_t tok_ld, const void* wte, const void* wpe, void* x);
-int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok, int64_t tok_ld, const void* dx, float* dwte, float* dwpe, int accumulate);
+int embed_fwd(hipStream_t s, int dtype, int B, int S, int H, int V, const int32_t* tok, int64_t tok_ld, const void* wte, const void* wpe, void* x);
+int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, int V, const int32_t* tok, int64_t tok_ld, const void* dx, float* dwte, float* dwpe, int accumulate);
 int xent_fwd_bwd(hipStream_t s, int dtype, int64_t T, int V, int64_t ld, void* logits, const int32_t* targets, int64_t tgt_ld, int S,
                  float loss_scale, float* loss, float* row_loss);
 int adam_shard(hipStream_t s, int lowp_dtype, float* p, float* m, float* v, const float* g, void* p_lowp, int64_t n,

@@ -805,7 +805,7 @@ int rope_inplace(hipStream_t s, int dtype, int B, int S, int nh, int d, void* qk
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ void embed_fwd_kernel(const int32_t* __restrict__ tok, int64_t tok_ld, const T* __restrict__ wte, const T* __restrict__ wpe,
-                                 T* __restrict__ x, int64_t tokens, int S, int H) {
+                                 T* __restrict__ x, int64_t tokens, int S, int H, int V) {
   constexpr int VN = Vec<T>::N;
   const int per_row = H / VN;
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -816,7 +816,11 @@ __global__ void embed_fwd_kernel(const int32_t* __restrict__ tok, int64_t tok_ld
     int64_t b = t / S, sp = t % S;
     int id = tok[b * tok_ld + sp];
     float a[VN], p[VN];
-    Vec<T> v; v.load(wte + (int64_t)id * H + c); v.unpack(a);
+    Vec<T> v;
+#pragma unroll
+    for (int k = 0; k < VN; ++k) a[k] = 0.f;
+    // an id outside [0, V) embeds as zero (and receives no gradient): nothing outside the table is touched
+    if (id >= 0 && id < V) { v.load(wte + (int64_t)id * H + c); v.unpack(a); }
     if (wpe) {
       v.load(wpe + sp * H + c); v.unpack(p);
 #pragma unroll
@@ -825,11 +829,11 @@ __global__ void embed_fwd_kernel(const int32_t* __restrict__ tok, int64_t tok_ld
     v.pack(a); v.store(x + t * H + c);
   }
 }
-int embed_fwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok, int64_t tok_ld, const void* wte, const void* wpe, void* x) {
+int embed_fwd(hipStream_t s, int dtype, int B, int S, int H, int V, const int32_t* tok, int64_t tok_ld, const void* wte, const void* wpe, void* x) {
   int64_t tokens = (int64_t)B * S;
   if (tokens == 0) return POPLAR_OK;
   DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(embed_fwd_kernel<T>, dim3(grid_for(tokens * H / Vec<T>::N, 256)), dim3(256), 0, s, tok, tok_ld,
-                                           (const T*)wte, (const T*)wpe, (T*)x, tokens, S, H));
+                                           (const T*)wte, (const T*)wpe, (T*)x, tokens, S, H, V));
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }
@@ -839,14 +843,14 @@ int embed_fwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok,
 // atomic a memory transaction of its own (measured 4x slower).
 template <typename T>
 __global__ void embed_bwd_wte_kernel(const int32_t* __restrict__ tok, int64_t tok_ld, const T* __restrict__ dx, float* __restrict__ dwte,
-                                     int64_t tokens, int S, int H) {
+                                     int64_t tokens, int S, int H, int V) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < tokens * H; i += stride) {
     const int64_t t = i / H;
     const int c = (int)(i - t * H);
     const int id = tok[(t / S) * tok_ld + (t % S)];
-    unsafeAtomicAdd(dwte + (int64_t)id * H + c, to_float<T>(dx[i]));
+    if (id >= 0 && id < V) unsafeAtomicAdd(dwte + (int64_t)id * H + c, to_float<T>(dx[i]));
   }
 }
 template <typename T>
@@ -870,11 +874,11 @@ __global__ void embed_bwd_wpe_kernel(const T* __restrict__ dx, float* __restrict
 #pragma unroll
   for (int k = 0; k < VN; ++k) o[k] = accumulate ? o[k] + acc[k] : acc[k];
 }
-int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, const int32_t* tok, int64_t tok_ld, const void* dx, float* dwte, float* dwpe, int accumulate) {
+int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, int V, const int32_t* tok, int64_t tok_ld, const void* dx, float* dwte, float* dwpe, int accumulate) {
   int64_t tokens = (int64_t)B * S;
   if (tokens == 0) return POPLAR_OK;
   DISPATCH_DTYPE(dtype, {
-    hipLaunchKernelGGL(embed_bwd_wte_kernel<T>, dim3(grid_for(tokens * H, 256)), dim3(256), 0, s, tok, tok_ld, (const T*)dx, dwte, tokens, S, H);
+    hipLaunchKernelGGL(embed_bwd_wte_kernel<T>, dim3(grid_for(tokens * H, 256)), dim3(256), 0, s, tok, tok_ld, (const T*)dx, dwte, tokens, S, H, V);
     POPLAR_LAUNCH_CHECK();
     if (dwpe) {
       hipLaunchKernelGGL(embed_bwd_wpe_kernel<T>, dim3((unsigned)cdiv((int64_t)S * H / Vec<T>::N, 256)), dim3(256), 0, s, (const T*)dx, dwpe, B, S, H, accumulate);

@@ -370,7 +370,7 @@ extern "C" int poplar_embed_fwd(poplar_ctx* ctx, int32_t B, const int32_t* token
   const poplar_model_cfg& c = ctx->cfg;
   if (!tokens || !wte || !x) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
   if (c.arch == POPLAR_ARCH_GPT && !wpe) return poplar_fail(POPLAR_ERR_INVALID, "GPT needs wpe");
-  return embed_fwd(ctx->stream, c.dtype, B, c.seq, c.hidden, tokens, c.seq, wte, c.arch == POPLAR_ARCH_GPT ? wpe : nullptr, x);
+  return embed_fwd(ctx->stream, c.dtype, B, c.seq, c.hidden, c.vocab, tokens, c.seq, wte, c.arch == POPLAR_ARCH_GPT ? wpe : nullptr, x);
 }
 
 extern "C" int poplar_embed_bwd(poplar_ctx* ctx, int32_t B, const int32_t* tokens, const void* dx, float* dwte, float* dwpe, int32_t accumulate) {
@@ -378,7 +378,7 @@ extern "C" int poplar_embed_bwd(poplar_ctx* ctx, int32_t B, const int32_t* token
   const poplar_model_cfg& c = ctx->cfg;
   if (!tokens || !dx || !dwte) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
   if (c.arch == POPLAR_ARCH_GPT && !dwpe) return poplar_fail(POPLAR_ERR_INVALID, "GPT needs dwpe");
-  return embed_bwd(ctx->stream, c.dtype, B, c.seq, c.hidden, tokens, c.seq, dx, dwte, c.arch == POPLAR_ARCH_GPT ? dwpe : nullptr, accumulate);
+  return embed_bwd(ctx->stream, c.dtype, B, c.seq, c.hidden, c.vocab, tokens, c.seq, dx, dwte, c.arch == POPLAR_ARCH_GPT ? dwpe : nullptr, accumulate);
 }
 
 // ---- head + loss -----------------------------------------------------------

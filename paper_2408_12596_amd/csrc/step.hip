@@ -255,7 +255,7 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   // ---------------- forward ----------------
   const void* p_emb;
   POPLAR_TRY(params_at(0, u.emb_hi, gbuf, sp_gf, &p_emb));
-  POPLAR_TRY(embed_fwd(s, c.dtype, B, c.seq, (int)H, tokens, tok_ld, p_emb, llama ? nullptr : (const char*)p_emb + mo.wpe * es, X(0)));
+  POPLAR_TRY(embed_fwd(s, c.dtype, B, c.seq, (int)H, c.vocab, tokens, tok_ld, p_emb, llama ? nullptr : (const char*)p_emb + mo.wpe * es, X(0)));
   for (int l = 0; l < c.n_layer; ++l) {
     const void* p_l;
     const int64_t lo = u.layer0 + (int64_t)l * u.lc;
@@ -313,7 +313,7 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
       // stage 0/1 GPT: the head already wrote dwte, the embedding adds to it; everywhere else start from zero
       // (an accumulating pass at stage 0/1 adds to the earlier micro-steps' gradient instead)
       if (stage >= 2 || (llama && !acc)) POPLAR_TRY(fill_zero(s, ge, (int64_t)c.vocab * H * 4));
-      POPLAR_TRY(embed_bwd(s, c.dtype, B, c.seq, (int)H, tokens, tok_ld, dx_cur, ge, llama ? nullptr : ge + mo.wpe, stage < 2 ? acc : 0));
+      POPLAR_TRY(embed_bwd(s, c.dtype, B, c.seq, (int)H, c.vocab, tokens, tok_ld, dx_cur, ge, llama ? nullptr : ge + mo.wpe, stage < 2 ? acc : 0));
       POPLAR_TRY(reduce_unit(ge, 0, u.emb_hi));
     }
     POPLAR_TRY(ev.mark(&e_bwd_end));

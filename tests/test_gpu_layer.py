@@ -122,6 +122,27 @@ def test_embedding_fwd_bwd(arch, dtype):
     if arch == "gpt":
         assert rel_l2(to_np(dwpe), r_dwpe) <= 1e-6
 
+    # ids outside [0, V) embed as zero rows and receive no gradient
+    bad = tok.copy()
+    bad[0, 0], bad[1, 5] = V, -3
+    d_bad = to_dev(bad)
+    ctx.embed_fwd(B, d_bad, to_dev(wte, dtype), to_dev(wpe, dtype) if arch == "gpt" else None, d_x)
+    dwte2 = torch.zeros((V, H), device=DEV)
+    ctx.embed_bwd(B, d_bad, to_dev(dx, dtype), dwte2, dwpe, 0)
+    sync()
+    ok = tok.copy()
+    ref_ok = otr.embed_fwd(arch, quantize(wte, dtype), quantize(wpe, dtype), ok)
+    got_x = to_np(d_x)
+    pos = quantize(wpe, dtype) if arch == "gpt" else np.zeros((S, H))
+    for (b, s_) in ((0, 0), (1, 5)):
+        np.testing.assert_allclose(got_x[b, s_], pos[s_], atol=1e-6)
+        ref_ok[b, s_] = got_x[b, s_]
+    assert rel_l2(got_x, ref_ok) <= (4e-3 if dtype == "bf16" else 1e-7)
+    r2 = r_dwte.copy()
+    for (b, s_) in ((0, 0), (1, 5)):
+        r2[tok[b, s_]] -= quantize(dx, dtype)[b, s_]
+    assert rel_l2(to_np(dwte2), r2) <= 1e-6
+
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("arch,V", [("gpt", 211), ("llama", 256), ("gpt", 1031), ("llama", 20011), ("gpt", 50257), ("llama", 70001)])
