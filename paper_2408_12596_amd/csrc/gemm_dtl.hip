@@ -528,8 +528,10 @@ static double dtl_plan(const GemmArgs* a, int n, bool plain, int* pick_out, int*
       if (sp > 1 && (!plain || ksteps / sp < 8)) break;
       const double rounds = ceil((double)(t * sp) / tc.slots);
       // two 128x128 blocks that really share a CU slow each other down a little more
-      // (measured; likewise the 64x64 blocks as a CU fills up)
-      const double step = cfg == 2 ? (t * sp > 256 ? 0.68 : tc.step) : cfg == 3 ? (t * sp > 768 ? 0.45 : t * sp > 256 ? 0.40 : tc.step) : tc.step;
+      // (measured; likewise the 64x64 blocks as a CU fills up: four to a CU they cost almost twice the lone block's
+      // step, more again with two strided operands)
+      const double step3 = t * sp > 768 ? (a[0].layout == GEMM_TN ? 0.75 : 0.62) : t * sp > 256 ? 0.50 : tc.step;
+      const double step = cfg == 2 ? (t * sp > 256 ? 0.68 : tc.step) : cfg == 3 ? step3 : tc.step;
       const double cost = rounds * ((double)cdiv(ksteps, sp) * step + (sp > 1 ? tc.epi_atomic : tc.epi)) +
                           (sp > 1 ? 3.0 * n + 2.7e-6 * (double)sp * mn : 0.0);   // one zero fill per problem, atomics
       if (cost < best) { best = cost; pick = cfg; splits = sp; }
