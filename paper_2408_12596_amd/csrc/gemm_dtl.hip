@@ -530,7 +530,7 @@ static double dtl_plan(const GemmArgs* a, int n, bool plain, int* pick_out, int*
       // two 128x128 blocks that really share a CU slow each other down a little more
       // (measured; likewise the 64x64 blocks as a CU fills up: four to a CU they cost almost twice the lone block's
       // step, more again with two strided operands)
-      const double step3 = t * sp > 768 ? (a[0].layout == GEMM_TN ? 0.75 : 0.62) : t * sp > 256 ? 0.50 : tc.step;
+      const double step3 = t * sp > 768 ? (a[0].layout == GEMM_TN ? 0.75 : 0.66) : t * sp > 256 ? 0.50 : tc.step;
       const double step = cfg == 2 ? (t * sp > 256 ? 0.68 : tc.step) : cfg == 3 ? step3 : tc.step;
       const double cost = rounds * ((double)cdiv(ksteps, sp) * step + (sp > 1 ? tc.epi_atomic : tc.epi)) +
                           (sp > 1 ? 3.0 * n + 2.7e-6 * (double)sp * mn : 0.0);   // one zero fill per problem, atomics
