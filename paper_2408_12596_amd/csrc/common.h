@@ -77,7 +77,7 @@ struct GemmArgs {
   float beta;             // C = acc + beta * C_old  (float C only; 0 or 1)
   const void* bias;       // lowp [N] or null, added per column
   const void* residual;   // lowp [M,N] (ldc) or null, added after activation
-  int act;                // ACT_GELU: aux <- pre-activation, C <- gelu;  ACT_GELU_BWD: C <- acc * gelu'(aux)
+  int act;                // ACT_GELU: with h = acc + bias, aux <- gelu'(h), C <- gelu(h);  ACT_GELU_BWD: C <- acc * aux
   void* aux; int64_t ldaux;
   float* a_rowsum;        // TN only, or null: a_rowsum[m] (+)= sum_k A(k, m), the bias gradient next to a weight gradient;
   int a_rowsum_accumulate;  //   honoured by the direct-to-LDS kernel only (ask gemm_bf16_dtl_accepts first)

@@ -102,6 +102,15 @@ __device__ inline float gelu_sigmoid_fast(float h, float h2) {
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z));
 }
 __device__ inline float gelu_tanh_fast(float h) { return h * gelu_sigmoid_fast(h, h * h); }
+// value and derivative together: the sigmoid is shared, the derivative costs five more operations
+__device__ inline void gelu_tanh_both_fast(float h, float* g, float* dg) {
+  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
+  const float h2 = h * h;
+  const float s = gelu_sigmoid_fast(h, h2);
+  const float du2 = __builtin_fmaf(h2, 6.0f * k0 * k1, 2.0f * k0);   // 2 u'
+  *g = h * s;
+  *dg = __builtin_fmaf(h * du2 * s, 1.0f - s, s);
+}
 __device__ inline float gelu_tanh_grad_fast(float h) {
   const float k0 = 0.7978845608028654f, k1 = 0.044715f;
   const float h2 = h * h;

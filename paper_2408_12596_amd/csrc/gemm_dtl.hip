@@ -206,7 +206,7 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
     for (int l = 0; l < NL; ++l) load_one(st, l);
   };
 
-  // Second operand of the epilogue (the stashed pre-activation for GeLU', or the residual; the launcher admits
+  // Second operand of the epilogue (the stashed gelu' factor for the backward of GeLU, or the residual; the launcher admits
   // one of the two), 16 bytes per lane for each 16-row group of the wave tile.  The first TMC tile rows are
   // fetched here, before the K loop, the rest at the start of the epilogue behind the first chunk's work: the
   // epilogue then never waits on memory for them.
@@ -413,13 +413,15 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
               for (int k = 0; k < 8; ++k) v[k] += f[k];
             }
             if (p.act == ACT_GELU) {
-              t.pack(v); t.store(p.aux + m * p.ldaux + n);
+              // the backward pass needs the pre-activation only for gelu': that is what is stashed, formed here from the
+              // fp32 value next to the activation itself (they share the sigmoid)
 #pragma unroll
-              for (int k = 0; k < 8; ++k) v[k] = gelu_tanh_fast(v[k]);
+              for (int k = 0; k < 8; ++k) gelu_tanh_both_fast(v[k], &v[k], &f[k]);
+              t.pack(f); t.store(p.aux + m * p.ldaux + n);
             } else if (p.act == ACT_GELU_BWD) {
               t.raw = pre[c][ii][half][it]; t.unpack(f);
 #pragma unroll
-              for (int k = 0; k < 8; ++k) v[k] *= gelu_tanh_grad_fast(f[k]);
+              for (int k = 0; k < 8; ++k) v[k] *= f[k];
             }
             if (p.residual) {   // never together with GeLU' (the launcher refuses that pair): pre holds the residual
               t.raw = pre[c][ii][half][it]; t.unpack(f);

@@ -266,13 +266,15 @@ __global__ void __launch_bounds__(256, (TM * TN > 4 && LAYOUT == GEMM_TN ? 1 : 2
             for (int k = 0; k < 8; ++k) v[k] += f[k];
           }
           if (p.act == ACT_GELU) {
-            t.pack(v); t.store(p.aux + m * p.ldaux + n);
+            // the backward pass needs the pre-activation only for gelu': that is what is stashed, formed here from the
+            // fp32 value next to the activation itself (they share the sigmoid)
 #pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = gelu_tanh_fast(v[k]);
+            for (int k = 0; k < 8; ++k) gelu_tanh_both_fast(v[k], &v[k], &f[k]);
+            t.pack(f); t.store(p.aux + m * p.ldaux + n);
           } else if (p.act == ACT_GELU_BWD) {
             t.load(p.aux + m * p.ldaux + n); t.unpack(f);
 #pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] *= gelu_tanh_grad_fast(f[k]);
+            for (int k = 0; k < 8; ++k) v[k] *= f[k];
           }
           if (p.residual) {
             t.load(p.residual + m * p.ldc + n); t.unpack(f);

@@ -53,8 +53,8 @@ __global__ void __launch_bounds__(256) gemm_simple_kernel(const T* __restrict__ 
       if (n >= p.N) continue;
       float v = acc[i][j];
       if (bias) v += to_float<T>(bias[n]);
-      if (p.act == ACT_GELU) { aux[m * p.ldaux + n] = from_float<T>(v); v = gelu_tanh(v); }
-      else if (p.act == ACT_GELU_BWD) v *= gelu_tanh_grad(to_float<T>(aux[m * p.ldaux + n]));
+      if (p.act == ACT_GELU) { aux[m * p.ldaux + n] = from_float<T>(gelu_tanh_grad(v)); v = gelu_tanh(v); }
+      else if (p.act == ACT_GELU_BWD) v *= to_float<T>(aux[m * p.ldaux + n]);
       if (residual) v += to_float<T>(residual[m * p.ldc + n]);
       if (p.c_float) {
         float* C = reinterpret_cast<float*>(Cv);
