@@ -125,8 +125,11 @@ template <int R> struct ImageA<GEMM_TN, R> { typedef StridedImage<R> type; };
 template <int LAYOUT, int R> struct ImageB { typedef StridedImage<R> type; };
 template <int R> struct ImageB<GEMM_NT, R> { typedef DirectImage<R> type; };
 
-template <int LAYOUT, int WM, int WN, int TM, int TN, bool ATOMIC>
+// EPI selects the epilogue: 0 float staging (any output and fused operand), 1 float atomics (split K), 2 transposed
+// bf16 staging (bf16 output, nothing fused that is indexed by row)
+template <int LAYOUT, int WM, int WN, int TM, int TN, int EPI>
 __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParams gp) {
+  constexpr bool ATOMIC = EPI == 1, TRANSPOSED = EPI == 2;
   constexpr int NW = WM * WN;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   typedef typename ImageA<LAYOUT, BM>::type ImA;
@@ -234,7 +237,7 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
           if (m < p.M && n < n_ext) pre[c][i][half][it] = *reinterpret_cast<const uint4*>(extra + m * ldx + n);
         }
   };
-  if (!ATOMIC) prefetch(0);
+  if (!ATOMIC && !TRANSPOSED) prefetch(0);
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -367,7 +370,117 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
     }
     return;
   }
-  // Epilogue through a per-wave float staging area (see gemm_mfma.hip).  The bias depends on the column only
+  // bf16 outputs whose epilogue is elementwise in the accumulator's own layout (bias, GeLU; no second operand
+  // indexed by row): bias and activation are applied in registers in fp32, the results are rounded once, written
+  // to LDS as the transpose (a lane holds four consecutive rows of one column: one 8-byte write), and read back
+  // with transposing reads that hand each lane eight consecutive columns of one row for a 16-byte store.  A
+  // quarter of the LDS instructions and half the LDS bytes of the float staging below, which costs 3.7 us per
+  // 256x256 tile (measured), more than the stores themselves.
+  if (TRANSPOSED) {
+    constexpr int IC = TM >= 2 ? 2 : 1;                 // 32-row tiles per round
+    constexpr int P = IC * 64 + 16;                     // bytes per image row (one column of C, IC*32 rows), padded
+    constexpr int IMG = TN * 32 * P;
+    static_assert((NW / 2) * IMG <= STAGE, "transposed staging must fit the stages");
+    static_assert(TM % IC == 0, "whole rounds");
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float floatx2_t __attribute__((ext_vector_type(2)));
+    char* img = (wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * IMG;
+    // a wave's epilogue is bound by its instruction count (two waves share a SIMD and nothing else runs): every
+    // address below is a per-lane base plus a compile-time offset, and what is uniform is decided outside the loops
+    char* wbase = img + lr * P + lk * 8;                                   // + (j*32)*P + (ii*32 + g4*8)*2
+    const int j16 = lane & 15, grp = lane >> 4;
+    const uint32_t rbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)(img + (grp * 8 + (j16 >> 2)) * P + (4 * (j16 & 3)) * 2);
+    float bcol[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int64_t n = n0 + wn + j * 32 + lr;
+      bcol[j] = (p.bias && n < p.N) ? to_float<bf16>(p.bias[n]) : 0.f;
+    }
+    const bool gelu = p.act == ACT_GELU;                // GeLU has two outputs: the activation, then gelu' for the backward pass
+    const bool has_bias = p.bias != nullptr;
+    bool ncol_ok[TN];
+#pragma unroll
+    for (int nb = 0; nb < TN; ++nb) ncol_ok[nb] = n0 + wn + nb * 32 + grp * 8 < n_ext;
+    auto put = [&](int ii, int j, int g4, float v0, float v1, float v2, float v3) __attribute__((always_inline)) {
+      const bf16x2_t h0 = __builtin_convertvector(floatx2_t{v0, v1}, bf16x2_t);
+      const bf16x2_t h1 = __builtin_convertvector(floatx2_t{v2, v3}, bf16x2_t);
+      // column j*32 + lr of the wave tile, rows ii*32 + g4*8 + lk*4 .. +3
+      *reinterpret_cast<uint2*>(wbase + (j * 32) * P + (ii * 32 + g4 * 8) * 2) =
+          make_uint2(__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1));
+    };
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      if (pass == 1 && !gelu) break;
+      bf16* outp = pass == 0 ? reinterpret_cast<bf16*>(p.C) : p.aux;
+      const int64_t ldo = pass == 0 ? p.ldc : p.ldaux;
+#pragma unroll
+      for (int r = 0; r < TM / IC; ++r) {
+        if (gelu) {
+#pragma unroll
+          for (int ii = 0; ii < IC; ++ii)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+              for (int g4 = 0; g4 < 4; ++g4) {
+                float v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                  float gv, dg;
+                  gelu_tanh_both_fast(acc[r * IC + ii][j][g4 * 4 + k] + bcol[j], &gv, &dg);
+                  v[k] = pass == 0 ? gv : dg;
+                }
+                put(ii, j, g4, v[0], v[1], v[2], v[3]);
+              }
+        } else if (has_bias) {
+#pragma unroll
+          for (int ii = 0; ii < IC; ++ii)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+              for (int g4 = 0; g4 < 4; ++g4) {
+                const floatx16& t = acc[r * IC + ii][j];
+                put(ii, j, g4, t[g4 * 4] + bcol[j], t[g4 * 4 + 1] + bcol[j], t[g4 * 4 + 2] + bcol[j], t[g4 * 4 + 3] + bcol[j]);
+              }
+        } else {
+#pragma unroll
+          for (int ii = 0; ii < IC; ++ii)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+              for (int g4 = 0; g4 < 4; ++g4) {
+                const floatx16& t = acc[r * IC + ii][j];
+                put(ii, j, g4, t[g4 * 4], t[g4 * 4 + 1], t[g4 * 4 + 2], t[g4 * 4 + 3]);
+              }
+        }
+        wave_lds_sync();
+        // 16 lanes: lane j16 addresses image row (j16 >> 2) of a 4 x 16 block at element 4 (j16 & 3) and receives element
+        // j16 of the four rows, i.e. C[row mb*16 + j16][four consecutive columns]; two reads give eight columns.
+        // All reads of a 16-row block are issued before the one wait.
+        const int64_t mrow = m0 + wm + (r * IC * 32) + j16;
+        bf16* orow = outp + mrow * ldo + (n0 + wn + grp * 8);
+#pragma unroll
+        for (int mb = 0; mb < IC * 2; ++mb) {
+          intx2 lo[TN], hi[TN];
+#pragma unroll
+          for (int nb = 0; nb < TN; ++nb) {
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo[nb]) : "v"(rbase), "n"(nb * 32 * P + mb * 32));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi[nb]) : "v"(rbase), "n"(nb * 32 * P + mb * 32 + 4 * P));
+          }
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+          for (int nb = 0; nb < TN; ++nb) asm volatile("" : "+v"(lo[nb]), "+v"(hi[nb]));   // landed: only now may the values be used
+          if (mrow + mb * 16 < p.M) {
+#pragma unroll
+            for (int nb = 0; nb < TN; ++nb)
+              if (ncol_ok[nb]) *reinterpret_cast<uint4*>(orow + (int64_t)(mb * 16) * ldo + nb * 32) = make_uint4(lo[nb][0], lo[nb][1], hi[nb][0], hi[nb][1]);
+          }
+        }
+        wave_lds_sync();
+      }
+    }
+    return;
+  }
+  // Everything else goes through a per-wave float staging area (see gemm_mfma.hip).  The bias depends on the column only
   // and is read once.
   float* stage = reinterpret_cast<float*>(stage0) + wave * (16 * SW);
   uint4 bias_raw[ITS];
@@ -449,14 +562,14 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
   }
 }
 
-template <int WM, int WN, int TM, int TN, bool ATOMIC>
+template <int WM, int WN, int TM, int TN, int EPI>
 static void launch_dtl(hipStream_t s, int layout, dim3 grid, const DtlGroupParams& gp, hipEvent_t e0, hipEvent_t e1) {
   dim3 block(64 * WM * WN);
   // with events the launch itself carries them: they receive the kernel's own start and end
   switch (layout) {
-    case GEMM_NT: hipExtLaunchKernelGGL((gemm_dtl_kernel<GEMM_NT, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, e0, e1, 0, gp); break;
-    case GEMM_NN: hipExtLaunchKernelGGL((gemm_dtl_kernel<GEMM_NN, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, e0, e1, 0, gp); break;
-    default: hipExtLaunchKernelGGL((gemm_dtl_kernel<GEMM_TN, WM, WN, TM, TN, ATOMIC>), grid, block, 0, s, e0, e1, 0, gp); break;
+    case GEMM_NT: hipExtLaunchKernelGGL((gemm_dtl_kernel<GEMM_NT, WM, WN, TM, TN, EPI>), grid, block, 0, s, e0, e1, 0, gp); break;
+    case GEMM_NN: hipExtLaunchKernelGGL((gemm_dtl_kernel<GEMM_NN, WM, WN, TM, TN, EPI>), grid, block, 0, s, e0, e1, 0, gp); break;
+    default: hipExtLaunchKernelGGL((gemm_dtl_kernel<GEMM_TN, WM, WN, TM, TN, EPI>), grid, block, 0, s, e0, e1, 0, gp); break;
   }
 }
 
@@ -617,19 +730,21 @@ static int dtl_group_impl(hipStream_t s, const GemmArgs* a, int n, bool may_cut)
     }
   }
   dim3 grid((unsigned)tiles, (unsigned)splits);
-  if (pick == 0) {
-    if (atomic) launch_dtl<2, 4, 4, 2, true>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
-    else launch_dtl<2, 4, 4, 2, false>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
-  } else if (pick == 1) {
-    if (atomic) launch_dtl<4, 2, 2, 3, true>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
-    else launch_dtl<4, 2, 2, 3, false>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
-  } else if (pick == 2) {
-    if (atomic) launch_dtl<2, 2, 2, 2, true>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
-    else launch_dtl<2, 2, 2, 2, false>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
-  } else {
-    if (atomic) launch_dtl<2, 2, 1, 1, true>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
-    else launch_dtl<2, 2, 1, 1, false>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);
-  }
+  // which epilogue: split K -> atomics; bf16 outputs with nothing fused that is indexed by row -> transposed staging
+  bool transposed = !atomic;
+  for (int i = 0; i < n; ++i) transposed = transposed && !a[i].c_float && !a[i].residual && a[i].act != ACT_GELU_BWD;
+  const int epi = atomic ? 1 : transposed ? 2 : 0;
+#define DTL_LAUNCH(WM, WN, TM, TN)                                                                        \
+  do {                                                                                                    \
+    if (epi == 1) launch_dtl<WM, WN, TM, TN, 1>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);      \
+    else if (epi == 2) launch_dtl<WM, WN, TM, TN, 2>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop); \
+    else launch_dtl<WM, WN, TM, TN, 0>(s, a[0].layout, grid, gp, a[0].ev_start, a[0].ev_stop);               \
+  } while (0)
+  if (pick == 0) DTL_LAUNCH(2, 4, 4, 2);
+  else if (pick == 1) DTL_LAUNCH(4, 2, 2, 3);
+  else if (pick == 2) DTL_LAUNCH(2, 2, 2, 2);
+  else DTL_LAUNCH(2, 2, 1, 1);
+#undef DTL_LAUNCH
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }
