@@ -458,22 +458,34 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
         // All reads of a 16-row block are issued before the one wait.
         const int64_t mrow = m0 + wm + (r * IC * 32) + j16;
         bf16* orow = outp + mrow * ldo + (n0 + wn + grp * 8);
-#pragma unroll
-        for (int mb = 0; mb < IC * 2; ++mb) {
-          intx2 lo[TN], hi[TN];
+        constexpr int NMB = IC * 2;
+        intx2 lo[2][TN], hi[2][TN];
+        auto issue = [&](int mb, int buf) __attribute__((always_inline)) {
 #pragma unroll
           for (int nb = 0; nb < TN; ++nb) {
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo[nb]) : "v"(rbase), "n"(nb * 32 * P + mb * 32));
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi[nb]) : "v"(rbase), "n"(nb * 32 * P + mb * 32 + 4 * P));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo[buf][nb]) : "v"(rbase), "n"(nb * 32 * P + mb * 32));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi[buf][nb]) : "v"(rbase), "n"(nb * 32 * P + mb * 32 + 4 * P));
           }
-          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        };
+        issue(0, 0);
 #pragma unroll
-          for (int nb = 0; nb < TN; ++nb) asm volatile("" : "+v"(lo[nb]), "+v"(hi[nb]));   // landed: only now may the values be used
+        for (int mb = 0; mb < NMB; ++mb) {
+          // the reads of the next 16-row block are in flight while this one is stored
+          if (mb + 1 < NMB) {
+            issue(mb + 1, (mb + 1) & 1);
+            asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(2 * TN) : "memory");
+          } else {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          }
+#pragma unroll
+          for (int nb = 0; nb < TN; ++nb) asm volatile("" : "+v"(lo[mb & 1][nb]), "+v"(hi[mb & 1][nb]));   // landed: only now may the values be used
           if (mrow + mb * 16 < p.M) {
 #pragma unroll
             for (int nb = 0; nb < TN; ++nb)
-              if (ncol_ok[nb]) *reinterpret_cast<uint4*>(orow + (int64_t)(mb * 16) * ldo + nb * 32) = make_uint4(lo[nb][0], lo[nb][1], hi[nb][0], hi[nb][1]);
+              if (ncol_ok[nb])
+                *reinterpret_cast<uint4*>(orow + nb * 32) = make_uint4(lo[mb & 1][nb][0], lo[mb & 1][nb][1], hi[mb & 1][nb][0], hi[mb & 1][nb][1]);
           }
+          orow += 16 * ldo;
         }
         wave_lds_sync();
       }
