@@ -2,7 +2,7 @@
 on one MI355X, through libpoplar's C ABI.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B]
-                    [--curve-report] [--layer-report] [--model-report]
+                    [--curve-report] [--layer-report] [--model-report] [--clock-report]
 
 A step is poplar_profile_step(stage 1, B): embedding, 12 layers forward, head
 and loss, backward, Adam on the rank's 1/8 shard, all on synthetic inputs that
@@ -158,6 +158,54 @@ def layer_report(pb, torch, iters=5):
     return out
 
 
+def clock_report(pb, ctx, torch, shapes=((16384, 3072, 768), (8192, 2048, 8192)), iters=200):
+    """The same GEMM launches on operands of zeros, ones and normal values: the matrix pipes draw power with the
+    bits that toggle, the chip holds its power limit by lowering the shader clock, and so the rate a GEMM reaches
+    depends on its data.  Reports the rate per kind of data and the shader clock rocm-smi shows during a long run."""
+    import re
+    import subprocess
+    dev, rows = "cuda:0", []
+
+    def operands(kind, M, N, K):
+        if kind == "normal":
+            return (torch.randn(M, K, device=dev) * 0.5).to(torch.bfloat16), (torch.randn(N, K, device=dev) * 0.5).to(torch.bfloat16)
+        fill = torch.zeros if kind == "zeros" else torch.ones
+        return fill(M, K, device=dev, dtype=torch.bfloat16), fill(N, K, device=dev, dtype=torch.bfloat16)
+
+    def timed(A, B, C, M, N, K, n, sample):
+        for _ in range(3):
+            ctx.gemm(0, M, N, K, A, K, B, K, C, N, False, 0.0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            ctx.gemm(0, M, N, K, A, K, B, K, C, N, False, 0.0)
+        e1.record()
+        mhz = None
+        if sample:   # the launches are queued and still running: read the clock while they do
+            time.sleep(0.05)
+            try:
+                txt = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=30).stdout
+                m = re.search(r"sclk clock level.*?\((\d+)Mhz\)", txt)
+                mhz = int(m.group(1)) if m else None
+            except (OSError, subprocess.SubprocessError):
+                mhz = None
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / n, mhz
+
+    for (M, N, K) in shapes:
+        C = torch.empty(M, N, device=dev, dtype=torch.bfloat16)
+        for kind in ("zeros", "ones", "normal"):
+            A, B = operands(kind, M, N, K)
+            t, _ = timed(A, B, C, M, N, K, iters, False)
+            seconds_each = max(t, 1e-6)
+            _, mhz = timed(A, B, C, M, N, K, int(min(40000, max(iters, 2.0 / seconds_each))), True)
+            rows.append({"M": M, "N": N, "K": K, "data": kind, "us": t * 1e6, "tflops": 2.0 * M * N * K / t / 1e12,
+                         "frac_mfma_peak": 2.0 * M * N * K / t / 1e12 / PEAK_BF16_TFLOPS, "sclk_mhz_during_run": mhz})
+            del A, B
+    return rows
+
+
 MODEL_CONFIGS = {   # the larger configurations: (model, world, ZeRO stage, local batches)
     # (after the sweep 1, 2, 4, 8: the odd batches of the allocation stress, whose token counts leave partial tiles)
     "gpt-1.3B, ZeRO-2 on a 1/4 shard": (dict(arch="gpt", L=24, H=2048, nh=16, F=8192, S=2048, V=50257), 4, 2, (1, 2, 4, 8, 3, 5, 7, 13)),
@@ -253,6 +301,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--curve-report", action="store_true", help="add the dense-sweep / spline / Algorithm 2 report to the line")
     ap.add_argument("--layer-report", action="store_true", help="add one-layer timings at the larger configurations' shapes")
+    ap.add_argument("--clock-report", action="store_true", help="add GEMM rates on zero, one and normal operands with the shader "
+                    "clock during each run")
     ap.add_argument("--model-report", action="store_true", help="add whole-model steps of the 1.3B and Llama-7B-shaped configurations "
                     "and the allocation stress under an emulated 40 GiB cap (a few minutes, about 120 GB of HBM)")
     args = ap.parse_args()
@@ -348,6 +398,8 @@ def main():
         out["curve_report"] = curve_report(pb, ctx, P, max_b)
     if args.layer_report:
         out["layer_report"] = layer_report(pb, torch)
+    if args.clock_report:
+        out["clock_report"] = clock_report(pb, ctx, torch)
     if args.model_report:
         out["model_report"] = model_report(pb, torch)
     if not args.no_cpu_baseline:
