@@ -113,16 +113,30 @@ struct Rows64 {
   // Written as assembly: the compiler would make the builtin form wait for every global -> LDS load in
   // flight (it cannot tell the stage being filled from the one being read).  It does not see these reads
   // complete either: the caller waits with fa_wait_lds() before it uses the fragment.
-  __device__ static bf16x8 frag_tr(const char* lds, int2 base, int j) {
-    const uint32_t a0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)(lds + base.x + j * 16 * ROWB);
-    const uint32_t a1 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)(lds + base.y + j * 16 * ROWB);
+  // The chunk index (0 .. 3, a constant wherever this is called) goes into the instruction's offset field: a chunk
+  // is 16 rows further on, which leaves the swizzle of a row unchanged.
+  template <int J>
+  __device__ static bf16x8 frag_tr_at(uint32_t a0, uint32_t a1) {
     intx2 lo, hi;
-    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a0));
-    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(a1));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(a0), "n"(J * 16 * ROWB));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a1), "n"(J * 16 * ROWB));
     intx4 f = {lo[0], lo[1], hi[0], hi[1]};
     return __builtin_bit_cast(bf16x8, f);
   }
+  __device__ static bf16x8 frag_tr(const char* lds, int2 base, int j) {
+    const uint32_t a0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)(lds + base.x);
+    const uint32_t a1 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)(lds + base.y);
+    switch (j) {
+      case 0: return frag_tr_at<0>(a0, a1);
+      case 1: return frag_tr_at<1>(a0, a1);
+      case 2: return frag_tr_at<2>(a0, a1);
+      default: return frag_tr_at<3>(a0, a1);
+    }
+  }
 };
+
+// component c (a constant after unrolling) of a float4
+__device__ inline float f4_at(const float4& v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
 
 // all LDS reads issued so far have returned; nothing moves across
 __device__ inline void fa_wait_lds() {
@@ -555,22 +569,29 @@ __global__ void __launch_bounds__(256, D == 64 ? 2 : 1) flash_bwd_dkv_kernel(con
         sm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(q_lds, u * 32 + lr, s, g), kf[s], sm, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(do_lds, u * 32 + lr, s, g), vf[s], dp, 0, 0, 0);
       }
+      // statistics of this lane's 16 queries: four runs of four consecutive floats each, read whole before either
+      // path (a read inside the masked path's select would turn every element into a branch around an LDS access)
+      float4 l4[4], d4[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        l4[r] = *reinterpret_cast<const float4*>(lse_lds + u * 32 + r * 8 + g * 4);
+        d4[r] = *reinterpret_cast<const float4*>(delta_lds + u * 32 + r * 8 + g * 4);
+      }
       if ((causal && q0 < kvb + wave * 32 + 31) || q0 + 64 > S || kvb + 128 > S) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int ql = u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-          const int qq = q0 + ql;
+          const int qq = q0 + u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
           const bool ok = qq < S && kv < S && (!causal || kv <= qq);
-          const float p = ok ? fast_exp2(__builtin_fmaf(sm[i], c2, -lse_lds[ql])) : 0.f;
-          dp[i] = p * (dp[i] - delta_lds[ql]);   // dS
-          sm[i] = p;                              // P
+          const float e = fast_exp2(__builtin_fmaf(sm[i], c2, -f4_at(l4[i >> 2], i & 3)));
+          const float p = ok ? e : 0.f;
+          dp[i] = p * (dp[i] - f4_at(d4[i >> 2], i & 3));   // dS
+          sm[i] = p;                                          // P
         }
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int ql = u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-          const float p = fast_exp2(__builtin_fmaf(sm[i], c2, -lse_lds[ql]));
-          dp[i] = p * (dp[i] - delta_lds[ql]);
+          const float p = fast_exp2(__builtin_fmaf(sm[i], c2, -f4_at(l4[i >> 2], i & 3)));
+          dp[i] = p * (dp[i] - f4_at(d4[i >> 2], i & 3));
           sm[i] = p;
         }
       }
