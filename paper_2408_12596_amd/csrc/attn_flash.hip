@@ -327,41 +327,13 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const b
 }
 
 // =============================================================================
-// delta[b,h,i] = sum_c dout[i,c] * o[i,c]
-// =============================================================================
-__global__ void __launch_bounds__(256) flash_delta_kernel(const bf16* __restrict__ o, const bf16* __restrict__ dout, float* __restrict__ delta,
-                                                           int64_t rows, int S, int nh, int D) {
-  // one thread per 8 columns; D/8 consecutive threads share a (token, head) row
-  const int per = D / 8;
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t row = idx / per;  // over tokens * nh
-  float acc = 0.f;
-  if (row < rows) {
-    const int c = (int)(idx % per) * 8;
-    const int64_t t = row / nh;
-    const int h = (int)(row % nh);
-    const int64_t off = t * (int64_t)nh * D + h * D + c;
-    float a[8], d[8];
-    Vec<bf16> v; v.load(o + off); v.unpack(a);
-    v.load(dout + off); v.unpack(d);
-#pragma unroll
-    for (int k = 0; k < 8; ++k) acc += a[k] * d[k];
-  }
-  for (int ofs = per >> 1; ofs > 0; ofs >>= 1) acc += __shfl_xor(acc, ofs, 64);
-  if (row < rows && (idx % per) == 0) {
-    const int64_t t = row / nh;
-    const int h = (int)(row % nh);
-    delta[((t / S) * nh + h) * S + (t % S)] = acc;
-  }
-}
-
-// =============================================================================
 // backward, dQ: block = 128 queries, loop over key tiles (S^T form, lane = query)
 // =============================================================================
 template <int D>
-__global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
-                                                            const float* __restrict__ lse, const float* __restrict__ delta,
-                                                            bf16* __restrict__ dqkv, int B, int S, int nh, int causal, float scale) {
+__global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
+                                                            const bf16* __restrict__ dout, const float* __restrict__ lse,
+                                                            float* __restrict__ delta, bf16* __restrict__ dqkv, int B, int S, int nh,
+                                                            int causal, float scale) {
   typedef Rows64<D> Img;
   constexpr int NS = D == 64 ? 3 : 2;   // LDS stages: tiles t+1 .. t+NS-1 are in flight while tile t is used
   __shared__ __attribute__((aligned(1024))) char lds[NS * 2 * Img::BYTES];   // [stage][K | V]
@@ -397,7 +369,19 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(cons
   const float c2 = scale * LOG2E;
   const int64_t stat = ((int64_t)b * nh + h) * S + q;
   const float lse2 = q < S ? lse[stat] : 0.f;
-  const float dl = q < S ? delta[stat] : 0.f;
+  // delta = sum_c dO[q, c] O[q, c]: the lane holds half of dO's row already; O's row is read the same way, once.  The
+  // sums are stored for the dK/dV kernel, which runs after this one.
+  float dl = 0.f;
+  {
+    bf16x8 of[D / 16];
+    load_row_frags<D>(of, o + (int64_t)b * S * H + h * D, H, q, S, g);
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) dl = __builtin_fmaf((float)dof[s][k], (float)of[s][k], dl);
+    dl += __shfl_xor(dl, 32, 64);
+    if (g == 0 && q < S) delta[stat] = dl;
+  }
   floatx16 dq[D / 32];
   int2 trb[D / 32];
 #pragma unroll
@@ -653,18 +637,15 @@ int attn_bwd_flash(hipStream_t s, int B, int S, int nh, int d, int causal, const
   POPLAR_TRY(check_flash(B, S, nh, d, qkv));
   if (B == 0 || S == 0) return POPLAR_OK;
   const float scale = 1.0f / sqrtf((float)d);
-  const int64_t rows = (int64_t)B * S * nh;
-  // the first launch carries the start event, the last one the stop event
-  hipExtLaunchKernelGGL(flash_delta_kernel, dim3((unsigned)cdiv(rows * (d / 8), 256)), dim3(256), 0, s, ev_start, nullptr, 0, (const bf16*)o,
-                        (const bf16*)dout, delta, rows, S, nh, d);
-  POPLAR_LAUNCH_CHECK();
+  // dQ first: it also forms delta = rowsum(dO * O), which dK/dV reads.  The first launch carries the start event, the
+  // last one the stop event.
   dim3 grid((unsigned)((int64_t)B * nh * ((S + 127) / 128)));
   if (d == 64) {
-    hipLaunchKernelGGL(flash_bwd_dkv_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
-    hipExtLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, dim3(256), 0, s, nullptr, ev_stop, 0, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
+    hipExtLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, dim3(256), 0, s, ev_start, nullptr, 0, (const bf16*)qkv, (const bf16*)o, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
+    hipExtLaunchKernelGGL(flash_bwd_dkv_kernel<64>, grid, dim3(256), 0, s, nullptr, ev_stop, 0, (const bf16*)qkv, (const bf16*)dout, lse, (const float*)delta, (bf16*)dqkv, B, S, nh, causal, scale);
   } else {
-    hipLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
-    hipExtLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, dim3(256), 0, s, nullptr, ev_stop, 0, (const bf16*)qkv, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
+    hipExtLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, dim3(256), 0, s, ev_start, nullptr, 0, (const bf16*)qkv, (const bf16*)o, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S, nh, causal, scale);
+    hipExtLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, dim3(256), 0, s, nullptr, ev_stop, 0, (const bf16*)qkv, (const bf16*)dout, lse, (const float*)delta, (bf16*)dqkv, B, S, nh, causal, scale);
   }
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
