@@ -32,7 +32,9 @@ def rel_l2(a, b):
 
 
 def scratch(nbytes):
-    return torch.empty(int(nbytes) + 256, dtype=torch.uint8, device=DEV)
+    """Caller-owned scratch memory, poisoned: every byte 0xFF reads as NaN in fp32 and in bf16, so a kernel that
+    reads workspace or stash it has not written shows up in the results."""
+    return torch.full((int(nbytes) + 256,), 255, dtype=torch.uint8, device=DEV)
 
 
 def quantize(a, dtype):
