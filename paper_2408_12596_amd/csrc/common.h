@@ -81,6 +81,9 @@ struct GemmArgs {
   void* aux; int64_t ldaux;
   float* a_rowsum;        // TN only, or null: a_rowsum[m] (+)= sum_k A(k, m), the bias gradient next to a weight gradient;
   int a_rowsum_accumulate;  //   honoured by the direct-to-LDS kernel only (ask gemm_bf16_dtl_accepts first)
+  // TN with a float C and nothing fused (a weight gradient), or null: room for M * ldc + M floats.  With it the
+  // direct-to-LDS kernel may cut K in two: the second half's sums go here and are added to C (and to a_rowsum) afterwards.
+  float* k_partial = nullptr;
   int a_k_pad_zero;       // NN only: A's rows hold zeros from column K up to K rounded up to 64 (lda covers them)
   // Optional: events that receive the start and the end of the kernel itself (hipExtLaunchKernelGGL), without the
   // barrier packets a recorded event puts between kernels.  Honoured by the direct-to-LDS kernel only.
@@ -89,7 +92,7 @@ struct GemmArgs {
 int gemm_simple(hipStream_t s, int dtype, const GemmArgs& a);
 int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a);
 int gemm_bf16_dtl(hipStream_t s, const GemmArgs& a);   // POPLAR_ERR_UNIMPLEMENTED when the shape is outside its preconditions
-// up to four problems of one layout and one K in a single launch; POPLAR_ERR_UNIMPLEMENTED (nothing launched) when it cannot
+// up to four problems of one layout and one K in a single launch (two when their K is cut in two halves); POPLAR_ERR_UNIMPLEMENTED (nothing launched) when it cannot
 int gemm_bf16_dtl_group(hipStream_t s, const GemmArgs* a, int n);
 bool gemm_bf16_dtl_accepts(const GemmArgs* a, int n);   // preconditions only, nothing launched
 int gemm(hipStream_t s, int dtype, const GemmArgs& a);

@@ -171,6 +171,13 @@ BwdPlan bwd_plan(const poplar_model_cfg& c, int B) {
   p.da = take(T * H * es);
   p.delta = take((int64_t)B * c.n_head * c.seq * 4);
   p.scratch = take((2 * norm_scratch_floats(c) + colsum_scratch_floats(c)) * 4);
+  // bf16: room for the second half of each weight-gradient GEMM's sums (and of the bias gradient that rides on it)
+  // when its contraction over the tokens is cut in two; in the order of the GEMMs: W2, W1 (or Wg | Wu), Wo, Wqkv
+  const int64_t hw = llama ? 2 * F : F;
+  const int64_t rows[4] = {H, hw, H, 3 * H}, cols[4] = {F, H, H, H};
+  const int64_t before = at;
+  for (int i = 0; i < 4; ++i) p.kpart[i] = c.dtype == POPLAR_BF16 ? take((rows[i] * cols[i] + rows[i]) * 4) : -1;
+  p.kpart_bytes = at - before;
   p.bytes = at;
   return p;
 }
@@ -312,6 +319,7 @@ int layer_bwd_impl(poplar_ctx* ctx, int B, const void* x_in, const void* dy, con
   // first norm; dx = dx1 + norm_bwd(da)
   POPLAR_TRY(layernorm_bwd_partial(s, c.dtype, T, (int)H, da, x_in, P(lo.g1), stats1, dx1, dx, G(lo.g1), G(lo.b1), scratch_n1, norm_n, llama, &jobs[njobs++]));
   for (int i = 1; i < 4; ++i) { dw[i].c_float = 1; dw[i].beta = beta; }
+  for (int i = 0; i < 4; ++i) dw[i].k_partial = bp.kpart[i] < 0 ? nullptr : (float*)(ws + bp.kpart[i]);
   GemmArgs* grp = dy_is_dx ? dw + 1 : dw;
   const int ngrp = dy_is_dx ? 3 : 4;
   if (ncs && c.dtype == POPLAR_BF16 && gemm_bf16_dtl_accepts(grp, ngrp)) {

@@ -5,7 +5,7 @@
 #include <algorithm>
 
 struct SavedPlan { int64_t stats1, a, qkv, o, lse, x1, stats2, m, h, g, bytes; };
-struct BwdPlan { int64_t dh, dg, dm, dx1, dob, dqkv, da, delta, scratch, bytes; };
+struct BwdPlan { int64_t dh, dg, dm, dx1, dob, dqkv, da, delta, scratch, kpart[4], kpart_bytes, bytes; };   // kpart: -1 without (fp32 path); kpart_bytes: their share of bytes (no batch in it)
 struct HeadPlan { int64_t ldl, hf, stats, logits, row_loss, dhf, dhf32, scratch, bytes; bool dhf_split; };
 
 SavedPlan saved_plan(const poplar_model_cfg& c, int B);

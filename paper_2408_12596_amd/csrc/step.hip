@@ -68,7 +68,12 @@ static StepPlan step_plan(const poplar_model_cfg& c, int stage, int B) {
   p.xs = take((int64_t)(c.n_layer + 1) * round_up(T * H * es, 256));
   p.saved_each = saved_plan(c, B).bytes;
   p.saved = take(p.saved_each * (c.checkpoint ? 1 : c.n_layer));
-  p.shared = take(std::max(head_plan(c, B).bytes, bwd_plan(c, B).bytes));
+  {
+    // the head's and the layers' backward workspaces share one region; the layers' constant part (the K-split
+    // buffers) is counted on both sides of the max so that the size stays affine in the batch
+    const BwdPlan bw = bwd_plan(c, B);
+    p.shared = take(std::max(head_plan(c, B).bytes + bw.kpart_bytes, bw.bytes));
+  }
   p.dxa = take(T * H * es);
   p.dxb = take(T * H * es);
   p.staging = stage >= 2 ? take((u.max_unit + 2 * H) * 4) : -1;
@@ -97,7 +102,10 @@ static int64_t accounted_bytes(const poplar_model_cfg& c, int stage, int B, int 
   const HeadPlan hp = head_plan(c, B);
   int64_t act = (int64_t)(c.n_layer + 1) * round_up(T * H * es, 256) + saved_plan(c, B).bytes * (c.checkpoint ? 1 : c.n_layer) + (int64_t)B * (c.seq + 1) * 4;
   if (forward_only) act += hp.dhf;  // hf, stats, logits, row_loss (everything before dhf)
-  else act += std::max(hp.bytes, bwd_plan(c, B).bytes) + 2 * round_up(T * H * es, 256);
+  else {
+    const BwdPlan bw = bwd_plan(c, B);
+    act += std::max(hp.bytes + bw.kpart_bytes, bw.bytes) + 2 * round_up(T * H * es, 256);
+  }
   return state_bytes(c, stage) + act;
 }
 
