@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes that cross the L2 per GEMM launch at local batch 16, averaged over the 111 launches of a step: rocprofv3
 # counters FETCH_SIZE x 2.0 (calibrated on kernels of known size) + WRITE_SIZE, summarised under profiles/.
 # Valid for the GEMM kernel as profiled; set to None when that kernel changes until the counters are taken again.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 291.6e6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 296.2e6
 # Events ride on the GEMM launches of every GEMM_EVENTS_EVERY-th timed step (the first, the sixth, ...): an attached
 # pair of events costs about 4.5 us per launch, 0.5 ms on a step's 111 launches, and the headline number should
 # carry as little of the instrument as the measurement allows.
