@@ -677,7 +677,8 @@ static const TileCfg cfgs[4] = {{256, 256, 256.0, 1.0, 4.0, 6.0}, {256, 192, 256
 static double dtl_plan(const GemmArgs* a, int n, bool plain, int* pick_out, int* splits_out, bool* halves_out = nullptr) {
   const int64_t ksteps = cdiv(a[0].K, DTL_BK);
   bool can_halve = halves_out != nullptr && plain && a[0].layout == GEMM_TN && n <= DTL_MAX_PROBLEMS && ksteps >= 16;
-  for (int i = 0; i < n; ++i) can_halve = can_halve && a[i].k_partial != nullptr;
+  // (dense outputs only: the second pass runs over M * ldc floats of C and of the buffer alike)
+  for (int i = 0; i < n; ++i) can_halve = can_halve && a[i].k_partial != nullptr && ((uintptr_t)a[i].k_partial & 15) == 0 && a[i].ldc == a[i].N;
   bool halves = false;
   double mn = 0.0;
   for (int i = 0; i < n; ++i) mn += (double)a[i].M * (double)a[i].N;
