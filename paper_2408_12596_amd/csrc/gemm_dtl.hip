@@ -672,8 +672,9 @@ static const TileCfg cfgs[4] = {{256, 256, 256.0, 1.0, 4.0, 6.0}, {256, 192, 256
 
 // plain: every problem writes a float matrix with no bias / activation / residual, so K may be split
 // *halves_out (may be null): the plan is a cut of K in two whose second half goes to the problems' k_partial buffers
-// and is added afterwards: no zero fill and no atomics, one pass over the outputs instead (1.2e-6 units per element:
-// 14.6 us for the 7.1 M elements of a GPT-2-small layer's weight gradients).  Offered when every problem brings the buffer.
+// and is added afterwards: no zero fill and no atomics, one pass over the outputs instead (14.6 us for the 7.1 M
+// elements of a GPT-2-small layer's weight gradients; the coefficient is set so that the cut begins where it was
+// measured to pay on that layer: above 8192 tokens).  Offered when every problem brings the buffer.
 static double dtl_plan(const GemmArgs* a, int n, bool plain, int* pick_out, int* splits_out, bool* halves_out = nullptr) {
   const int64_t ksteps = cdiv(a[0].K, DTL_BK);
   bool can_halve = halves_out != nullptr && plain && a[0].layout == GEMM_TN && n <= DTL_MAX_PROBLEMS && ksteps >= 16;
@@ -704,7 +705,7 @@ static double dtl_plan(const GemmArgs* a, int n, bool plain, int* pick_out, int*
     if (can_halve && cfg < 3) {
       const double rounds = ceil((double)(2 * t) / tc.slots);
       const double step = cfg == 2 ? (2 * t > 256 ? 0.68 : tc.step) : tc.step;
-      const double cost = rounds * ((double)cdiv(ksteps, 2) * step + tc.epi) + 2.0 + 1.2e-6 * mn;
+      const double cost = rounds * ((double)cdiv(ksteps, 2) * step + tc.epi) + 2.0 + 2.6e-6 * mn;
       if (cost < best) { best = cost; pick = cfg; splits = 1; halves = true; }
     }
   }

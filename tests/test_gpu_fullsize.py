@@ -20,9 +20,9 @@ SHAPES = [
     dict(arch="llama", L=1, H=4096, nh=32, F=11008, S=2048, V=1, B=1),
     # three samples of the GPT-2-small shape: a token count that is not a multiple of the 256-row tile
     dict(arch="gpt", L=1, H=768, nh=12, F=3072, S=1024, V=1, B=3),
-    # eight samples: the contraction over 8192 tokens is long enough for the weight-gradient group to be cut in two
+    # nine samples: the contraction over 9216 tokens is long enough for the weight-gradient group to be cut in two
     # along it (second half summed into buffers of its own and added afterwards)
-    dict(arch="gpt", L=1, H=768, nh=12, F=3072, S=1024, V=1, B=8),
+    dict(arch="gpt", L=1, H=768, nh=12, F=3072, S=1024, V=1, B=9),
 ]
 
 
