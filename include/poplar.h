@@ -212,7 +212,13 @@ int poplar_zero3_gather_local(poplar_ctx* ctx, void* out, const void* own_shard,
 /* ---- whole step, profile and search ---------------------------------------- */
 
 /* Device buffers of one rank's training state, bound to a context for
- * poplar_profile_step / poplar_search_mbs.  All stay owned by the caller. */
+ * poplar_profile_step / poplar_search_mbs.  All stay owned by the caller.
+ * `len` below is the shard length of the stage that runs: ceil(P / world) at
+ * stages 1-3, but P at stage 0, where every rank keeps the whole optimizer
+ * (Appendix "Details about ZeRO": stage 0 duplicates all model states).  The
+ * three *_len fields say how many elements the caller really allocated; a
+ * step at a stage that needs more is refused with POPLAR_ERR_INVALID before
+ * anything is launched. */
 typedef struct poplar_state {
   void*    params;       /* lowp [P]: full compute copy (stages 0-2); at stage 3 it plays the peers' stand-in */
   void*    own_shard;    /* lowp [len]: stage 3 only, this rank's parameter shard (else NULL) */
@@ -220,9 +226,13 @@ typedef struct poplar_state {
   float*   m;            /* float [len] */
   float*   v;            /* float [len] */
   float*   grads;        /* stage 0/1: float [P]; stage 2/3: float [len] shard buffer */
+  int64_t  master_len;   /* elements in each of master, m, v (>= 1) */
+  int64_t  grads_len;    /* elements in grads (>= 1) */
+  int64_t  own_len;      /* elements in own_shard (0 when it is NULL) */
   const int32_t* tokens; /* int32 [max_batch, S+1]; inputs [:, :S], targets [:, 1:] */
   int32_t  max_batch;
-  void*    workspace;    /* activations, logits, staging: poplar_step_workspace_bytes */
+  void*    workspace;    /* activations, logits, staging: poplar_step_workspace_bytes (may be NULL, with 0 bytes, when
+                            memory hooks supply the workspace of every step) */
   int64_t  workspace_bytes;
   float*   loss;         /* device float scalar */
   int32_t  adam_t;       /* step counter passed to Adam */
@@ -238,6 +248,9 @@ int poplar_bind_state(poplar_ctx* ctx, const poplar_state* st);
  * staging), which is what the emulated cap is compared with.  Both are affine
  * in B (Section "Heterogeneity Aware": memory is linear in the batch size). */
 int poplar_step_workspace_bytes(const poplar_model_cfg* cfg, int32_t stage, int32_t B, int64_t* bytes);
+/* Workspace bytes of the forward pass alone: what Algorithm 1's memory probe at batch 1 allocates through the
+ * memory hooks (always below poplar_step_workspace_bytes of the same stage and batch). */
+int poplar_step_forward_bytes(const poplar_model_cfg* cfg, int32_t stage, int32_t B, int64_t* bytes);
 int poplar_step_accounted_bytes(const poplar_model_cfg* cfg, int32_t stage, int32_t B, int32_t forward_only, int64_t* bytes);
 
 typedef struct poplar_profile {
@@ -256,6 +269,7 @@ typedef struct poplar_profile {
   double t_gemm, gemm_flops;    /* summed launch durations (s) and algorithmic flop 2*M*N*K of the GEMM launches */
   double t_attn, attn_flops;    /* same for the attention kernels: 2 S^2 H fwd, 5 S^2 H bwd per sample (causal) */
   int32_t n_gemm, n_attn;       /* launches counted */
+  int64_t measured_bytes;       /* with memory hooks: what bytes_now() returned while the step's workspace was held; else 0 */
 } poplar_profile;
 
 /* What the current HIP device reports: compute units, the peak engine clock in
@@ -271,6 +285,39 @@ int poplar_device_info(int32_t* compute_units, int32_t* clock_khz, int64_t* memo
 /* on: 0 none, 1 the GEMM launches, 2 the attention launches, 3 both (each timed
  * launch costs a few microseconds of step time); anything else ERR_INVALID. */
 int poplar_set_kernel_timing(poplar_ctx* ctx, int32_t on);
+
+/* How many runs stand behind one profile sample of poplar_profile_step and of
+ * the searches: `warmup` untimed runs first, then `repeats` timed ones, of which
+ * the run with the median TimeConsumedDuringStep is reported (the lower middle
+ * one for an even count).  The default, 0 and 1, is the single run of Algorithm
+ * 1; Appendix "Relationship Between Compute Capability and Batch Size" notes
+ * that single runs fluctuate.  Every run is a real training step: the optimizer
+ * state and the parameters advance once per run (adam_t stays as bound).
+ * 0 <= warmup <= 64, 1 <= repeats <= 65. */
+int poplar_set_sampling(poplar_ctx* ctx, int32_t warmup, int32_t repeats);
+
+/* Memory by measurement instead of by accounting.  Algorithm 1 reads the
+ * allocator before and after a forward pass and reacts to an out-of-memory
+ * event; with these hooks the library does the same against the caller's
+ * allocator.  While hooks are set, every step (poplar_profile_step,
+ * poplar_accum_step, each step of the searches) asks `alloc` for its workspace
+ * of poplar_step_workspace_bytes(stage, batch) bytes, runs in it and hands it
+ * back through `release` after the stream has been synchronised; the bound
+ * workspace and cfg.cap_bytes are not consulted.  alloc returning NULL is the
+ * out-of-memory event: the call returns POPLAR_ERR_OOM with nothing launched
+ * and the training state untouched (the searches take it as "this batch does
+ * not fit").  poplar_search_mbs estimates the maximum from bytes_now() before
+ * the forward workspace of one sample is allocated and while it is held, and
+ * from bytes_total().  All four are called on the calling thread, between
+ * launches; `user` is passed back untouched.  hooks = NULL removes them. */
+typedef struct poplar_mem_hooks {
+  void*   user;
+  void*   (*alloc)(void* user, int64_t bytes);      /* device memory, 256-byte aligned, or NULL */
+  void    (*release)(void* user, void* ptr);
+  int64_t (*bytes_now)(void* user);                 /* bytes the allocator holds right now (CurrentMemoryAlloced) */
+  int64_t (*bytes_total)(void* user);               /* bytes it may hold at most (TotalMemory) */
+} poplar_mem_hooks;
+int poplar_set_mem_hooks(poplar_ctx* ctx, const poplar_mem_hooks* hooks);
 
 /* model.step(local_batch) of Algorithm 1 at a ZeRO stage, timed:
  * embedding, L layers, head and loss, backward, (stage 2/3) local gradient
@@ -304,7 +351,9 @@ int poplar_accum_step(poplar_ctx* ctx, int32_t stage, int32_t n_micro, const int
  * pass at batch 1, run steps at 1, 2, 4, ... and then bisect to the largest
  * batch that fits.  samples: host array of max_samples entries, filled in call
  * order with the successful steps; *n_samples their count; *mbs = 0 means
- * batch 1 does not fit at this stage. */
+ * batch 1 does not fit at this stage.  Each sample is a real step (see
+ * poplar_set_sampling): the bound optimizer state and parameters advance by
+ * one update per run, as they do when the paper's profiler calls model.step. */
 int poplar_search_mbs(poplar_ctx* ctx, int32_t stage, int32_t* mbs,
                       poplar_profile* samples, int32_t max_samples, int32_t* n_samples);
 
@@ -313,7 +362,9 @@ int poplar_search_mbs(poplar_ctx* ctx, int32_t stage, int32_t* mbs,
  * Runs poplar_search_mbs at first_stage, first_stage + 1, ... 3 and stops at the
  * first stage whose mbs is positive: *stage is that stage (-1 if none fits),
  * *mbs and the samples are that stage's.  The bound state must serve every
- * stage tried (gradient buffer of P floats, own_shard for stage 3). */
+ * stage tried (gradient buffer of P floats; master, m and v of P floats when
+ * first_stage is 0; own_shard for stage 3): a stage the state is too small for
+ * ends the search with POPLAR_ERR_INVALID before anything of it runs. */
 int poplar_search_stage(poplar_ctx* ctx, int32_t first_stage, int32_t* stage, int32_t* mbs,
                         poplar_profile* samples, int32_t max_samples, int32_t* n_samples);
 
@@ -352,8 +403,11 @@ typedef struct poplar_alloc {
   int32_t* b;      /* host [n_dev]: micro-batch */
   int32_t* gas;    /* host [n_dev]: accumulation steps (stage 2/3: same on every device) */
   int32_t* lbs;    /* host [n_dev]: batch of the last accumulation step */
-  double T;        /* predicted iteration time: Eq. (1) for stage 0/1, wall time for 2/3 */
+  double T;        /* predicted iteration time: Eq. (1) with t_i = gmbs_i / speed_i for stage 0/1, wall time for 2/3 */
   double t;        /* stage 2/3: chosen per-micro-step time; stage 0/1: time_optimal */
+  double T_steps;  /* stage 0/1: Eq. (1) with t_i read off device i's own curve for the steps it will run,
+                      (gas_i - 1) time_i(b_i) + time_i(lbs_i), time_i(b) = b / speed_i(b): never below T, and above
+                      it where lbs_i sits on the slow part of the curve.  Stage 2/3: equal to T */
 } poplar_alloc;
 
 /* Algorithm 2.  Stage 0/1: speed_i = max of the curve, time_optimal = gbs /

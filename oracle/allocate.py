@@ -24,11 +24,17 @@ Readings where the paper is silent or the listing is garbled:
     {b : speed_i(b) >= peak_frac * max}, peak_frac = 0.95 by default;
     gas_i = ceil(gmbs_i / b_i), lbs_i = gmbs_i - (gas_i - 1) b_i;
   * stage 2/3: candidate t are all distinct values of time_i(b); find(g_i, t)
-    is the largest b <= mbs_i with running-max time_i(b) <= t;
+    is the largest b <= mbs_i with time_i(b) <= t, where time_i is the running
+    maximum of b / speed_i(b) (a spline through noisy samples may dip; with the
+    running maximum "can finish b samples within t" is monotone in b);
     gas = ceil(gbs / sum_i b_i); wall = (t + time_communication) * gas; the
     first strict minimum wins; the last accumulation step carries
     gbs - (gas - 1) sum_i b_i samples, handed out one at a time to the device
-    whose time after taking it is smallest (never above b_i).
+    whose time after taking it is smallest (never above b_i);
+  * stage 0/1 reports two predictions: T, Eq. 1 with t_i = gmbs_i / speed_i
+    (what the split was made for), and T_steps, Eq. 1 with t_i summed over the
+    accumulation steps the device will really run on its own curve,
+    (gas_i - 1) time_i(b_i) + time_i(lbs_i) with time_i(b) = b / speed_i(b).
 """
 import math
 import numpy as np
@@ -61,6 +67,13 @@ def time_curve(speed):
     for b in range(1, len(speed)):
         t[b] = max(t[b - 1], b / speed[b])
     return t
+
+
+def find(tm, t):
+    """Largest batch whose step time does not exceed t (0 if none): the `find`
+    of Algorithm 2, written as its definition over the whole curve."""
+    fits = [b for b in range(1, len(tm)) if tm[b] <= t]
+    return max(fits) if fits else 0
 
 
 def iteration_time(t):
@@ -108,7 +121,8 @@ def allocate_stage01(gbs, curves, peak_frac=0.95):
         gi = -(-gmbs[i] // bi)
         b.append(bi), gas.append(gi), lbs.append(gmbs[i] - (gi - 1) * bi)
     T = max(gmbs[i] / speed[i] for i in range(n) if speed[i] > 0.0)
-    return dict(gmbs=gmbs, b=b, gas=gas, lbs=lbs, T=T)
+    T_steps = max((gas[i] - 1) * (b[i] / sp[i][b[i]]) + lbs[i] / sp[i][lbs[i]] for i in range(n) if gmbs[i] > 0)
+    return dict(gmbs=gmbs, b=b, gas=gas, lbs=lbs, T=T, T_steps=T_steps)
 
 
 def allocate_stage23(gbs, curves, time_communication):
@@ -118,12 +132,7 @@ def allocate_stage23(gbs, curves, time_communication):
     cand = sorted({float(tm[i][k]) for i in range(n) for k in range(1, len(tm[i]))})
     best = None
     for t in cand:
-        bs = []
-        for i in range(n):
-            k = 0
-            while k + 1 < len(tm[i]) and tm[i][k + 1] <= t:
-                k += 1
-            bs.append(k)
+        bs = [find(tm[i], t) for i in range(n)]
         mb = sum(bs)
         if mb == 0:
             continue

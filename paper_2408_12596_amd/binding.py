@@ -39,7 +39,8 @@ class ModelCfg(C.Structure):
 
 class State(C.Structure):
     _fields_ = [("params", C.c_void_p), ("own_shard", C.c_void_p), ("master", C.c_void_p), ("m", C.c_void_p),
-                ("v", C.c_void_p), ("grads", C.c_void_p), ("tokens", C.c_void_p), ("max_batch", C.c_int32),
+                ("v", C.c_void_p), ("grads", C.c_void_p), ("master_len", C.c_int64), ("grads_len", C.c_int64), ("own_len", C.c_int64),
+                ("tokens", C.c_void_p), ("max_batch", C.c_int32),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64), ("loss", C.c_void_p),
                 ("adam_t", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("targets", C.c_void_p)]
@@ -50,10 +51,20 @@ class Profile(C.Structure):
                 ("t_gather_fwd", C.c_double), ("t_gather_bwd", C.c_double), ("t_reduce_bwd", C.c_double),
                 ("t_adam", C.c_double), ("t_consumed", C.c_double), ("accounted_bytes", C.c_int64),
                 ("flops", C.c_double), ("loss", C.c_float), ("t_gemm", C.c_double), ("gemm_flops", C.c_double),
-                ("t_attn", C.c_double), ("attn_flops", C.c_double), ("n_gemm", C.c_int32), ("n_attn", C.c_int32)]
+                ("t_attn", C.c_double), ("attn_flops", C.c_double), ("n_gemm", C.c_int32), ("n_attn", C.c_int32),
+                ("measured_bytes", C.c_int64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_void_p, C.c_int64)
+RELEASE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+BYTES_FN = C.CFUNCTYPE(C.c_int64, C.c_void_p)
+
+
+class MemHooks(C.Structure):
+    _fields_ = [("user", C.c_void_p), ("alloc", ALLOC_FN), ("release", RELEASE_FN), ("bytes_now", BYTES_FN), ("bytes_total", BYTES_FN)]
 
 
 class Curve(C.Structure):
@@ -62,7 +73,7 @@ class Curve(C.Structure):
 
 class Alloc(C.Structure):
     _fields_ = [("gmbs", C.POINTER(C.c_int32)), ("b", C.POINTER(C.c_int32)), ("gas", C.POINTER(C.c_int32)),
-                ("lbs", C.POINTER(C.c_int32)), ("T", C.c_double), ("t", C.c_double)]
+                ("lbs", C.POINTER(C.c_int32)), ("T", C.c_double), ("t", C.c_double), ("T_steps", C.c_double)]
 
 
 EXPORTS = [
@@ -72,7 +83,7 @@ EXPORTS = [
     "poplar_head_loss_fwd_bwd", "poplar_adam_shard", "poplar_zero2_reduce_local", "poplar_zero3_gather_local",
     "poplar_bind_state", "poplar_step_workspace_bytes", "poplar_step_accounted_bytes", "poplar_profile_step",
     "poplar_accum_step", "poplar_search_mbs", "poplar_search_stage", "poplar_comm_model", "poplar_speed_curve", "poplar_allocate", "poplar_set_kernel_timing", "poplar_device_info",
-    "poplar_gemm",
+    "poplar_gemm", "poplar_set_sampling", "poplar_set_mem_hooks", "poplar_step_forward_bytes",
 ]
 
 _lib = None
@@ -114,11 +125,14 @@ def _declare(L):
         "poplar_bind_state": [vp, C.POINTER(State)],
         "poplar_step_workspace_bytes": [cfgp, i32, i32, p64],
         "poplar_step_accounted_bytes": [cfgp, i32, i32, i32, p64],
+        "poplar_step_forward_bytes": [cfgp, i32, i32, p64],
         "poplar_profile_step": [vp, i32, i32, C.POINTER(Profile)],
         "poplar_accum_step": [vp, i32, i32, C.POINTER(i32), i32, C.POINTER(Profile)],
         "poplar_search_mbs": [vp, i32, C.POINTER(i32), C.POINTER(Profile), i32, C.POINTER(i32)],
         "poplar_search_stage": [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(Profile), i32, C.POINTER(i32)],
         "poplar_set_kernel_timing": [vp, i32],
+        "poplar_set_sampling": [vp, i32, i32],
+        "poplar_set_mem_hooks": [vp, C.POINTER(MemHooks)],
         "poplar_device_info": [C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)],
         "poplar_gemm": [vp, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, f32],
         "poplar_comm_model": [i64, i32, i32, f64, f64, f64] + [C.POINTER(f64)] * 5,
@@ -229,6 +243,10 @@ def step_workspace_bytes(cfg, stage, B):
     return _bytes_query(lib().poplar_step_workspace_bytes, cfg, stage, B)
 
 
+def step_forward_bytes(cfg, stage, B):
+    return _bytes_query(lib().poplar_step_forward_bytes, cfg, stage, B)
+
+
 def step_accounted_bytes(cfg, stage, B, forward_only=False):
     return _bytes_query(lib().poplar_step_accounted_bytes, cfg, stage, B, int(forward_only))
 
@@ -257,7 +275,7 @@ def speed_curve(batches, times, mbs):
 
 
 def allocate(stage, gbs, curves, time_communication=0.0, peak_frac=0.95):
-    """curves: list of (batches, times, mbs).  Returns dict(gmbs, b, gas, lbs, T, t)."""
+    """curves: list of (batches, times, mbs).  Returns dict(gmbs, b, gas, lbs, T, t, T_steps)."""
     n = len(curves)
     keep = []
     arr = (Curve * n)()
@@ -267,9 +285,9 @@ def allocate(stage, gbs, curves, time_communication=0.0, peak_frac=0.95):
         keep += [b, t]
         arr[i] = Curve(len(bs), b, t, mbs)
     outs = [(C.c_int32 * n)() for _ in range(4)]
-    al = Alloc(*outs, 0.0, 0.0)
+    al = Alloc(*outs, 0.0, 0.0, 0.0)
     _check(lib().poplar_allocate(stage, n, arr, C.c_int64(gbs), C.c_double(time_communication), C.c_double(peak_frac), C.byref(al)))
-    return dict(gmbs=list(outs[0]), b=list(outs[1]), gas=list(outs[2]), lbs=list(outs[3]), T=al.T, t=al.t)
+    return dict(gmbs=list(outs[0]), b=list(outs[1]), gas=list(outs[2]), lbs=list(outs[3]), T=al.T, t=al.t, T_steps=al.T_steps)
 
 
 # ---- context ---------------------------------------------------------------------
@@ -328,11 +346,38 @@ class Context:
                                                C.c_int64(shard_off), C.c_int64(shard_len)))
 
     def bind_state(self, params, master, m, v, grads, tokens, max_batch, workspace, workspace_bytes, loss,
-                   own_shard=None, adam_t=1, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, targets=None):
-        st = State(_ptr(params), _ptr(own_shard), _ptr(master), _ptr(m), _ptr(v), _ptr(grads), _ptr(tokens), max_batch,
+                   own_shard=None, adam_t=1, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, targets=None,
+                   master_len=None, grads_len=None, own_len=None):
+        """master_len / grads_len / own_len: elements allocated; read off the tensors when not given (raw addresses need them)."""
+        def count(t, given):
+            if given is not None:
+                return given
+            if t is None:
+                return 0
+            if isinstance(t, int):
+                raise ValueError("a raw address needs its element count")
+            return t.numel()
+        mlen = min(count(master, master_len), count(m, master_len), count(v, master_len))
+        st = State(_ptr(params), _ptr(own_shard), _ptr(master), _ptr(m), _ptr(v), _ptr(grads), mlen, count(grads, grads_len),
+                   count(own_shard, own_len), _ptr(tokens), max_batch,
                    _ptr(workspace), workspace_bytes, _ptr(loss), adam_t, lr, beta1, beta2, eps, _ptr(targets))
         _check(lib().poplar_bind_state(self._h, C.byref(st)))
         self._state_refs = (params, master, m, v, grads, tokens, workspace, loss, own_shard, targets)  # keep the tensors alive
+
+    def set_sampling(self, warmup, repeats):
+        _check(lib().poplar_set_sampling(self._h, int(warmup), int(repeats)))
+
+    def set_mem_hooks(self, alloc=None, release=None, bytes_now=None, bytes_total=None):
+        """Python callables alloc(bytes) -> address or 0, release(address), bytes_now() -> int, bytes_total() -> int;
+        all None removes the hooks."""
+        if alloc is None:
+            _check(lib().poplar_set_mem_hooks(self._h, None))
+            self._hooks = None
+            return
+        hooks = MemHooks(None, ALLOC_FN(lambda user, n: alloc(n) or None), RELEASE_FN(lambda user, p: release(p)),
+                         BYTES_FN(lambda user: bytes_now()), BYTES_FN(lambda user: bytes_total()))
+        _check(lib().poplar_set_mem_hooks(self._h, C.byref(hooks)))
+        self._hooks = hooks   # the callbacks must outlive their use
 
     def set_kernel_timing(self, on):
         _check(lib().poplar_set_kernel_timing(self._h, int(on)))

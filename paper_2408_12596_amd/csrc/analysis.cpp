@@ -152,7 +152,7 @@ static int allocate_stage01(int n, const poplar_curve* curves, int64_t gbs, doub
     gmbs[best] += 1;
     remain -= 1;
   }
-  double T = 0.0;
+  double T = 0.0, T_steps = 0.0;
   for (int i = 0; i < n; ++i) {
     if (gmbs[i] > std::numeric_limits<int32_t>::max()) return poplar_fail(POPLAR_ERR_INVALID, "gmbs overflows int32");
     out->gmbs[i] = (int32_t)gmbs[i];
@@ -166,8 +166,11 @@ static int allocate_stage01(int n, const poplar_curve* curves, int64_t gbs, doub
     out->gas[i] = (int32_t)gi;
     out->lbs[i] = (int32_t)(gmbs[i] - (gi - 1) * bi);
     T = std::max(T, (double)gmbs[i] / speed[i]);
+    const int64_t li = gmbs[i] - (gi - 1) * bi;
+    T_steps = std::max(T_steps, (double)(gi - 1) * ((double)bi / sp[i][bi]) + (double)li / sp[i][li]);
   }
   out->T = T;
+  out->T_steps = T_steps;
   out->t = time_optimal;
   return POPLAR_OK;
 }
@@ -222,6 +225,7 @@ static int allocate_stage23(int n, const poplar_curve* curves, int64_t gbs, doub
     out->gmbs[i] = (int32_t)g;
   }
   out->T = best_wall;
+  out->T_steps = best_wall;
   out->t = best_t;
   return POPLAR_OK;
 }

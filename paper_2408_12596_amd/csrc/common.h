@@ -39,6 +39,9 @@ struct poplar_ctx {
   int kernel_timing;               // bit 0: time every GEMM launch with events, bit 1: every attention launch
   bool in_step;                    // a profiled step is being enqueued
   std::vector<TimedLaunch> launches;
+  int warmup, repeats;             // untimed and timed runs behind one profile sample
+  bool have_hooks;                 // step workspaces come from the caller's allocator
+  poplar_mem_hooks hooks;
 };
 // record the next pooled event on the context's stream
 int ctx_mark(poplar_ctx* ctx, hipEvent_t* e);
@@ -140,4 +143,5 @@ int adam_shard(hipStream_t s, int lowp_dtype, float* p, float* m, float* v, cons
 int zero2_reduce_local(hipStream_t s, float* gshard, const float* g_unit, int64_t unit_lo, int64_t unit_hi, int64_t shard_off, int64_t shard_len);
 int zero3_gather_local(hipStream_t s, int dtype, void* out, const void* own, const void* peers, int64_t lo, int64_t hi, int64_t shard_off, int64_t shard_len);
 int fill_zero(hipStream_t s, void* p, int64_t bytes);
+int fill_zero_2d(hipStream_t s, void* p, int64_t rows, int64_t cols, int64_t ld);   // rows x cols 32-bit words, row stride ld words
 int cast_f32_to_lowp(hipStream_t s, int dtype, const float* in, void* out, int64_t n);

@@ -4,6 +4,7 @@
 // softmax cross-entropy.  All use 16-byte accesses per lane and 64-lane
 // wavefront reductions; math is float whatever the storage type.
 #include "device_utils.h"
+#include <algorithm>
 
 #define DISPATCH_DTYPE(dtype, ...)                                         \
   do {                                                                      \
@@ -34,6 +35,21 @@ int fill_zero(hipStream_t s, void* p, int64_t bytes) {
   if (bytes % 4 || ((uintptr_t)p & 3)) return poplar_fail(POPLAR_ERR_INVALID, "fill_zero needs 4-byte granularity");
   int64_t n = bytes / 4;
   hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, (uint32_t*)p, n);
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+// rows x cols 32-bit words at row stride ld (words), in one launch: blockIdx.y walks the rows
+__global__ void fill_zero_2d_kernel(uint32_t* p, int64_t rows, int64_t cols, int64_t ld) {
+  for (int64_t r = blockIdx.y; r < rows; r += gridDim.y)
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cols; i += (int64_t)gridDim.x * blockDim.x) p[r * ld + i] = 0u;
+}
+int fill_zero_2d(hipStream_t s, void* p, int64_t rows, int64_t cols, int64_t ld) {
+  if (rows <= 0 || cols <= 0) return POPLAR_OK;
+  if ((uintptr_t)p & 3) return poplar_fail(POPLAR_ERR_INVALID, "fill_zero_2d needs 4-byte alignment");
+  if (ld < cols) return poplar_fail(POPLAR_ERR_INVALID, "fill_zero_2d: row stride below the row length");
+  const dim3 grid((unsigned)std::min<int64_t>(cdiv(cols, 256), 64), (unsigned)std::min<int64_t>(rows, 16384));
+  hipLaunchKernelGGL(fill_zero_2d_kernel, grid, dim3(256), 0, s, (uint32_t*)p, rows, cols, ld);
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }

@@ -824,7 +824,7 @@ static int dtl_group_impl(hipStream_t s, const GemmArgs* a, int n, bool may_cut,
     for (int i = 0; i < n; ++i) {
       if (a[i].beta != 0.f) continue;
       if (a[i].ldc != a[i].N) {
-        for (int64_t m = 0; m < a[i].M; ++m) POPLAR_TRY(fill_zero(s, (float*)a[i].C + m * a[i].ldc, a[i].N * 4));
+        POPLAR_TRY(fill_zero_2d(s, a[i].C, a[i].M, a[i].N, a[i].ldc));
       } else {
         POPLAR_TRY(fill_zero(s, a[i].C, a[i].M * a[i].N * 4));
       }

@@ -354,7 +354,7 @@ int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a) {
     p.atomic = 1;
     if (a.beta == 0.f) {
       if (a.ldc != a.N) {
-        for (int64_t m = 0; m < a.M; ++m) POPLAR_TRY(fill_zero(s, (float*)a.C + m * a.ldc, a.N * 4));
+        POPLAR_TRY(fill_zero_2d(s, a.C, a.M, a.N, a.ldc));
       } else {
         POPLAR_TRY(fill_zero(s, a.C, a.M * a.N * 4));
       }

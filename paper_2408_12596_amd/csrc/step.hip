@@ -16,6 +16,10 @@ extern "C" int poplar_create(const poplar_model_cfg* cfg, void* hip_stream, popl
   c->ev_next = 0;
   c->kernel_timing = 0;
   c->in_step = false;
+  c->warmup = 0;
+  c->repeats = 1;
+  c->have_hooks = false;
+  memset(&c->hooks, 0, sizeof c->hooks);
   *out = c;
   return POPLAR_OK;
 }
@@ -29,9 +33,12 @@ extern "C" int poplar_destroy(poplar_ctx* ctx) {
 
 extern "C" int poplar_bind_state(poplar_ctx* ctx, const poplar_state* st) {
   if (!ctx || !st) return poplar_fail(POPLAR_ERR_INVALID, "null argument");
-  if (!st->params || !st->master || !st->m || !st->v || !st->grads || !st->tokens || !st->workspace || !st->loss)
+  if (!st->params || !st->master || !st->m || !st->v || !st->grads || !st->tokens || !st->loss)
     return poplar_fail(POPLAR_ERR_INVALID, "state has a null device pointer");
+  if (!st->workspace && st->workspace_bytes != 0) return poplar_fail(POPLAR_ERR_INVALID, "null workspace with a size");
   if (st->max_batch < 1 || st->workspace_bytes < 0 || st->adam_t < 1) return poplar_fail(POPLAR_ERR_INVALID, "bad max_batch / workspace_bytes / adam_t");
+  if (st->master_len < 1 || st->grads_len < 1 || st->own_len < 0 || (st->own_shard != nullptr) != (st->own_len > 0))
+    return poplar_fail(POPLAR_ERR_INVALID, "state needs master_len >= 1, grads_len >= 1 and own_len > 0 exactly when own_shard is given");
   ctx->st = *st;
   ctx->bound = true;
   return POPLAR_OK;
@@ -59,7 +66,9 @@ static void stage_shard(const poplar_model_cfg& c, int stage, int64_t P, int64_t
 struct StepPlan {
   int64_t xs, saved, saved_each, shared, dxa, dxb, staging, gather, bytes;
 };
-static StepPlan step_plan(const poplar_model_cfg& c, int stage, int B) {
+// forward_only: what a forward pass alone touches (the probe of Algorithm 1's memory estimate): residual stream,
+// stashes, the head's forward half, the stage 3 gather buffer; the other offsets are -1.
+static StepPlan step_plan(const poplar_model_cfg& c, int stage, int B, bool forward_only = false) {
   const int64_t T = (int64_t)B * c.seq, H = c.hidden, es = elt_size(c.dtype);
   const Units u = units_of(c);
   StepPlan p;
@@ -68,6 +77,13 @@ static StepPlan step_plan(const poplar_model_cfg& c, int stage, int B) {
   p.xs = take((int64_t)(c.n_layer + 1) * round_up(T * H * es, 256));
   p.saved_each = saved_plan(c, B).bytes;
   p.saved = take(p.saved_each * (c.checkpoint ? 1 : c.n_layer));
+  if (forward_only) {
+    p.shared = take(head_plan(c, B).dhf);   // normed input, statistics, logits, per-row loss
+    p.dxa = p.dxb = p.staging = -1;
+    p.gather = stage >= 3 ? take((u.max_unit + u.tail_count) * es) : -1;
+    p.bytes = at;
+    return p;
+  }
   {
     // the head's and the layers' backward workspaces share one region; the layers' constant part (the K-split
     // buffers) is counted on both sides of the max so that the size stays affine in the batch
@@ -116,6 +132,13 @@ extern "C" int poplar_step_workspace_bytes(const poplar_model_cfg* cfg, int32_t 
   return POPLAR_OK;
 }
 
+extern "C" int poplar_step_forward_bytes(const poplar_model_cfg* cfg, int32_t stage, int32_t B, int64_t* bytes) {
+  POPLAR_TRY(validate_cfg(cfg));
+  if (stage < 0 || stage > 3 || B < 1 || !bytes) return poplar_fail(POPLAR_ERR_INVALID, "bad stage / batch / null pointer");
+  *bytes = step_plan(*cfg, stage, B, true).bytes;
+  return POPLAR_OK;
+}
+
 extern "C" int poplar_step_accounted_bytes(const poplar_model_cfg* cfg, int32_t stage, int32_t B, int32_t forward_only, int64_t* bytes) {
   POPLAR_TRY(validate_cfg(cfg));
   if (stage < 0 || stage > 3 || B < 0 || !bytes) return poplar_fail(POPLAR_ERR_INVALID, "bad stage / batch / null pointer");
@@ -140,6 +163,15 @@ int ctx_take(poplar_ctx* ctx, hipEvent_t* e) {
     ctx->events.push_back(ne);
   }
   *e = ctx->events[ctx->ev_next++];
+  return POPLAR_OK;
+}
+// grow the pool to n events now, so that no event is created between two timed marks
+static int ctx_reserve(poplar_ctx* ctx, size_t n) {
+  while (ctx->events.size() < n) {
+    hipEvent_t ne;
+    POPLAR_CHECK_HIP(hipEventCreateWithFlags(&ne, hipEventReleaseToDevice));
+    ctx->events.push_back(ne);
+  }
   return POPLAR_OK;
 }
 int ctx_mark(poplar_ctx* ctx, hipEvent_t* e) {
@@ -195,7 +227,9 @@ static int span_seconds(const std::vector<Span>& v, double* out) {
 // loss weight per token, whether its gradients add to what is there, whether the optimizer runs after it.
 struct MicroStep { int row0; float loss_scale; int accumulate; int optimizer; };
 
-static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_profile* out, const MicroStep* mstep = nullptr) {
+// workspace: the bound one, or one the memory hooks handed out for this step alone
+static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_profile* out, const MicroStep* mstep = nullptr,
+                    void* workspace = nullptr) {
   const poplar_model_cfg& c = ctx->cfg;
   const poplar_state& st = ctx->st;
   hipStream_t s = ctx->stream;
@@ -203,18 +237,18 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   const int64_t T = (int64_t)B * c.seq, H = c.hidden, es = elt_size(c.dtype);
   const Units u = units_of(c);
   const ModelOffsets mo = model_offsets(c);
-  const StepPlan sp = step_plan(c, stage, B);
+  const StepPlan sp = step_plan(c, stage, B, forward_only != 0);
   int64_t sh_off, sh_len, sh_valid;
   stage_shard(c, stage, u.P, &sh_off, &sh_len, &sh_valid);
 
-  char* ws = (char*)st.workspace;
+  char* ws = (char*)(workspace ? workspace : st.workspace);
   const int64_t xstride = round_up(T * H * es, 256);
   auto X = [&](int l) -> void* { return ws + sp.xs + (int64_t)l * xstride; };
   // with checkpointing every layer uses the one stash: the forward pass leaves nothing but the layer inputs X(l)
   auto SV = [&](int l) -> void* { return ws + sp.saved + (c.checkpoint ? 0 : (int64_t)l * sp.saved_each); };
   void* shared = ws + sp.shared;
-  void* dx_cur = ws + sp.dxa;
-  void* dx_nxt = ws + sp.dxb;
+  void* dx_cur = forward_only ? nullptr : ws + sp.dxa;
+  void* dx_nxt = forward_only ? nullptr : ws + sp.dxb;
   float* staging = sp.staging >= 0 ? (float*)(ws + sp.staging) : nullptr;
   float* staging_tail = staging ? staging + u.max_unit : nullptr;  // GPT: gf, bf gradients next to the tied wte bucket
   char* gbuf = sp.gather >= 0 ? ws + sp.gather : nullptr;
@@ -229,6 +263,10 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
 
   ctx->ev_next = 0;
   ctx->launches.clear();
+  // every event of the step exists before the first mark: four step marks, two per gather and per reduce span
+  // (at most two gathers and three reduces per unit), two per timed launch (at most 16 GEMM and 3 attention
+  // launches per layer, 4 in the head)
+  POPLAR_TRY(ctx_reserve(ctx, 8 + 2 * (size_t)(5 * (c.n_layer + 4)) + (ctx->kernel_timing ? 2 * (size_t)(20 * c.n_layer + 8) : 0)));
   ctx->in_step = true;
   struct StepScope { poplar_ctx* c; ~StepScope() { c->in_step = false; } } scope{ctx};
   EventCursor ev{ctx};
@@ -371,10 +409,25 @@ static int check_step_args(poplar_ctx* ctx, int stage, int B) {
   if (B < 1) return poplar_fail(POPLAR_ERR_INVALID, "batch must be >= 1, got %d", B);
   if (stage == 3 && !ctx->st.own_shard) return poplar_fail(POPLAR_ERR_INVALID, "stage 3 needs own_shard");
   if (B > ctx->st.max_batch) return poplar_fail(POPLAR_ERR_INVALID, "batch %d above the bound token buffer (%d)", B, ctx->st.max_batch);
+  // the bound buffers must hold what this stage touches: the optimizer runs over the stage's shard (all P elements
+  // at stage 0), the gradients are the whole flat vector at stage 0/1 and the shard at 2/3
+  const Units u = units_of(ctx->cfg);
+  int64_t off, len, valid;
+  stage_shard(ctx->cfg, stage, u.P, &off, &len, &valid);
+  if (valid > ctx->st.master_len)
+    return poplar_fail(POPLAR_ERR_INVALID, "stage %d updates %lld optimizer elements, master / m / v hold %lld", stage, (long long)valid,
+                       (long long)ctx->st.master_len);
+  const int64_t gneed = stage < 2 ? u.P : len;
+  if (gneed > ctx->st.grads_len)
+    return poplar_fail(POPLAR_ERR_INVALID, "stage %d needs a gradient buffer of %lld floats, the bound one holds %lld", stage, (long long)gneed,
+                       (long long)ctx->st.grads_len);
+  if (stage == 3 && valid > ctx->st.own_len)
+    return poplar_fail(POPLAR_ERR_INVALID, "stage 3 writes %lld parameters to own_shard, it holds %lld", (long long)valid, (long long)ctx->st.own_len);
   return POPLAR_OK;
 }
 
 static int check_memory(poplar_ctx* ctx, int stage, int B, int forward_only) {
+  if (ctx->have_hooks) return POPLAR_OK;   // the allocator behind the hooks decides
   const poplar_model_cfg& c = ctx->cfg;
   const int64_t acc = accounted_bytes(c, stage, B, forward_only);
   if (c.cap_bytes > 0 && acc > c.cap_bytes)
@@ -386,11 +439,65 @@ static int check_memory(poplar_ctx* ctx, int stage, int B, int forward_only) {
   return POPLAR_OK;
 }
 
+extern "C" int poplar_set_sampling(poplar_ctx* ctx, int32_t warmup, int32_t repeats) {
+  if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
+  if (warmup < 0 || repeats < 1 || warmup > 64 || repeats > 65) return poplar_fail(POPLAR_ERR_INVALID, "need 0 <= warmup <= 64 and 1 <= repeats <= 65");
+  ctx->warmup = warmup; ctx->repeats = repeats;
+  return POPLAR_OK;
+}
+
+extern "C" int poplar_set_mem_hooks(poplar_ctx* ctx, const poplar_mem_hooks* hooks) {
+  if (!ctx) return poplar_fail(POPLAR_ERR_INVALID, "ctx is null");
+  if (!hooks) { ctx->have_hooks = false; return POPLAR_OK; }
+  if (!hooks->alloc || !hooks->release || !hooks->bytes_now || !hooks->bytes_total) return poplar_fail(POPLAR_ERR_INVALID, "a memory hook is null");
+  ctx->hooks = *hooks;
+  ctx->have_hooks = true;
+  return POPLAR_OK;
+}
+
+// A workspace for one step at (stage, B): with hooks, asked of the caller's allocator (POPLAR_ERR_OOM when it has
+// none to give; nothing has been launched and the state is as it was); without, the bound one.
+struct StepWorkspace {
+  poplar_ctx* ctx;
+  void* p = nullptr;
+  bool owned = false;
+  int64_t held_bytes = 0;   // what the allocator reports while the workspace is held
+  int acquire(int stage, int B, bool forward_only) {
+    if (!ctx->have_hooks) { p = ctx->st.workspace; return POPLAR_OK; }
+    const int64_t need = step_plan(ctx->cfg, stage, B, forward_only).bytes;
+    p = ctx->hooks.alloc(ctx->hooks.user, need);
+    if (!p) return poplar_fail(POPLAR_ERR_OOM, "stage %d batch %d: the allocator refused a workspace of %lld bytes", stage, B, (long long)need);
+    owned = true;
+    held_bytes = ctx->hooks.bytes_now(ctx->hooks.user);
+    return POPLAR_OK;
+  }
+  ~StepWorkspace() {
+    if (owned) ctx->hooks.release(ctx->hooks.user, p);   // every step has synchronised the stream before it returns
+  }
+};
+
+// One profile sample: `warmup` untimed runs, `repeats` timed ones, the run with the median TimeConsumedDuringStep
+// (the lower of the two middle ones for an even count) is reported whole, so that its fields belong together.
+static int sample_step(poplar_ctx* ctx, int stage, int B, poplar_profile* out) {
+  StepWorkspace w{ctx};
+  POPLAR_TRY(w.acquire(stage, B, false));
+  poplar_profile tmp;
+  for (int i = 0; i < ctx->warmup; ++i) POPLAR_TRY(run_step(ctx, stage, B, 0, &tmp, nullptr, w.p));
+  std::vector<poplar_profile> runs((size_t)ctx->repeats);
+  for (int i = 0; i < ctx->repeats; ++i) POPLAR_TRY(run_step(ctx, stage, B, 0, &runs[i], nullptr, w.p));
+  std::vector<int> order((size_t)ctx->repeats);
+  for (int i = 0; i < ctx->repeats; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return runs[a].t_consumed < runs[b].t_consumed; });
+  *out = runs[order[(ctx->repeats - 1) / 2]];
+  out->measured_bytes = w.held_bytes;
+  return POPLAR_OK;
+}
+
 extern "C" int poplar_profile_step(poplar_ctx* ctx, int32_t stage, int32_t local_batch, poplar_profile* out) {
   POPLAR_TRY(check_step_args(ctx, stage, local_batch));
   if (!out) return poplar_fail(POPLAR_ERR_INVALID, "out is null");
   POPLAR_TRY(check_memory(ctx, stage, local_batch, 0));
-  return run_step(ctx, stage, local_batch, 0, out);
+  return sample_step(ctx, stage, local_batch, out);
 }
 
 extern "C" int poplar_accum_step(poplar_ctx* ctx, int32_t stage, int32_t n_micro, const int32_t* micro_batch, int32_t loss_batch,
@@ -399,16 +506,22 @@ extern "C" int poplar_accum_step(poplar_ctx* ctx, int32_t stage, int32_t n_micro
   if (n_micro < 1 || !micro_batch || !out) return poplar_fail(POPLAR_ERR_INVALID, "need n_micro >= 1, micro_batch and out");
   if (loss_batch < 1) return poplar_fail(POPLAR_ERR_INVALID, "loss_batch must be >= 1, got %d", loss_batch);
   int64_t rows = 0;
+  int bmax = 0;
   for (int k = 0; k < n_micro; ++k) {
     POPLAR_TRY(check_step_args(ctx, stage, micro_batch[k]));
     POPLAR_TRY(check_memory(ctx, stage, micro_batch[k], 0));
     rows += micro_batch[k];
+    bmax = std::max(bmax, (int)micro_batch[k]);
   }
   if (rows > ctx->st.max_batch)
     return poplar_fail(POPLAR_ERR_INVALID, "micro-batches sum to %lld samples, the bound token buffer holds %d", (long long)rows, ctx->st.max_batch);
+  // one workspace, sized for the largest micro-batch, serves the whole run
+  StepWorkspace w{ctx};
+  POPLAR_TRY(w.acquire(stage, bmax, false));
   poplar_profile tot;
   memset(&tot, 0, sizeof tot);
   tot.stage = stage;
+  tot.measured_bytes = w.held_bytes;
   int row0 = 0;
   for (int k = 0; k < n_micro; ++k) {
     MicroStep ms;
@@ -417,7 +530,7 @@ extern "C" int poplar_accum_step(poplar_ctx* ctx, int32_t stage, int32_t n_micro
     ms.accumulate = k > 0;
     ms.optimizer = k == n_micro - 1;
     poplar_profile pr;
-    POPLAR_TRY(run_step(ctx, stage, micro_batch[k], 0, &pr, &ms));
+    POPLAR_TRY(run_step(ctx, stage, micro_batch[k], 0, &pr, &ms, w.p));
     row0 += micro_batch[k];
     tot.batch += pr.batch;
     tot.t_fwd += pr.t_fwd; tot.t_bwd += pr.t_bwd; tot.t_gather_fwd += pr.t_gather_fwd; tot.t_gather_bwd += pr.t_gather_bwd;
@@ -437,21 +550,35 @@ extern "C" int poplar_search_mbs(poplar_ctx* ctx, int32_t stage, int32_t* mbs, p
   if (!mbs || !samples || !n_samples || max_samples < 1) return poplar_fail(POPLAR_ERR_INVALID, "null output or no room for samples");
   const poplar_model_cfg& c = ctx->cfg;
   *mbs = 0; *n_samples = 0;
-  // step 1: memory before and after one forward pass at batch 1 gives the theoretical maximum
-  int64_t total = c.cap_bytes;
-  if (total == 0) {
-    size_t free_b = 0, total_b = 0;
-    POPLAR_CHECK_HIP(hipMemGetInfo(&free_b, &total_b));
-    total = (int64_t)total_b;
+  // step 1: memory before and after one forward pass at batch 1 gives the theoretical maximum.  With memory hooks
+  // both readings and the total are the allocator's; without, they are the accounted bytes and the emulated cap.
+  int64_t total, bf, af;
+  if (ctx->have_hooks) {
+    total = ctx->hooks.bytes_total(ctx->hooks.user);
+    bf = ctx->hooks.bytes_now(ctx->hooks.user);
+    StepWorkspace w{ctx};
+    const int rc = w.acquire(stage, 1, true);
+    if (rc == POPLAR_ERR_OOM) return POPLAR_OK;   // not even the forward pass of one sample can be held: mbs = 0
+    POPLAR_TRY(rc);
+    poplar_profile fwd;
+    POPLAR_TRY(run_step(ctx, stage, 1, 1, &fwd, nullptr, w.p));
+    af = w.held_bytes;
+  } else {
+    total = c.cap_bytes;
+    if (total == 0) {
+      size_t free_b = 0, total_b = 0;
+      POPLAR_CHECK_HIP(hipMemGetInfo(&free_b, &total_b));
+      total = (int64_t)total_b;
+    }
+    bf = accounted_bytes(c, stage, 0, 1);
+    poplar_profile fwd;
+    const int rc = check_memory(ctx, stage, 1, 1);
+    if (rc == POPLAR_ERR_OOM) return POPLAR_OK;  // not even a forward pass of one sample fits: mbs = 0
+    POPLAR_TRY(rc);
+    POPLAR_TRY(run_step(ctx, stage, 1, 1, &fwd));
+    af = fwd.accounted_bytes;
   }
-  const int64_t bf = accounted_bytes(c, stage, 0, 1);
-  poplar_profile fwd;
-  int rc = check_memory(ctx, stage, 1, 1);
-  if (rc == POPLAR_ERR_OOM) return POPLAR_OK;  // not even a forward pass of one sample fits: mbs = 0
-  POPLAR_TRY(rc);
-  POPLAR_TRY(run_step(ctx, stage, 1, 1, &fwd));
-  const int64_t af = fwd.accounted_bytes;
-  if (af <= bf) return poplar_fail(POPLAR_ERR_INVALID, "forward pass accounted no memory");
+  if (af <= bf) return poplar_fail(POPLAR_ERR_INVALID, "forward pass took no memory (%lld bytes before, %lld after)", (long long)bf, (long long)af);
   int64_t est = (total - bf) / (af - bf);
   if (est > ctx->st.max_batch) est = ctx->st.max_batch;
   auto try_step = [&](int b, bool* fits) -> int {
@@ -460,7 +587,9 @@ extern "C" int poplar_search_mbs(poplar_ctx* ctx, int32_t stage, int32_t* mbs, p
     if (r == POPLAR_ERR_OOM) return POPLAR_OK;
     POPLAR_TRY(r);
     if (*n_samples >= max_samples) return poplar_fail(POPLAR_ERR_INVALID, "more than %d samples", max_samples);
-    POPLAR_TRY(run_step(ctx, stage, b, 0, &samples[*n_samples]));
+    r = sample_step(ctx, stage, b, &samples[*n_samples]);
+    if (r == POPLAR_ERR_OOM) return POPLAR_OK;   // the allocator behind the hooks had no room: nothing ran
+    POPLAR_TRY(r);
     *n_samples += 1;
     *fits = true;
     return POPLAR_OK;

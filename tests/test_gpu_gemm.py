@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2408_12596_amd import binding as pb
-from gpu_util import DEV, rel_l2, to_np, sync
+from gpu_util import DEV, assert_close_blockwise, rel_l2, to_np, sync
 
 pytestmark = pytest.mark.gpu
 
@@ -88,6 +88,45 @@ def test_gemm_ragged_mid_size_on_sampled_outputs(layout, M, N, K, c_float):
 @pytest.mark.parametrize("layout,M,N,K", FULL)
 def test_gemm_full_size_on_sampled_outputs(layout, M, N, K):
     check_sampled(layout, M, N, K, True)
+
+
+# Every element of the output, tile by tile, at the shapes the benchmark launches: the three GPT-2-small products at
+# local batch 16, the LM head at 16384 tokens (all three of its products), the ~1.3B layer's products at local
+# batch 13 (26624 tokens: an odd tile count on every axis that carries the tokens) and the Llama-7B shape's at 4.
+WHOLE = [
+    (pb.GEMM_NT, 16384, 2304, 768, False), (pb.GEMM_NN, 16384, 768, 3072, False), (pb.GEMM_TN, 3072, 768, 16384, True),
+    (pb.GEMM_NT, 16384, 50257, 768, False), (pb.GEMM_NN, 16384, 768, 50257, False), (pb.GEMM_TN, 50257, 768, 16384, True),
+    (pb.GEMM_NT, 26624, 8192, 2048, False), (pb.GEMM_NN, 26624, 2048, 8192, False), (pb.GEMM_TN, 8192, 2048, 26624, True),
+    (pb.GEMM_TN, 2048, 6144, 26624, True),
+    (pb.GEMM_NT, 8192, 22016, 4096, False), (pb.GEMM_TN, 4096, 11008, 8192, True),
+]
+
+
+@pytest.mark.parametrize("layout,M,N,K,c_float", WHOLE)
+def test_gemm_full_size_every_tile(layout, M, N, K, c_float):
+    """The float64 product of the same operands, compared whole and on every 64 x 64 tile of the output."""
+    ctx = pb.Context(pb.make_cfg(dtype="bf16"))
+    g = torch.Generator().manual_seed(layout * 11 + 3)
+    sa = (K, M) if layout == pb.GEMM_TN else (M, K)
+    sb = (N, K) if layout == pb.GEMM_NT else (K, N)
+    lda, ldb = sa[1] + (-sa[1]) % 8, sb[1] + (-sb[1]) % 8
+    if layout == pb.GEMM_NN and K % 64:
+        lda = K + (-K) % 64                                  # the head's input gradient: logits rows padded with zeros
+    A = torch.zeros(sa[0], lda, dtype=torch.bfloat16)
+    A[:, :sa[1]] = torch.randn(sa, generator=g).to(torch.bfloat16)
+    B = torch.zeros(sb[0], ldb, dtype=torch.bfloat16)
+    B[:, :sb[1]] = torch.randn(sb, generator=g).to(torch.bfloat16)
+    dA, dB = A.to(DEV), B.to(DEV)
+    ldc = N + (-N) % 8
+    C = torch.full((M, ldc), float("nan"), device=DEV, dtype=torch.float32 if c_float else torch.bfloat16)
+    ctx.gemm(layout, M, N, K, dA, lda, dB, ldb, C, ldc, c_float=c_float, beta=0.0)
+    sync()
+    got = C[:, :N].float().cpu().numpy()
+    del C
+    a, b = A[:, :sa[1]].double().numpy(), B[:, :sb[1]].double().numpy()
+    ref = a @ b.T if layout == pb.GEMM_NT else a @ b if layout == pb.GEMM_NN else a.T @ b
+    assert np.isfinite(got).all()
+    assert_close_blockwise(got, ref, 1e-5 if c_float else 4e-3, name=(layout, M, N, K))
 
 
 def check_sampled(layout, M, N, K, c_float):

@@ -362,7 +362,9 @@ def test_search_moves_to_the_next_stage_when_nothing_fits():
     assert cap < need[1] and cap < pb.step_accounted_bytes(probe, 2, 2)
     rk = Rank(model, "bf16", 3, world, 0, max_batch=8, cap_bytes=cap)          # built for stage 3: has own_shard
     grads = torch.zeros(rk.P, device=DEV)                                      # a gradient buffer that serves every stage
-    rk.ctx.bind_state(rk.params, rk.master, rk.m, rk.v, grads, rk.tokens, 8, rk.ws, rk.wsb, rk.loss, own_shard=rk.own, adam_t=1)
+    # stage 0 keeps the whole optimizer on the rank: master, m, v of P elements (rank 0's shard is their head)
+    master, m, v = to_dev(rk.flat), torch.zeros(rk.P, device=DEV), torch.zeros(rk.P, device=DEV)
+    rk.ctx.bind_state(rk.params, master, m, v, grads, rk.tokens, 8, rk.ws, rk.wsb, rk.loss, own_shard=rk.own, adam_t=1)
     stage, mbs, samples = rk.ctx.search_stage(0)
 
     def search(s):
@@ -374,6 +376,142 @@ def test_search_moves_to_the_next_stage_when_nothing_fits():
     # nothing fits anywhere
     tiny = Rank(model, "bf16", 3, world, 0, max_batch=2, cap_bytes=1000)
     assert tiny.ctx.search_stage(1) == (-1, 0, [])
+    # a state sized for the shard cannot serve stage 0, where Adam runs over all P elements: refused before anything
+    # is launched, also when stage 0 would fit the cap
+    roomy = Rank(model, "bf16", 3, world, 0, max_batch=2)
+    roomy.ctx.bind_state(roomy.params, roomy.master, roomy.m, roomy.v, grads, roomy.tokens, 2, roomy.ws, roomy.wsb, roomy.loss,
+                         own_shard=roomy.own, adam_t=1)
+    before = roomy.master.clone()
+    for call in (lambda: roomy.ctx.search_stage(0), lambda: roomy.ctx.profile_step(0, 1), lambda: roomy.ctx.accum_step(0, [1], 1)):
+        with pytest.raises(pb.PoplarError) as e:
+            call()
+        assert e.value.status == pb.ERR_INVALID and "optimizer elements" in str(e.value)
+    sync()
+    assert torch.equal(before, roomy.master)
+    assert roomy.ctx.search_stage(1)[0] == 1          # from stage 1 on the same state serves
+
+
+# ---- how many runs stand behind a profile sample ------------------------------------------------------------------
+def test_sampling_runs_warmup_and_repeats_and_reports_the_median_run():
+    model = MODELS["gpt"]
+    # rank 3's shard holds no part of wte (float atomics in free order): everything else is bit-reproducible
+    a = Rank(model, "f32", 1, 4, 3, max_batch=3)
+    b = Rank(model, "f32", 1, 4, 3, max_batch=3)
+    a.ctx.set_sampling(1, 3)
+    pa = a.ctx.profile_step(1, 3)
+    runs = [b.ctx.profile_step(1, 3) for _ in range(4)]
+    sync()
+    assert torch.equal(a.master, b.master) and torch.equal(a.m, b.m)       # four real steps each
+    assert pa["loss"] in [r["loss"] for r in runs[1:]]                     # one of the three timed runs, reported whole
+    assert pa["t_consumed"] > 0 and pa["batch"] == 3
+    for bad in ((-1, 1), (0, 0), (65, 1), (0, 66)):
+        with pytest.raises(pb.PoplarError):
+            a.ctx.set_sampling(*bad)
+    # the median of three is never the slowest run: a warmed-up sample does not carry first-launch costs
+    c = Rank(model, "bf16", 1, 4, 0, max_batch=8)
+    cold = c.ctx.profile_step(1, 8)["t_consumed"]
+    c.ctx.set_sampling(1, 5)
+    warm = [c.ctx.profile_step(1, 8)["t_consumed"] for _ in range(3)]
+    assert max(warm) <= 1.5 * min(warm)                                      # stated spread of repeated samples
+    assert min(warm) <= cold
+
+
+def test_two_searches_give_the_same_allocation():
+    model, world, stage = MODELS["gpt"], 4, 1
+    probe = pb.make_cfg(**model, dtype="bf16", world=world, zero_stage=stage)
+    cap = pb.step_accounted_bytes(probe, stage, 12) + 100
+    rk = Rank(model, "bf16", stage, world, 0, max_batch=16, cap_bytes=cap)
+    rk.ctx.set_sampling(2, 5)
+    found = [rk.ctx.search_mbs(stage) for _ in range(2)]
+    assert found[0][0] == found[1][0] == 12
+    assert [s["batch"] for s in found[0][1]] == [s["batch"] for s in found[1][1]]
+    for s0, s1 in zip(found[0][1], found[1][1]):
+        assert abs(s0["t_consumed"] - s1["t_consumed"]) <= 0.5 * min(s0["t_consumed"], s1["t_consumed"])
+    plans = []
+    for mbs, samples in found:
+        bs, ts = [s["batch"] for s in samples], [s["t_consumed"] for s in samples]
+        curves = [(bs, [t * k for t in ts], mbs) for k in (1.0, 1 / 1.5, 1 / 2.0, 1 / 3.0)]
+        plans.append(pb.allocate(stage, 64, curves, 0.0))
+    assert plans[0]["gmbs"] == plans[1]["gmbs"] and sum(plans[0]["gmbs"]) == 64
+
+
+# ---- memory by measurement: the search against a real allocator with a byte budget --------------------------------
+class BudgetAllocator:
+    """torch's caching allocator behind a byte budget: alloc() hands out device memory while the bytes requested
+    so far (on top of what was held when the budget began) stay inside it, else refuses."""
+
+    def __init__(self, budget):
+        self.base = torch.cuda.memory_allocated()
+        self.budget, self.held, self.requested, self.log = budget, {}, 0, []
+
+    def alloc(self, n):
+        self.log.append(n)
+        if self.base + self.requested + n > self.budget:
+            return 0
+        t = torch.full((n,), 255, dtype=torch.uint8, device=DEV)      # poisoned like every other scratch here
+        self.held[t.data_ptr()] = (t, n)
+        self.requested += n
+        return t.data_ptr()
+
+    def release(self, p):
+        self.requested -= self.held.pop(p)[1]
+
+    def bytes_now(self):
+        return self.base + self.requested
+
+    def bytes_total(self):
+        return self.budget
+
+
+@pytest.mark.parametrize("stage", [1, 3])
+def test_search_mbs_against_a_measuring_allocator(stage):
+    model, world, want = MODELS["gpt"], 4, 11
+    rk = Rank(model, "bf16", stage, world, 0, max_batch=16)
+    ws_bytes = lambda b: pb.step_workspace_bytes(rk.cfg, stage, b)
+    al = BudgetAllocator(0)
+    al.budget = al.base + ws_bytes(want) + 100                        # room for the workspace of 11 samples, not of 12
+    rk.ctx.bind_state(rk.params, rk.master, rk.m, rk.v, rk.grads, rk.tokens, 16, None, 0, rk.loss, own_shard=rk.own, adam_t=1)
+    rk.ctx.set_mem_hooks(al.alloc, al.release, al.bytes_now, al.bytes_total)
+    mbs, samples = rk.ctx.search_mbs(stage)
+    asked = list(al.log)
+    assert mbs == want == max(b for b in range(17) if al.base + ws_bytes(b) <= al.budget)
+    assert not al.held and al.requested == 0                          # every workspace went back
+    fwd1 = pb.step_forward_bytes(rk.cfg, stage, 1)
+    assert al.log[0] == fwd1 and fwd1 < ws_bytes(1)
+    # the oracle's Algorithm 1 on the same allocator model visits the same batches in the same order
+    now = [al.base]
+
+    def forward(b):
+        now[0] = al.base + pb.step_forward_bytes(rk.cfg, stage, b)
+
+    tried = []
+
+    def step(b):
+        tried.append(b)
+        if al.base + ws_bytes(b) > al.budget:
+            raise opf.OutOfMemory()
+        return 1.0
+    o_mbs, o_samples = opf.search_mbs(lambda: now[0], forward, step, al.budget)
+    assert o_mbs == mbs and [s["batch"] for s in samples] == [b for b, _ in o_samples]
+    assert asked[1:] == [ws_bytes(b) for b in tried] and tried == [1, 2, 4, 8, 16, 12, 10, 11]
+    for s in samples:
+        assert s["measured_bytes"] == al.base + ws_bytes(s["batch"]) and s["t_consumed"] > 0 and np.isfinite(s["loss"])
+    # a refused allocation is POPLAR_ERR_OOM with the state as it was
+    before = rk.master.clone()
+    with pytest.raises(pb.OutOfMemory):
+        rk.ctx.profile_step(stage, 12)
+    sync()
+    assert torch.equal(before, rk.master)
+    # and the result of a step in an allocator-supplied workspace is the step's: same loss as with a bound workspace
+    twin = Rank(model, "bf16", stage, world, 0, max_batch=16)
+    rk2 = Rank(model, "bf16", stage, world, 0, max_batch=16)
+    al2 = BudgetAllocator(1 << 60)
+    rk2.ctx.set_mem_hooks(al2.alloc, al2.release, al2.bytes_now, al2.bytes_total)
+    p_hook, p_bound = rk2.ctx.profile_step(stage, 3), twin.ctx.profile_step(stage, 3)
+    sync()
+    assert p_hook["loss"] == p_bound["loss"] and p_bound["measured_bytes"] == 0
+    rk2.ctx.set_mem_hooks()
+    assert rk2.ctx.profile_step(stage, 3)["measured_bytes"] == 0
 
 
 def test_kernel_timing_selects_and_counts_the_launches():

@@ -160,3 +160,129 @@ def test_checkpointing_keeps_one_stash_instead_of_one_per_layer():
         bad = pb.make_cfg(**base)
         bad.checkpoint = 2
         pb.model_param_count(bad)
+
+
+# ---- the allocator against things the oracle does not supply ------------------------------------------------------
+def test_dipping_and_negative_splines_from_fixture():
+    """tests/golden/alloc_dip_cases.json: hand-worked curves whose spline dips in time or falls below zero in speed."""
+    import json
+    with open(os.path.join(ROOT, "tests", "golden", "alloc_dip_cases.json")) as f:
+        gold = json.load(f)
+    for case in gold["cases"]:
+        curve = (case["batches"], case["times"], case["mbs"])
+        sp = pb.speed_curve(*curve)
+        assert sp[0] == 0.0
+        np.testing.assert_allclose(sp[1:], case["speed"], rtol=1e-12)
+        a = case["alloc"]
+        got = pb.allocate(a["stage"], a["gbs"], [curve], a["time_communication"])
+        assert got["b"] == a["b"] and got["gas"] == [a["gas"]] and got["lbs"] == a["lbs"] and got["gmbs"] == a["gmbs"]
+        assert abs(got["t"] - a["t"]) < 1e-12 and abs(got["T"] - a["wall"]) < 1e-12 and got["T_steps"] == got["T"]
+        # `find` through the library: with communication so costly that only the step count matters, a lone device
+        # whose gbs equals its batch at time t runs that batch in one step
+        for t, b in case["find"]:
+            if b == 0:
+                continue
+            one = pb.allocate(2, b, [curve], 1e12)
+            assert one["gas"] == [1] and one["b"][0] >= b
+
+
+def _compositions(total, n):
+    import itertools
+    for c in itertools.combinations(range(total + n - 1), n - 1):
+        yield [b - a - 1 for a, b in zip((-1,) + c, c + (total + n - 1,))]
+
+
+def test_stage01_split_minimises_eq1_and_eq4_by_brute_force_on_the_library():
+    """Every split of gbs over the devices, Eq. (1) and Eq. (4) evaluated here from the devices' peak speeds: the
+    library's split attains both minima, and its remainder hand-out never leaves a device that could take a sample
+    and still finish before the slowest one (the equal-step-time property, as far as integers allow)."""
+    rng = np.random.default_rng(7)
+    for _ in range(60):
+        n = int(rng.integers(2, 5))
+        gbs = int(rng.integers(1, 19))
+        speeds = [float(rng.integers(1, 9)) / 2 for _ in range(n)]
+        pts = [1, 2, 4, 8, 16, 32]
+        got = pb.allocate(0, gbs, [(pts, [b / s for b in pts], 32) for s in speeds])
+        g = got["gmbs"]
+        assert sum(g) == gbs and min(g) >= 0
+        best_T = best_U = np.inf
+        for B in _compositions(gbs, n):
+            t = [b / s for b, s in zip(B, speeds)]
+            T = max(t)
+            best_T = min(best_T, T)
+            best_U = min(best_U, sum((T - ti) * pi for ti, pi in zip(t, speeds)))
+        t = [gi / s for gi, s in zip(g, speeds)]
+        T = max(t)
+        assert abs(T - best_T) < 1e-12 and abs(got["T"] - best_T) < 1e-12
+        assert abs(sum((T - ti) * pi for ti, pi in zip(t, speeds)) - best_U) < 1e-9
+        last = int(np.argmax(t))          # no other device could take one more sample and finish before the slowest one
+        assert all((g[j] + 1) / speeds[j] >= T - 1e-12 for j in range(n) if j != last)
+
+
+def test_stage23_wall_time_is_the_brute_force_minimum_on_the_library():
+    """All micro-batch vectors (b_1..b_n): wall = (max_i time_i(b_i) + t_comm) ceil(gbs / sum b), with time_i read
+    from the library's own speed curve; the sweep over t with `find` must reach the exhaustive minimum."""
+    import itertools
+    rng = np.random.default_rng(8)
+    for _ in range(40):
+        n = int(rng.integers(2, 4))
+        curves = []
+        for _i in range(n):
+            mbs = int(rng.integers(1, 7))
+            bs = sorted(set([1, mbs] + [int(b) for b in rng.integers(1, mbs + 1, 2)]))
+            sat, half = float(rng.uniform(1, 6)), float(rng.uniform(0.5, 4))
+            noise = rng.uniform(0.8, 1.25, len(bs))                       # noisy enough for dips
+            curves.append((bs, [b / (sat * b / (b + half)) * float(k) for b, k in zip(bs, noise)], mbs))
+        gbs = int(rng.integers(1, 40))
+        tc = float(rng.choice([0.0, 0.3, 5.0]))
+        got = pb.allocate(3, gbs, curves, tc)
+        tms = []
+        for c in curves:
+            sp = pb.speed_curve(*c)
+            tms.append(np.concatenate([[0.0], np.maximum.accumulate([b / sp[b] for b in range(1, c[2] + 1)])]))
+        best = np.inf
+        for B in itertools.product(*[range(0, c[2] + 1) for c in curves]):
+            if sum(B):
+                best = min(best, (max(tms[i][b] for i, b in enumerate(B)) + tc) * -(-gbs // sum(B)))
+        assert abs(got["T"] - best) <= 1e-12 * max(1.0, best)
+        assert sum(got["gmbs"]) == gbs
+        assert all(0 <= l <= b <= c[2] for l, b, c in zip(got["lbs"], got["b"], curves))
+        assert all(tms[i][b] <= got["t"] * (1 + 1e-15) for i, b in enumerate(got["b"]))
+
+
+def test_stage01_predicted_time_on_the_curve_itself():
+    bs = list(range(1, 9))
+    sp = [1.0, 2.0, 3.0, 3.9, 4.0, 4.0, 4.0, 4.0]
+    fast = (bs, [b / s for b, s in zip(bs, sp)], 8)
+    slow = (bs, [b / (s / 2) for b, s in zip(bs, sp)], 6)
+    got = pb.allocate(1, 30, [fast, slow])
+    ref = oal.allocate(1, 30, [fast, slow])
+    assert got["gmbs"] == [20, 10] and got["b"] == [8, 6] and got["gas"] == [3, 2] and got["lbs"] == [4, 4]
+    assert abs(got["T"] - 5.0) < 1e-12
+    assert abs(got["T_steps"] - max(2 * 8 / 4.0 + 4 / 3.9, 6 / 2.0 + 4 / 1.95)) < 1e-12
+    assert abs(got["T_steps"] - ref["T_steps"]) < 1e-12 and got["T_steps"] >= got["T"]
+
+
+def test_state_sized_for_a_shard_cannot_run_stage_0():
+    """Host-side check only (nothing is launched, so no GPU is needed): stage 0 runs the optimizer over all P
+    elements; a state whose master / m / v hold one shard is refused."""
+    cfg = pb.make_cfg(arch="gpt", L=2, H=128, nh=2, F=256, S=64, V=211, dtype="bf16", world=4, rank=0)
+    P = pb.model_param_count(cfg)
+    off, ln, valid = pb.shard_range(P, 4, 0)
+    ctx = pb.Context(cfg)
+    fake = 0x1000   # never dereferenced: every call below fails its argument checks first
+    ctx.bind_state(fake, fake, fake, fake, fake, fake, 4, fake, 1 << 40, fake, master_len=ln, grads_len=P, own_len=0)
+    for stage, word in ((0, "optimizer elements"), (3, "own_shard")):
+        with pytest.raises(pb.PoplarError) as e:
+            ctx.profile_step(stage, 1)
+        assert e.value.status == pb.ERR_INVALID and word in str(e.value)
+    ctx.bind_state(fake, fake, fake, fake, fake, fake, 4, fake, 1 << 40, fake, master_len=ln, grads_len=ln, own_len=0)
+    with pytest.raises(pb.PoplarError) as e:
+        ctx.profile_step(1, 1)                      # stage 1 keeps the whole gradient
+    assert "gradient buffer" in str(e.value)
+    with pytest.raises(pb.PoplarError):
+        ctx.bind_state(fake, fake, fake, fake, fake, fake, 4, fake, 0, fake, master_len=0, grads_len=P, own_len=0)
+    with pytest.raises(pb.PoplarError):
+        ctx.bind_state(fake, fake, fake, fake, fake, fake, 4, fake, 0, fake, own_shard=fake, master_len=ln, grads_len=P, own_len=0)
+    with pytest.raises(pb.PoplarError):
+        ctx.set_sampling(0, 0)

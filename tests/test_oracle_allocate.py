@@ -31,6 +31,32 @@ def test_hand_cases_from_fixture():
             assert abs(al.under_utilization(t, case["speeds"])) < 1e-9
 
 
+def test_dipping_and_negative_splines_from_fixture():
+    # pins the running maximum of the step-time curve, the speed floor and `find`
+    with open(os.path.join(GOLDEN, "alloc_dip_cases.json")) as f:
+        gold = json.load(f)
+    for case in gold["cases"]:
+        curve = (case["batches"], case["times"], case["mbs"])
+        sp = al.speed_curve(*curve)
+        np.testing.assert_allclose(sp[1:], case["speed"], rtol=1e-12)
+        tm = al.time_curve(sp)
+        assert tm[0] == 0.0
+        np.testing.assert_allclose(tm[1:], case["time"], rtol=1e-12)
+        assert np.all(np.diff(tm) >= 0)
+        for t, b in case["find"]:
+            assert al.find(tm, t) == b, (case["name"], t)
+        a = case["alloc"]
+        out = al.allocate(a["stage"], a["gbs"], [curve], a["time_communication"])
+        assert out["b"] == a["b"] and out["gas"] == a["gas"] and out["lbs"] == a["lbs"] and out["gmbs"] == a["gmbs"]
+        assert abs(out["t"] - a["t"]) < 1e-12 and abs(out["wall"] - a["wall"]) < 1e-12
+
+
+def test_find_is_the_largest_batch_within_t():
+    tm = np.array([0.0, 1.0, 1.0, 2.5, 2.5, 7.0])
+    assert [al.find(tm, t) for t in (0.5, 1.0, 2.4, 2.5, 6.9, 7.0, 1e9)] == [0, 2, 2, 4, 4, 5, 5]
+    assert al.find(np.zeros(1), 3.0) == 0       # a device that cannot run one sample
+
+
 def compositions(total, n):
     for c in itertools.combinations(range(total + n - 1), n - 1):
         yield [b - a - 1 for a, b in zip((-1,) + c, c + (total + n - 1,))]
@@ -70,6 +96,10 @@ def test_stage01_micro_batches_and_accumulation():
     for i in range(2):
         assert (out["gas"][i] - 1) * out["b"][i] + out["lbs"][i] == out["gmbs"][i]
         assert 1 <= out["lbs"][i] <= out["b"][i]
+    # Eq. 1 on the peak speeds (what the split was made for) against Eq. 1 on the steps that will really run:
+    # fast: two steps of 8 at speed 4 and one of 4 at speed 3.9; slow: one of 6 at speed 2 and one of 4 at 1.95
+    assert abs(out["T"] - 5.0) < 1e-12
+    assert abs(out["T_steps"] - max(2 * 8 / 4.0 + 4 / 3.9, 6 / 2.0 + 4 / 1.95)) < 1e-12
     # a device that gets nothing
     out = al.allocate(1, 1, [fast, slow])
     assert out["gmbs"] == [1, 0] and out["b"] == [1, 0] and out["gas"] == [1, 0] and out["lbs"] == [1, 0]

@@ -16,6 +16,28 @@ def test_feed_forward_block_at_stage_3_is_24_d_h_squared():
         assert ocomm.comm_elements(P, d, 3) == (2 * P, P, 0, 0)
 
 
+def test_elements_per_stage_follow_from_the_appendix_list_of_collectives():
+    # tests/golden/zero_collectives.json lists, stage by stage, the collectives Appendix "Details about ZeRO" names;
+    # every one moves the whole flat vector (P elements per device, the count of Appendix "Analysis of Experiments")
+    import json, os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "zero_collectives.json")) as f:
+        gold = json.load(f)["stages"]
+    P, d = 12345, 6
+    for stage in range(4):
+        want = {("micro_step", "parameters"): 0, ("micro_step", "gradients"): 0, ("optimizer_step", "parameters"): 0, ("optimizer_step", "gradients"): 0}
+        for c in gold[str(stage)]:
+            assert c["collective"] in ("reduce_scatter", "all_gather")
+            want[(c["when"], c["operand"])] += P
+        assert ocomm.comm_elements(P, d, stage) == (want[("micro_step", "parameters")], want[("micro_step", "gradients")],
+                                                    want[("optimizer_step", "parameters")], want[("optimizer_step", "gradients")]), stage
+    # textbook cross-check of the stage 0 total: a ring all-reduce moves 2 (d-1)/d P elements per device, which the
+    # paper's count (no (d-1)/d deduction) bounds from above and meets as d grows
+    for dd in (2, 8, 1024):
+        ring = 2 * (dd - 1) / dd * P
+        paper = sum(ocomm.comm_elements(P, dd, 0))
+        assert ring <= paper and paper / ring == pytest.approx(dd / (dd - 1))
+
+
 def test_collectives_per_stage_follow_the_appendix():
     P, d = 1000, 4
     # stage 0: all-reduce = reduce-scatter + all-gather of the gradients, at the end of the step
