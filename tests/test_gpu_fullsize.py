@@ -207,7 +207,18 @@ def test_gpt2_small_step_at_the_benchmark_configuration():
     sync()
     gacc = to_np(acc.grads)
     assert abs(pacc["loss"] - loss16) <= 5e-3 * abs(loss16)
-    assert_close_blockwise(gacc[:acc.valid], grad16[acc.off:acc.off + acc.valid], 2e-2, "stage 2 shard", block=4096)
+    assert rel_l2(gacc[:acc.valid], grad16[acc.off:acc.off + acc.valid]) <= 2e-2
+    seen = 0
+    for name, (off, shape) in table.items():      # tensor by tensor, the rows that lie inside the shard
+        cols = shape[-1] if len(shape) == 2 else 1
+        lo, hi = max(off, acc.off), min(off + int(np.prod(shape)), acc.off + acc.valid)
+        lo += (-(lo - off)) % cols
+        hi -= (hi - off) % cols
+        if hi > lo:
+            seen += 1
+            got_t, ref_t = gacc[lo - acc.off:hi - acc.off], grad16[lo:hi]
+            assert_close_blockwise(got_t.reshape(-1, cols) if cols > 1 else got_t, ref_t.reshape(-1, cols) if cols > 1 else ref_t, 2e-2, name)
+    assert seen >= 24                               # two whole layers at least
 
 
 def test_layer_backward_accumulates_and_may_overwrite_dy():
