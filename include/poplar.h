@@ -133,6 +133,22 @@ int poplar_layer_bwd(poplar_ctx* ctx, int32_t B, const void* x_in, const void* d
                      const void* saved, void* dx, float* grads, int32_t accumulate,
                      void* workspace, int64_t workspace_bytes);
 
+/* poplar_layer_bwd for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments and results as poplar_layer_bwd without the
+ * workspace pair: the scratch the pass needs (poplar_layer_workspace_bytes)
+ * lives in an array inside the library's code object, poplar_static_scratch_bytes
+ * (64 MiB) on every GPU the library runs on, held until the process ends.  A
+ * batch whose scratch does not fit is refused with POPLAR_ERR_INVALID before
+ * anything is launched (GPT-2-small's layer fits at local batch 1).  The call
+ * allocates nothing, on the device or through any library.  All calls on one GPU
+ * share that GPU's array: calls that overlap there (two streams, two threads)
+ * race; calls in stream order on one stream do not.  Nothing needs clearing
+ * between calls: every part of the scratch is written before it is read. */
+int poplar_layer_bwd_static(poplar_ctx* ctx, int32_t B, const void* x_in, const void* dy, const void* params,
+                            const void* saved, void* dx, float* grads, int32_t accumulate);
+int poplar_static_scratch_bytes(int64_t* bytes);
+
 /* The projection GEMM the layer is built from, on its own (lowp inputs, float
  * accumulation): the three operand layouts of a Linear layer y = x W^T,
  *   POPLAR_GEMM_NT  C[M,N] = A[M,K] B[N,K]^T      (forward)

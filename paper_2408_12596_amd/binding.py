@@ -84,6 +84,7 @@ EXPORTS = [
     "poplar_bind_state", "poplar_step_workspace_bytes", "poplar_step_accounted_bytes", "poplar_profile_step",
     "poplar_accum_step", "poplar_search_mbs", "poplar_search_stage", "poplar_comm_model", "poplar_speed_curve", "poplar_allocate", "poplar_set_kernel_timing", "poplar_device_info",
     "poplar_gemm", "poplar_set_sampling", "poplar_set_mem_hooks", "poplar_step_forward_bytes",
+    "poplar_layer_bwd_static", "poplar_static_scratch_bytes",
 ]
 
 _lib = None
@@ -115,6 +116,8 @@ def _declare(L):
         "poplar_layer_workspace_bytes": [cfgp, i32, p64],
         "poplar_layer_fwd": [vp, i32, vp, vp, vp, vp, vp, i64],
         "poplar_layer_bwd": [vp, i32, vp, vp, vp, vp, vp, vp, i32, vp, i64],
+        "poplar_layer_bwd_static": [vp, i32, vp, vp, vp, vp, vp, vp, i32],
+        "poplar_static_scratch_bytes": [p64],
         "poplar_embed_fwd": [vp, i32, vp, vp, vp, vp],
         "poplar_embed_bwd": [vp, i32, vp, vp, vp, vp, i32],
         "poplar_head_workspace_bytes": [cfgp, i32, p64],
@@ -251,6 +254,12 @@ def step_accounted_bytes(cfg, stage, B, forward_only=False):
     return _bytes_query(lib().poplar_step_accounted_bytes, cfg, stage, B, int(forward_only))
 
 
+def static_scratch_bytes():
+    n = C.c_int64()
+    _check(lib().poplar_static_scratch_bytes(C.byref(n)))
+    return n.value
+
+
 def device_info():
     cu, khz, mem = C.c_int32(), C.c_int32(), C.c_int64()
     _check(lib().poplar_device_info(C.byref(cu), C.byref(khz), C.byref(mem)))
@@ -317,6 +326,10 @@ class Context:
     def layer_bwd(self, B, x_in, dy, params, saved, dx, grads, accumulate, workspace, workspace_bytes):
         _check(lib().poplar_layer_bwd(self._h, B, _ptr(x_in), _ptr(dy), _ptr(params), _ptr(saved), _ptr(dx), _ptr(grads),
                                       int(accumulate), _ptr(workspace), C.c_int64(workspace_bytes)))
+
+    def layer_bwd_static(self, B, x_in, dy, params, saved, dx, grads, accumulate):
+        _check(lib().poplar_layer_bwd_static(self._h, B, _ptr(x_in), _ptr(dy), _ptr(params), _ptr(saved), _ptr(dx), _ptr(grads),
+                                             int(accumulate)))
 
     def gemm(self, layout, M, N, K, A, lda, B, ldb, C, ldc, c_float=False, beta=0.0):
         _check(lib().poplar_gemm(self._h, layout, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, int(c_float), beta))

@@ -2,6 +2,7 @@
 // sharded optimizer and the single-rank share of the ZeRO collectives.
 // Host orchestration only: every arithmetic step is a kernel launch.
 #include "layer_plan.h"
+#include <mutex>
 
 int gemm(hipStream_t s, int dtype, const GemmArgs& a) {
   if (dtype == POPLAR_BF16) {
@@ -357,6 +358,55 @@ extern "C" int poplar_layer_bwd(poplar_ctx* ctx, int32_t B, const void* x_in, co
   if (workspace_bytes < bwd_plan(ctx->cfg, B).bytes)
     return poplar_fail(POPLAR_ERR_OOM, "layer backward workspace: have %lld bytes, need %lld", (long long)workspace_bytes, (long long)bwd_plan(ctx->cfg, B).bytes);
   return layer_bwd_impl(ctx, B, x_in, dy, params, saved, dx, grads, accumulate, workspace);
+}
+
+// ---- the same backward pass for callers that cannot allocate -----------------
+// Scratch of the no-allocation entry point: one array per GPU, loaded with the code object and held until the
+// process ends.  Host code never uses the array's name as an address; it asks the runtime for the device address
+// once per device (below) and passes that pointer on.
+#define POPLAR_STATIC_SCRATCH_BYTES (64ll << 20)
+static __device__ __align__(256) unsigned char scratch[POPLAR_STATIC_SCRATCH_BYTES];
+
+#define POPLAR_MAX_DEVICES 64
+static void* scratch_ptr[POPLAR_MAX_DEVICES];   // device address of `scratch` on each GPU, null until first asked for
+static std::mutex scratch_mutex;
+
+// Device address of this GPU's copy of the scratch array (the current device's: each GPU holds its own copy at
+// its own address).
+static int static_scratch(void** out) {
+  int dev = -1;
+  POPLAR_CHECK_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= POPLAR_MAX_DEVICES) return poplar_fail(POPLAR_ERR_INVALID, "device %d outside the %d the static scratch serves", dev, POPLAR_MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    POPLAR_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return poplar_fail(POPLAR_ERR_HIP, "hipGetSymbolAddress gave a null address for the static scratch");
+    scratch_ptr[dev] = p;
+  }
+  *out = scratch_ptr[dev];
+  return POPLAR_OK;
+}
+
+extern "C" int poplar_layer_bwd_static(poplar_ctx* ctx, int32_t B, const void* x_in, const void* dy, const void* params,
+                                       const void* saved, void* dx, float* grads, int32_t accumulate) {
+  POPLAR_TRY(check_ctx_batch(ctx, B));
+  if (!x_in || !dy || !params || !saved || !dx || !grads) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
+  const int64_t need = bwd_plan(ctx->cfg, B).bytes;
+  if (need > POPLAR_STATIC_SCRATCH_BYTES)
+    return poplar_fail(POPLAR_ERR_INVALID, "layer backward at batch %d needs %lld bytes of scratch, the static scratch holds %lld: use poplar_layer_bwd with a workspace",
+                       B, (long long)need, (long long)POPLAR_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  POPLAR_TRY(static_scratch(&ws));
+  // every region of the workspace is written by this pass before it is read (partial sums, staged gradients, the
+  // second halves of a cut contraction), so what an earlier call left behind needs no clearing
+  return layer_bwd_impl(ctx, B, x_in, dy, params, saved, dx, grads, accumulate, ws);
+}
+
+extern "C" int poplar_static_scratch_bytes(int64_t* bytes) {
+  if (!bytes) return poplar_fail(POPLAR_ERR_INVALID, "bytes is null");
+  *bytes = POPLAR_STATIC_SCRATCH_BYTES;
+  return POPLAR_OK;
 }
 
 extern "C" int poplar_gemm(poplar_ctx* ctx, int32_t layout, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
