@@ -1,12 +1,14 @@
-"""Benchmark: one rank's ZeRO-1 training step of the GPT-2-small-shaped workload
-on one MI355X, through libpoplar's C ABI.
+"""Benchmark: one rank's ZeRO training step on one MI355X, through libpoplar's C ABI.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--headline-only]
                     [--curve-report] [--layer-report] [--model-report] [--clock-report]
 
-A step is poplar_profile_step(stage 1, B): embedding, 12 layers forward, head
-and loss, backward, Adam on the rank's 1/8 shard, all on synthetic inputs that
-already sit in HBM.  Prints ONE JSON line.
+Headline: the Llama-7B-shaped configuration (32 layers, hidden 4096, SwiGLU 11008, seq 2048, vocab 32000) at
+ZeRO-3 on a 1/16 shard, the largest configuration that fits one GPU.  A step is poplar_profile_step(3, B):
+per-layer parameter gather, embedding, 32 layers forward, head and loss, backward with the local gradient reduce,
+Adam on the shard, all on synthetic inputs that already sit in HBM.  The ~1.3B configuration (ZeRO-2, 1/4 shard,
+with the odd batches and the 40 GiB allocation stress) and the GPT-2-small one (ZeRO-1, 1/8 shard) follow as
+sub-records with their own sweeps and rooflines.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -19,43 +21,53 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-WORKLOAD = dict(arch="gpt", L=12, H=768, nh=12, F=3072, S=1024, V=50257)
+WORKLOAD = dict(arch="gpt", L=12, H=768, nh=12, F=3072, S=1024, V=50257)   # the GPT-2-small sub-record (and the curve report)
 WORLD, RANK, STAGE = 8, 0, 1
 SWEEP = (1, 2, 4, 8, 16)
+HEADLINE = dict(arch="llama", L=32, H=4096, nh=32, F=11008, S=2048, V=32000)
+HEADLINE_WORLD, HEADLINE_STAGE, HEADLINE_SWEEP = 16, 3, (1, 2, 4)
+MID = dict(arch="gpt", L=24, H=2048, nh=16, F=8192, S=2048, V=50257)
+MID_WORLD, MID_STAGE, MID_SWEEP, MID_ODD = 4, 2, (1, 2, 4, 8), (3, 5, 7, 13)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# Bytes that cross the L2 per GEMM launch at local batch 16, averaged over the 111 launches of a step: rocprofv3
-# counters FETCH_SIZE x 2.0 (calibrated on kernels of known size) + WRITE_SIZE, summarised under profiles/.
-# Valid for the GEMM kernel as profiled; set to None when that kernel changes until the counters are taken again.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 296.2e6
+# Bytes that cross the L2 per GEMM launch of the headline step, averaged over its launches: rocprofv3 counters
+# FETCH_SIZE and WRITE_SIZE, scaled by the factors a copy of known size gives, summarised under profiles/.
+# None while no counters have been taken for the GEMM kernel as it stands.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = None
 # Events ride on the GEMM launches of every GEMM_EVENTS_EVERY-th timed step (the first, the sixth, ...): an attached
 # pair of events costs about 4.5 us per launch, 0.5 ms on a step's 111 launches, and the headline number should
 # carry as little of the instrument as the measurement allows.
 GEMM_EVENTS_EVERY = 5
 
 
-def cpu_baseline(model, flat, tok, tgt):
-    """The oracle as it stands, timed on this host: forward + backward of THREE samples
-    through all layers and the head, then Adam on the 1/8 shard (10-20 s of CPU work)."""
-    from oracle import optimizer as oopt
+def cpu_baseline(model):
+    """The oracle as it stands, timed on this host, on a bounded sample of the headline workload: forward +
+    backward of the headline's local batch (4 samples) through ONE decoder layer of the model's shape (fp64 NumPy;
+    10 TFLOP at the Llama-7B shape, 10-30 s).  The whole step is 32 such layers plus embedding, head and optimizer,
+    which a CPU run of bounded length cannot hold: samples/s is the layer time taken 32 times, the rest left out,
+    and says so."""
     from oracle import transformer as otr
+    from paper_2408_12596_amd import synth
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    f64 = flat.astype(np.float64)
+    H, S, L = model["H"], model["S"], model["L"]
+    spec = [(f"l0.{n}", s) for n, s in otr.layer_spec(model["arch"], H, model["F"])]
+    flat = synth.init_params(spec, seed=0).astype(np.float64)
+    p = {k[3:]: v for k, v in otr.unpack(flat, spec).items()}
+    n = max(HEADLINE_SWEEP)
+    x = synth.activations((n, S, H), seed=1).astype(np.float64)
+    dy = synth.activations((n, S, H), seed=2).astype(np.float64)
     t0 = time.perf_counter()
-    n = 3
-    loss, grad, _ = otr.model_fwd_bwd(model, f64, tok[:n], tgt[:n], 1.0 / (n * model["S"]))
-    off, ln, valid = oopt.shard_range(len(f64), WORLD, RANK)
-    sl = slice(off, off + valid)
-    z = np.zeros(valid)
-    oopt.adam_step(f64[sl], z, z, grad[sl], 1, 1e-3, 0.9, 0.999, 1e-8)
+    out, cache = otr.layer_fwd(model["arch"], p, x, model["nh"])
+    otr.layer_bwd(model["arch"], p, dy, cache, model["nh"])
     dt = time.perf_counter() - t0
-    return {"value": n / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
-            "sample": "3 samples (3072 tokens) through the full 12-layer model fwd+bwd + Adam on the 1/8 shard, fp64 NumPy",
-            "seconds": dt, "loss": float(loss)}
+    return {"value": n / (L * dt), "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n} samples ({n * S} tokens) through one decoder layer of the headline shape, forward + backward, fp64 NumPy: "
+                      f"{dt:.1f} s; value = {n} / ({L} layers x that), embedding, head, loss and optimizer left out",
+            "seconds": dt}
 
 
 def device_info(pb, torch):
@@ -210,13 +222,6 @@ def clock_report(pb, ctx, torch, shapes=((16384, 3072, 768), (8192, 2048, 8192))
     return rows
 
 
-MODEL_CONFIGS = {   # the larger configurations: (model, world, ZeRO stage, local batches)
-    # (after the sweep 1, 2, 4, 8: the odd batches of the allocation stress, whose token counts leave partial tiles)
-    "gpt-1.3B, ZeRO-2 on a 1/4 shard": (dict(arch="gpt", L=24, H=2048, nh=16, F=8192, S=2048, V=50257), 4, 2, (1, 2, 4, 8, 3, 5, 7, 13)),
-    "llama-7B, ZeRO-3 on a 1/16 shard": (dict(arch="llama", L=32, H=4096, nh=32, F=11008, S=2048, V=32000), 16, 3, (1, 2, 4)),
-}
-
-
 class DeviceRank:
     """One simulated rank whose state is drawn on the device (same recipe as synth.init_params: matrices N(0, 0.02),
     gains 1, biases 0; seed 0), for models too large to draw on the host in a bench run."""
@@ -227,6 +232,7 @@ class DeviceRank:
         self.P = pb.model_param_count(self.cfg)
         off, ln, valid = (0, self.P, self.P) if stage == 0 else pb.shard_range(self.P, world, 0)
         self.valid = valid
+        self.emb = next(o for name, shape, o in pb.model_spec(self.cfg) if name.startswith("l0."))   # elements before layer 0
         g = torch.Generator(device=dev).manual_seed(0)
         flat = torch.zeros(max(self.P, off + ln), device=dev)
         for name, shape, o in pb.model_spec(self.cfg):
@@ -246,53 +252,107 @@ class DeviceRank:
         ws = torch.empty(self.wsb + 256, dtype=torch.uint8, device=dev)
         loss = torch.zeros(1, device=dev)
         self.ctx = pb.Context(self.cfg, torch.cuda.current_stream().cuda_stream)
-        self.ctx.bind_state(params, master, m, v, grads, tok, max_b, ws, self.wsb, loss, own_shard=own, adam_t=1, lr=1e-4)
+        self.ctx.bind_state(params, master, m, v, grads, tok, max_b, ws, self.wsb, loss, own_shard=own, adam_t=1, lr=1e-6)   # the steps repeat one batch: a rate that leaves the loss near ln V
 
 
-def model_report(pb, torch):
-    """Whole steps of the larger configurations (1.3 B parameters at ZeRO-2, the Llama-7B shape at ZeRO-3) over their
-    local-batch sweeps, then the allocation stress on the 1.3 B model: odd local batches, Algorithm 1 under an
-    emulated cap of 40 GiB at stages 1-3, and Algorithm 2 over four devices whose step times are the measured curve
-    times 1, 1.5, 2 and 3, to a global batch of 64."""
-    out = {}
-    for name, (model, world, stage, batches) in MODEL_CONFIGS.items():
-        r = DeviceRank(pb, torch, model, world, stage, max(batches))
-        rows = []
-        for B in batches:
-            r.ctx.profile_step(stage, B)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            profs = [r.ctx.profile_step(stage, B) for _ in range(2)]
-            torch.cuda.synchronize()
-            dt = (time.perf_counter() - t0) / 2
-            p = profs[-1]
-            rows.append({"local_batch": B, "ms_per_step": dt * 1e3, "samples_per_s": B / dt, "tflops": p["flops"] / dt / 1e12,
-                         "frac_mfma_peak": p["flops"] / dt / 1e12 / PEAK_BF16_TFLOPS, "t_consumed_ms": p["t_consumed"] * 1e3,
-                         "t_adam_ms": p["t_adam"] * 1e3, "adam_gbs": 30.0 * r.valid / p["t_adam"] / 1e9,
-                         "t_reduce_ms": p["t_reduce_bwd"] * 1e3, "t_gather_ms": (p["t_gather_fwd"] + p["t_gather_bwd"]) * 1e3,
-                         "accounted_gib": p["accounted_bytes"] / 2**30, "loss": p["loss"]})
-        out[name] = {"params": r.P, "shard_elems": r.valid, "sweep": rows}
-        del r
-        torch.cuda.empty_cache()
-    model, world = MODEL_CONFIGS["gpt-1.3B, ZeRO-2 on a 1/4 shard"][0], 4
-    cap = 40 * 2**30
-    stress = {"cap_bytes": cap, "stages": {}}
+def rank_hbm_figures(P_model, emb, shard_valid, stage, p, tied):
+    """Bandwidth of the streaming kernels a whole step times on its own: Adam (30 B per element: g, p, m, v read,
+    p, m, v and the bf16 copy written), the ZeRO-3 parameter gathers (read 2 B, write 2 B per element; the forward
+    pass gathers every unit, the backward pass all but the embedding), the local gradient reduce (12 B per owned
+    element: the unit's gradient and the shard read, the shard written; a tied embedding matrix passes twice)."""
+    out = {"adam": {"achieved": 30.0 * shard_valid / p["t_adam"] / 1e9, "unit": "GB/s", "peak": PEAK_HBM_GBS, "bytes_per_elem": 30,
+                    "elems": shard_valid, "ms": p["t_adam"] * 1e3}}
+    if stage >= 3:
+        t = p["t_gather_fwd"] + p["t_gather_bwd"]
+        gathered = 2 * P_model + (emb if tied else -emb)   # a tied head gathers the embedding matrix again in both passes
+        out["gather"] = {"achieved": 4.0 * gathered / t / 1e9, "unit": "GB/s", "peak": PEAK_HBM_GBS, "bytes_per_elem": 4, "elems": gathered, "ms": t * 1e3}
+    if stage >= 2:
+        out["local_reduce"] = {"achieved": 12.0 * shard_valid / p["t_reduce_bwd"] / 1e9, "unit": "GB/s", "peak": PEAK_HBM_GBS,
+                               "bytes_per_elem": 12, "elems": shard_valid, "ms": p["t_reduce_bwd"] * 1e3}
+    for v in out.values():
+        v["frac"] = v["achieved"] / v["peak"]
+    return out
+
+
+def timed_steps(ctx, torch, stage, B, steps, warmup, timing=0, every=1):
+    """`steps` timed steps after `warmup` untimed ones, bracketed by synchronisations; the launches selected by
+    `timing` carry events in every `every`-th timed step (the first, the (every+1)-th, ...)."""
+    ctx.set_kernel_timing(0)
+    for _ in range(warmup):
+        ctx.profile_step(stage, B)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    profs = []
+    for i in range(steps):
+        ctx.set_kernel_timing(timing if i % every == 0 else 0)
+        profs.append(ctx.profile_step(stage, B))
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    ctx.set_kernel_timing(0)
+    return dt, profs
+
+
+def kernel_rooflines(ctx, torch, stage, B):
+    """GEMM and attention launches of two steps with events on the launches themselves."""
+    _, g = timed_steps(ctx, torch, stage, B, 2, 0, 1)
+    _, a = timed_steps(ctx, torch, stage, B, 2, 0, 2)
+    tg, ta = float(np.mean([p["t_gemm"] for p in g])), float(np.mean([p["t_attn"] for p in a]))
+    out = {"gemm": {"achieved": g[0]["gemm_flops"] / tg / 1e12, "launches_per_step": g[0]["n_gemm"], "ms_per_step": tg * 1e3},
+           "attention": {"achieved": a[0]["attn_flops"] / ta / 1e12, "launches_per_step": a[0]["n_attn"], "ms_per_step": ta * 1e3}}
+    for v in out.values():
+        v.update(unit="TFLOP/s", peak=PEAK_BF16_TFLOPS, frac=v["achieved"] / PEAK_BF16_TFLOPS)
+    return out
+
+
+def sweep_rows(r, torch, stage, batches, steps=3, warmup=1):
+    rows = []
+    for b in batches:
+        d, pr = timed_steps(r.ctx, torch, stage, b, steps, warmup)
+        rows.append({"local_batch": b, "samples_per_s": b / d, "ms_per_step": d * 1e3, "tflops": pr[0]["flops"] / d / 1e12,
+                     "frac_mfma_peak": pr[0]["flops"] / d / 1e12 / PEAK_BF16_TFLOPS,
+                     "t_consumed_ms": float(np.mean([p["t_consumed"] for p in pr])) * 1e3,
+                     "accounted_gib": pr[0]["accounted_bytes"] / 2**30})
+    return rows
+
+
+def sub_record(pb, torch, name, model, world, stage, batches, extra_batches=()):
+    """One configuration as a sub-record: its local-batch sweep, and at the top of the sweep the GEMM / attention
+    rooflines and the bandwidth of the optimizer and of the collectives' local share."""
+    r = DeviceRank(pb, torch, model, world, stage, max(batches + tuple(extra_batches)))
+    top = max(batches)
+    rec = {"workload": name, "zero_stage": stage, "world": world, "params": r.P, "shard_elems": r.valid,
+           "sweep": sweep_rows(r, torch, stage, batches)}
+    if extra_batches:
+        rec["odd_batches"] = sweep_rows(r, torch, stage, extra_batches)
+    _, pr = timed_steps(r.ctx, torch, stage, top, 2, 0)
+    rec["at_local_batch"] = top
+    rec["roofline"] = kernel_rooflines(r.ctx, torch, stage, top)
+    rec["hbm_kernels"] = rank_hbm_figures(r.P, r.emb, r.valid, stage, pr[-1], model["arch"] == "gpt")
+    del r
+    torch.cuda.empty_cache()
+    return rec
+
+
+def allocation_stress(pb, torch, model, world, cap, gbs=64):
+    """Algorithm 1 under an emulated cap at stages 1-3 (each sample the median of three warmed-up runs), then
+    Algorithm 2 for four devices whose step times are the measured curve times 1, 1.5, 2 and 3."""
+    stress = {"cap_bytes": cap, "gbs": gbs, "device_mix_time_factors": [1.0, 1.5, 2.0, 3.0], "stages": {}}
     for stage in (1, 2, 3):
         r = DeviceRank(pb, torch, model, world, stage, 16, cap_bytes=cap)
+        r.ctx.set_sampling(1, 3)
         mbs, samples = r.ctx.search_mbs(stage)
         pts = {p["batch"]: p["t_consumed"] for p in samples}
-        entry = {"mbs": mbs, "visited": sorted(pts), "t_consumed_ms": [pts[b] * 1e3 for b in sorted(pts)]}
         bs = sorted(pts)
+        entry = {"mbs": mbs, "visited": [p["batch"] for p in samples], "t_consumed_ms": [pts[b] * 1e3 for b in bs]}
         curves = [(bs, [pts[b] * k for b in bs], mbs) for k in (1.0, 1.5, 2.0, 3.0)]
-        cm = pb.comm_model(r.P, 4, stage, 2.0, 4.0, 7 * 153e9) if stage >= 2 else {"t_micro": 0.0}
-        al = pb.allocate(stage, 64, curves, cm["t_micro"])
-        entry["allocate_gbs64"] = {"t_comm_ms": cm["t_micro"] * 1e3, "gmbs": al["gmbs"], "b": al["b"], "gas": al["gas"], "lbs": al["lbs"],
-                                   "T_ms": al["T"] * 1e3}
+        cm = pb.comm_model(r.P, world, stage, 2.0, 4.0, 7 * 153e9) if stage >= 2 else {"t_micro": 0.0}
+        al = pb.allocate(stage, gbs, curves, cm["t_micro"])
+        entry["allocate"] = {"t_comm_ms": cm["t_micro"] * 1e3, "gmbs": al["gmbs"], "b": al["b"], "gas": al["gas"], "lbs": al["lbs"],
+                             "T_ms": al["T"] * 1e3, "T_steps_ms": al["T_steps"] * 1e3}
         stress["stages"][str(stage)] = entry
         del r
         torch.cuda.empty_cache()
-    out["allocation stress, gpt-1.3B, cap 40 GiB, devices 1 : 1.5 : 2 : 3, gbs 64"] = stress
-    return out
+    return stress
 
 
 def main():
@@ -300,15 +360,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--batch", type=int, default=16, help="local batch of the headline number")
+    ap.add_argument("--batch", type=int, default=max(HEADLINE_SWEEP), help="local batch of the headline number")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-sweep", action="store_true")
-    ap.add_argument("--curve-report", action="store_true", help="add the dense-sweep / spline / Algorithm 2 report to the line")
+    ap.add_argument("--headline-only", action="store_true", help="the headline configuration's timed steps and rooflines only "
+                    "(no sweeps, no sub-records, no CPU leg): the short run the rocprofv3 summaries under profiles/ are taken from")
+    ap.add_argument("--curve-report", action="store_true", help="add the dense-sweep / spline / Algorithm 2 report (GPT-2-small) to the line")
     ap.add_argument("--layer-report", action="store_true", help="add one-layer timings at the larger configurations' shapes")
     ap.add_argument("--clock-report", action="store_true", help="add GEMM rates on zero, one and normal operands with the shader "
                     "clock during each run")
-    ap.add_argument("--model-report", action="store_true", help="add whole-model steps of the 1.3B and Llama-7B-shaped configurations "
-                    "and the allocation stress under an emulated 40 GiB cap (a few minutes, about 120 GB of HBM)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one rank on ONE GPU (the ZeRO world is simulated by shard offsets); --gpus must be 1", file=sys.stderr)
@@ -316,106 +375,69 @@ def main():
 
     import torch
     from paper_2408_12596_amd import binding as pb
-    from paper_2408_12596_amd import synth
 
     pb.lib()   # fails loudly if the HIP library has not been built
-    dev = "cuda:0"
-    model = WORKLOAD
-    cfg = pb.make_cfg(**model, dtype="bf16", world=WORLD, rank=RANK, zero_stage=STAGE)
-    P = pb.model_param_count(cfg)
-    off, ln, valid = pb.shard_range(P, WORLD, RANK)
-    spec = [(name, shape) for name, shape, _ in pb.model_spec(cfg)]   # the library's own flat layout
-    assert sum(int(np.prod(s)) for _, s in spec) == P
-    flat = synth.init_params(spec, seed=0)
-    max_b = max(max(SWEEP), args.batch)
-    tok, tgt = synth.tokens(max_b, model["S"], model["V"], seed=0)
-    both = np.concatenate([tok, tgt[:, -1:]], axis=1).astype(np.int32)
-
-    params = torch.from_numpy(flat).to(dev).to(torch.bfloat16)
-    master = torch.from_numpy(flat[off:off + ln].copy()).to(dev)
-    m = torch.zeros(ln, device=dev)
-    v = torch.zeros(ln, device=dev)
-    grads = torch.zeros(P, device=dev)
-    tokens = torch.from_numpy(both).to(dev)
-    wsb = pb.step_workspace_bytes(cfg, STAGE, max_b)
-    ws = torch.empty(wsb + 256, dtype=torch.uint8, device=dev)
-    loss = torch.zeros(1, device=dev)
-    stream = torch.cuda.current_stream().cuda_stream
-    ctx = pb.Context(cfg, stream)
-    ctx.bind_state(params, master, m, v, grads, tokens, max_b, ws, wsb, loss, adam_t=1, lr=1e-4)
-
-    def run(B, steps, warmup, timing, every=1):
-        """`steps` timed steps after `warmup` untimed ones; the launches selected by `timing` carry events in every
-        `every`-th timed step (the first, the (every+1)-th, ...)."""
-        ctx.set_kernel_timing(0)
-        for _ in range(warmup):
-            ctx.profile_step(STAGE, B)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        profs = []
-        for i in range(steps):
-            ctx.set_kernel_timing(timing if i % every == 0 else 0)
-            profs.append(ctx.profile_step(STAGE, B))
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / steps
-        ctx.set_kernel_timing(0)
-        return dt, profs
-
+    model, world, stage = HEADLINE, HEADLINE_WORLD, HEADLINE_STAGE
     B = args.batch
-    # the timed steps carry events on the GEMM launches only (the roofline kernel); the attention kernels are timed in
-    # three more steps afterwards, outside the headline number
-    dt, profs = run(B, args.steps, args.warmup, 1, every=GEMM_EVENTS_EVERY)
+    r = DeviceRank(pb, torch, model, world, stage, max(max(HEADLINE_SWEEP), B))
+    ctx = r.ctx
+    # the timed steps carry events on the GEMM launches of every fifth step (the roofline kernel, measured live in the
+    # timed region on the launch stream); the attention kernels are timed in further steps afterwards
+    dt, profs = timed_steps(ctx, torch, stage, B, args.steps, args.warmup, 1, every=GEMM_EVENTS_EVERY)
     mean = lambda k: float(np.mean([p[k] for p in profs]))
     flops = profs[0]["flops"]
-    evp = profs[::GEMM_EVENTS_EVERY]   # the timed steps whose GEMM launches carried events
+    evp = profs[::GEMM_EVENTS_EVERY]
     t_gemm, f_gemm, n_gemm = float(np.mean([p["t_gemm"] for p in evp])), evp[0]["gemm_flops"], evp[0]["n_gemm"]
-    _, aprofs = run(B, 3, 0, 2)
-    t_attn, f_attn = float(np.mean([p["t_attn"] for p in aprofs])), aprofs[0]["attn_flops"]
     gemm_tflops = f_gemm / t_gemm / 1e12 if t_gemm > 0 else 0.0
-    adam_gbs = 30.0 * valid / mean("t_adam") / 1e9
+    _, aprofs = timed_steps(ctx, torch, stage, B, 2, 0, 2)
+    t_attn, f_attn = float(np.mean([p["t_attn"] for p in aprofs])), aprofs[0]["attn_flops"]
     out = {
         "metric": "samples/sec", "value": B / dt, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "GPT-2-small-shaped decoder (12 layers, hidden 768, 12 heads, MLP 3072 GeLU, seq 1024, vocab 50257), "
-                               "bf16 compute, fp32 master; ZeRO-1 step of rank 0 of a simulated world of 8: fwd + bwd + Adam on the 1/8 shard",
-                   "local_batch": B, "zero_stage": STAGE, "world": WORLD, "params": P, "shard_elems": valid},
+        "config": {"workload": "Llama-7B-shaped decoder (32 layers, hidden 4096, 32 heads of 128, SwiGLU MLP 11008, RMSNorm, RoPE, seq 2048, "
+                               "vocab 32000), bf16 compute, fp32 master; ZeRO-3 step of rank 0 of a simulated world of 16: per-layer parameter "
+                               "gather, fwd + bwd with the local gradient reduce, Adam on the 1/16 shard",
+                   "local_batch": B, "zero_stage": stage, "world": world, "params": r.P, "shard_elems": r.valid},
         "tflops": flops / dt / 1e12,
         "frac_mfma_peak_step": flops / dt / 1e12 / PEAK_BF16_TFLOPS,
         "samples_per_s_time_consumed": B / mean("t_consumed"),
-        "step_breakdown_ms": dict({k: mean(k) * 1e3 for k in ("t_fwd", "t_bwd", "t_adam")}, t_gemm=t_gemm * 1e3, t_attn=t_attn * 1e3),
+        "step_breakdown_ms": dict({k: mean(k) * 1e3 for k in ("t_fwd", "t_bwd", "t_adam", "t_gather_fwd", "t_gather_bwd", "t_reduce_bwd")},
+                                  t_gemm=t_gemm * 1e3, t_attn=t_attn * 1e3),
         "roofline": {"bound": "mfma", "kernel": "gemm_dtl_kernel (all GEMM launches of the step)", "achieved": gemm_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if B == 16 else None, "traffic_unit": "bytes per launch",
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if B == max(HEADLINE_SWEEP) else None, "traffic_unit": "bytes per launch",
                      "launches_per_step": n_gemm, "avg_launch_ms": t_gemm / max(n_gemm, 1) * 1e3,
-                     "timed_steps_with_events": len(evp),
-                     "flop_per_launch": f_gemm / max(n_gemm, 1)},
+                     "timed_steps_with_events": len(evp), "flop_per_launch": f_gemm / max(n_gemm, 1)},
         "attention": {"achieved": f_attn / t_attn / 1e12 if t_attn > 0 else 0.0, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS,
-                      "frac": (f_attn / t_attn / 1e12 / PEAK_BF16_TFLOPS) if t_attn > 0 else 0.0},
-        "adam": {"achieved": adam_gbs, "unit": "GB/s", "peak": PEAK_HBM_GBS, "frac": adam_gbs / PEAK_HBM_GBS,
-                 "bytes_per_elem": 30, "elems": valid},
-        "adam_4GB": adam_large(pb, ctx, torch),
+                      "frac": (f_attn / t_attn / 1e12 / PEAK_BF16_TFLOPS) if t_attn > 0 else 0.0, "head_dim": model["H"] // model["nh"],
+                      "ms_per_step": t_attn * 1e3},
+        "hbm_kernels": rank_hbm_figures(r.P, r.emb, r.valid, stage, {k: mean(k) for k in ("t_adam", "t_gather_fwd", "t_gather_bwd", "t_reduce_bwd")}, False),
         "loss": profs[-1]["loss"],
         "device": device_info(pb, torch),
     }
-    if not args.no_sweep:
-        sweep = []
-        for b in SWEEP:
-            d, pr = run(b, 3, 1, False)
-            sweep.append({"local_batch": b, "samples_per_s": b / d, "ms_per_step": d * 1e3, "tflops": pr[0]["flops"] / d / 1e12,
-                          "frac_mfma_peak": pr[0]["flops"] / d / 1e12 / PEAK_BF16_TFLOPS,
-                          "t_consumed_ms": float(np.mean([p["t_consumed"] for p in pr])) * 1e3})
-        out["sweep"] = sweep
-    if args.curve_report:
-        out["curve_report"] = curve_report(pb, ctx, P, max_b)
+    if not args.headline_only:
+        out["sweep"] = sweep_rows(r, torch, stage, HEADLINE_SWEEP)
+    del r, ctx
+    torch.cuda.empty_cache()
+    if not args.headline_only:
+        mid = sub_record(pb, torch, "~1.3B GPT decoder (24 layers, hidden 2048, 16 heads of 128, MLP 8192 GeLU, seq 2048, vocab 50257), "
+                         "ZeRO-2 on a 1/4 shard", MID, MID_WORLD, MID_STAGE, MID_SWEEP, MID_ODD)
+        mid["allocation_stress"] = allocation_stress(pb, torch, MID, MID_WORLD, 40 * 2**30)
+        small = sub_record(pb, torch, "GPT-2-small-shaped decoder (12 layers, hidden 768, 12 heads of 64, MLP 3072 GeLU, seq 1024, vocab 50257), "
+                           "ZeRO-1 on a 1/8 shard", WORKLOAD, WORLD, STAGE, SWEEP)
+        out["sub_records"] = {"gpt_1p3b_zero2": mid, "gpt2_small_zero1": small}
+    if args.curve_report or args.clock_report:
+        rs = DeviceRank(pb, torch, WORKLOAD, WORLD, STAGE, max(SWEEP))
+        if args.curve_report:
+            out["curve_report"] = curve_report(pb, rs.ctx, rs.P, max(SWEEP))
+        if args.clock_report:
+            out["clock_report"] = clock_report(pb, rs.ctx, torch)
+        del rs
     if args.layer_report:
         out["layer_report"] = layer_report(pb, torch)
-    if args.clock_report:
-        out["clock_report"] = clock_report(pb, ctx, torch)
-    if args.model_report:
-        out["model_report"] = model_report(pb, torch)
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(model, flat, tok, tgt)
+    if not args.no_cpu_baseline and not args.headline_only:
+        out["cpu_baseline"] = cpu_baseline(model)
     print(json.dumps(out))
 
 
