@@ -781,10 +781,67 @@ int swiglu_bwd(hipStream_t s, int dtype, int64_t T_, int F, const void* dg, cons
 
 // ---------------------------------------------------------------------------
 // RoPE in place on the q and k thirds of qkv [B*S, ld]: element i of a head is
-// paired with i + d/2 and rotated by pos * 10000^(-2i/d).  One thread owns one
-// (token, i) pair, evaluates the angle once in double and walks all heads.
-// sign = -1 applies the inverse rotation (the backward pass).
+// paired with i + d/2 and rotated by pos * 10000^(-2i/d).  sign = -1 applies the
+// inverse rotation (the backward pass).
+// rope_vec_kernel: one thread owns 16 bytes' worth of consecutive i of one token
+// (8 bfloat16 or 4 float), evaluates those angles once in double and walks all
+// heads of q and k with 16-byte accesses: eight (four) neighbouring lanes cover
+// the contiguous half of a head.  rope_kernel: one element pair per thread, for
+// head dims and alignments the vector form does not take.
 // ---------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) rope_vec_kernel(T* __restrict__ qkv, int64_t ld, int64_t tokens, int S, int nh, int d, float sign) {
+  constexpr int N = Vec<T>::N;
+  constexpr int HEADS = 8;       // heads per thread (blockIdx.y picks the run of heads), UNROLL of them in flight at a time
+  constexpr int UNROLL = 4;
+  const int half = d / 2, groups = half / N;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= tokens * groups) return;
+  const int64_t t = idx / groups;
+  const int i0 = (int)(idx % groups) * N;
+  const int pos = (int)(t % S);
+  float c[N], sn[N];
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    // angle and its reduction to [-pi, pi] in double (positions reach the thousands of radians), sine and cosine of
+    // the reduced angle in float
+    const double ang = (double)pos * exp(-9.210340371976184 * (2.0 * (double)(i0 + k) / (double)d));   // ln 10000
+    const double turns = rint(ang * 0.15915494309189535);
+    const float r = (float)fma(turns, -1.2246467991473532e-16 * 2.0, fma(turns, -6.283185307179586, ang));
+    float sf, cf;
+    sincosf(r, &sf, &cf);
+    c[k] = cf;
+    sn[k] = sign * sf;
+  }
+  const int heads = 2 * nh;   // q heads, then k heads: the two thirds are adjacent
+  const int h_begin = blockIdx.y * HEADS, h_end = min(heads, h_begin + HEADS);
+  T* row = qkv + t * ld + i0;
+  for (int h0 = h_begin; h0 < h_end; h0 += UNROLL) {
+    Vec<T> a[UNROLL], b[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+      if (h0 + u < h_end) {
+        a[u].load(row + (int64_t)(h0 + u) * d);
+        b[u].load(row + (int64_t)(h0 + u) * d + half);
+      }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+      if (h0 + u < h_end) {
+        float x1[N], x2[N], y1[N], y2[N];
+        a[u].unpack(x1);
+        b[u].unpack(x2);
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+          y1[k] = x1[k] * c[k] - x2[k] * sn[k];
+          y2[k] = x2[k] * c[k] + x1[k] * sn[k];
+        }
+        a[u].pack(y1);
+        b[u].pack(y2);
+        a[u].store(row + (int64_t)(h0 + u) * d);
+        b[u].store(row + (int64_t)(h0 + u) * d + half);
+      }
+  }
+}
 template <typename T>
 __global__ void rope_kernel(T* __restrict__ qkv, int64_t ld, int64_t tokens, int S, int nh, int d, float sign) {
   const int half = d / 2;
@@ -811,7 +868,15 @@ __global__ void rope_kernel(T* __restrict__ qkv, int64_t ld, int64_t tokens, int
 int rope_inplace(hipStream_t s, int dtype, int B, int S, int nh, int d, void* qkv, int64_t ld, float sign) {
   int64_t work = (int64_t)B * S * (d / 2);
   if (work == 0) return POPLAR_OK;
-  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, s, (T*)qkv, ld, (int64_t)B * S, S, nh, d, sign));
+  const int vec = dtype == POPLAR_BF16 ? 8 : 4;
+  // the vector form needs whole 16-byte groups in half a head and 16-byte aligned rows
+  if ((d / 2) % vec == 0 && ((uintptr_t)qkv & 15) == 0 && (ld * (int64_t)elt_size(dtype)) % 16 == 0) {
+    work /= vec;
+    const dim3 grid((unsigned)cdiv(work, 256), (unsigned)cdiv(2 * nh, 8));   // y: runs of eight heads
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(rope_vec_kernel<T>, grid, dim3(256), 0, s, (T*)qkv, ld, (int64_t)B * S, S, nh, d, sign));
+  } else {
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)cdiv(work, 256)), dim3(256), 0, s, (T*)qkv, ld, (int64_t)B * S, S, nh, d, sign));
+  }
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }
