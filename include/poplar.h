@@ -75,6 +75,10 @@ typedef struct poplar_model_cfg {
   int32_t checkpoint;  /* 1: whole steps keep one activation stash instead of L and run every layer's forward pass
                           again inside the backward pass (a memory-for-compute knob next to the ZeRO stage: Section
                           "Heterogeneity Aware" only asks for the largest batch that fits) */
+  int32_t deterministic; /* 1: every sum is taken in a fixed order, so that a step repeated on the same inputs gives the
+                          same bits: the embedding-matrix gradient is summed token by token in sequence order instead
+                          of with float atomics, and no GEMM splits its contraction over atomics (splits into halves
+                          with a separate sum are kept).  Slower for small batches; off by default */
 } poplar_model_cfg;
 
 typedef struct poplar_ctx poplar_ctx;
@@ -171,7 +175,8 @@ int poplar_gemm(poplar_ctx* ctx, int32_t layout, int64_t M, int64_t N, int64_t K
  * NULL for Llama. */
 int poplar_embed_fwd(poplar_ctx* ctx, int32_t B, const int32_t* tokens, const void* wte, const void* wpe, void* x);
 
-/* dwte[tok[b,s],:] += dx[b,s,:] (float atomics; summation order not fixed),
+/* dwte[tok[b,s],:] += dx[b,s,:] (float atomics, summation order not fixed; in sequence order when the context
+ * was created with cfg.deterministic = 1),
  * dwpe[s,:] (+)= sum_b dx[b,s,:].  With accumulate = 0 dwpe is overwritten but
  * dwte is still added to (the tied LM head wrote it first); zero it yourself
  * when there is no tied head. */

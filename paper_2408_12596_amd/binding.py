@@ -34,7 +34,7 @@ class ModelCfg(C.Structure):
     _fields_ = [("arch", C.c_int32), ("n_layer", C.c_int32), ("hidden", C.c_int32), ("n_head", C.c_int32),
                 ("ffn", C.c_int32), ("seq", C.c_int32), ("vocab", C.c_int32), ("dtype", C.c_int32),
                 ("world", C.c_int32), ("rank", C.c_int32), ("zero_stage", C.c_int32), ("causal", C.c_int32),
-                ("cap_bytes", C.c_int64), ("checkpoint", C.c_int32)]
+                ("cap_bytes", C.c_int64), ("checkpoint", C.c_int32), ("deterministic", C.c_int32)]
 
 
 class State(C.Structure):
@@ -166,9 +166,9 @@ def _ptr(t):
 
 
 def make_cfg(arch="gpt", L=1, H=256, nh=4, F=1024, S=128, V=1, dtype="bf16", world=1, rank=0, zero_stage=1,
-             causal=True, cap_bytes=0, checkpoint=False):
+             causal=True, cap_bytes=0, checkpoint=False, deterministic=False):
     return ModelCfg(ARCH_GPT if arch == "gpt" else ARCH_LLAMA, L, H, nh, F, S, V, BF16 if dtype == "bf16" else F32,
-                    world, rank, zero_stage, int(causal), cap_bytes, int(checkpoint))
+                    world, rank, zero_stage, int(causal), cap_bytes, int(checkpoint), int(deterministic))
 
 
 # ---- host-only queries --------------------------------------------------------

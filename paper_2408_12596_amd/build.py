@@ -63,5 +63,28 @@ def build(force=False, verbose=False):
     return LIB
 
 
+HOST_ONLY_SOURCES = ["layout.cpp", "analysis.cpp"]
+HOST_CHECK = os.path.join(OBJ, "host_check_san")
+
+
+def build_host_sanitized():
+    """The host-only part of the library (flat layout, shard arithmetic, speed curves, Algorithm 2, communication
+    model) with its command-line driver csrc/host_check_main.cc, compiled for the host alone with AddressSanitizer and
+    UndefinedBehaviorSanitizer (any finding aborts).  Returns the executable's path; tests/test_host_library.py runs it
+    on the cases it gives the library and compares the outputs."""
+    os.makedirs(OBJ, exist_ok=True)
+    cmd = [_hipcc(), "-O1", "-g", "-std=c++17", "--offload-host-only", "-Xarch_host", "-fsanitize=address", "-Xarch_host",
+           "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=all", "-ffp-contract=off", "-x", "hip"]
+    cmd += [os.path.join(CSRC, f) for f in HOST_ONLY_SOURCES]
+    cmd += ["-x", "c++", os.path.join(CSRC, "host_check_main.cc"), "-o", HOST_CHECK]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("sanitizer build of the host code failed:\n" + r.stderr)
+    return HOST_CHECK
+
+
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv, verbose=True))
+    if "--host-sanitize" in sys.argv:
+        print(build_host_sanitized())
+    else:
+        print(build(force="--force" in sys.argv, verbose=True))

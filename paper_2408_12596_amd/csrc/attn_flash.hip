@@ -115,6 +115,12 @@ struct Rows64 {
   // complete either: the caller waits with fa_wait_lds() before it uses the fragment.
   // The chunk index (0 .. 3, a constant wherever this is called) goes into the instruction's offset field: a chunk
   // is 16 rows further on, which leaves the swizzle of a row unchanged.
+  // INVARIANT for every caller (the compiler cannot check it): (1) a fragment read here is used only after a
+  // fa_wait_lds() that follows the read in program order; (2) every fragment that is read IS used after that wait,
+  // by an MFMA: a read whose result is dead would leave its destination registers free for the compiler to reuse while
+  // the data is still on its way, and the late return would overwrite whatever was put there (this happened once in
+  // the GEMM kernel, as a memory fault).  The three kernels below keep to it by prefetching the next group of
+  // fragments only under the same condition under which that group's MFMAs run (c + 1 < 4 / PF; u == 0).
   template <int J>
   __device__ static bf16x8 frag_tr_at(uint32_t a0, uint32_t a1) {
     intx2 lo, hi;

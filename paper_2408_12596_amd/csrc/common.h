@@ -87,6 +87,7 @@ struct GemmArgs {
   // TN with a float C and nothing fused (a weight gradient), or null: room for M * ldc + M floats.  With it the
   // direct-to-LDS kernel may cut K in two: the second half's sums go here and are added to C (and to a_rowsum) afterwards.
   float* k_partial = nullptr;
+  int no_atomics = 0;     // 1: the contraction is never split over float atomics (sums in a fixed order)
   int a_k_pad_zero;       // NN only: A's rows hold zeros from column K up to K rounded up to 64 (lda covers them)
   // Optional: events that receive the start and the end of the kernel itself (hipExtLaunchKernelGGL), without the
   // barrier packets a recorded event puts between kernels.  Honoured by the direct-to-LDS kernel only.
@@ -135,7 +136,9 @@ int swiglu_fwd(hipStream_t s, int dtype, int64_t T, int F, const void* hgu, void
 int swiglu_bwd(hipStream_t s, int dtype, int64_t T, int F, const void* dg, const void* hgu, void* dhgu);
 int rope_inplace(hipStream_t s, int dtype, int B, int S, int nh, int d, void* qkv, int64_t ld, float sign);
 int embed_fwd(hipStream_t s, int dtype, int B, int S, int H, int V, const int32_t* tok, int64_t tok_ld, const void* wte, const void* wpe, void* x);
-int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, int V, const int32_t* tok, int64_t tok_ld, const void* dx, float* dwte, float* dwpe, int accumulate);
+// ordered = 1: the embedding-matrix rows are summed token by token in sequence order (no atomics)
+int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, int V, const int32_t* tok, int64_t tok_ld, const void* dx, float* dwte, float* dwpe, int accumulate,
+              int ordered = 0);
 int xent_fwd_bwd(hipStream_t s, int dtype, int64_t T, int V, int64_t ld, void* logits, const int32_t* targets, int64_t tgt_ld, int S,
                  float loss_scale, float* loss, float* row_loss);
 int adam_shard(hipStream_t s, int lowp_dtype, float* p, float* m, float* v, const float* g, void* p_lowp, int64_t n,

@@ -934,6 +934,56 @@ __global__ void embed_bwd_wte_kernel(const int32_t* __restrict__ tok, int64_t to
     if (id >= 0 && id < V) unsafeAtomicAdd(dwte + (int64_t)id * H + c, to_float<T>(dx[i]));
   }
 }
+// The same sums in a fixed order, without atomics.  One block per token t: if an earlier token carries the same
+// id the block has nothing to do; otherwise it owns row id of dwte and adds to it the rows of dx of t and of every
+// later token with that id, in sequence order.  Tokens are compared 256 at a time (one per thread, a ballot per
+// wavefront); each thread keeps its columns of the sum in registers and adds them to dwte once at the end.
+template <typename T, int COLS>
+__global__ void __launch_bounds__(256) embed_bwd_wte_ordered_kernel(const int32_t* __restrict__ tok, int64_t tok_ld, const T* __restrict__ dx,
+                                                                    float* __restrict__ dwte, int64_t tokens, int S, int H, int V) {
+  __shared__ unsigned long long hits[4];
+  const int64_t t0 = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6;
+  const int id = tok[(t0 / S) * tok_ld + (t0 % S)];
+  if (id < 0 || id >= V) return;
+  auto scan = [&](int64_t base, int64_t end) {   // hits[w] <- which of tokens base + 64 w .. + 63 (below end) carry `id`
+    const int64_t t = base + tid;
+    const bool same = t < end && tok[(t / S) * tok_ld + (t % S)] == id;
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(same);
+    __syncthreads();                               // the previous chunk's masks have been read
+    if ((tid & 63) == 0) hits[wave] = m;
+    __syncthreads();
+  };
+  for (int64_t base = 0; base < t0; base += 256) {  // an earlier token with this id owns the row
+    scan(base, t0);
+    if (hits[0] | hits[1] | hits[2] | hits[3]) return;
+  }
+  float acc[COLS];
+#pragma unroll
+  for (int k = 0; k < COLS; ++k) acc[k] = 0.f;
+  for (int64_t first = t0; first < tokens; first += 256) {   // thread i looks at token first + i; the first chunk holds t0 itself
+    scan(first, tokens);
+    for (int w = 0; w < 4; ++w) {
+      unsigned long long m = hits[w];
+      while (m) {
+        const int bit = __builtin_ctzll(m);
+        m &= m - 1;
+        const T* row = dx + (first + w * 64 + bit) * H;
+#pragma unroll
+        for (int k = 0; k < COLS; ++k) {
+          const int c = tid + k * 256;
+          if (c < H) acc[k] += to_float<T>(row[c]);
+        }
+      }
+    }
+  }
+  float* out = dwte + (int64_t)id * H;
+#pragma unroll
+  for (int k = 0; k < COLS; ++k) {
+    const int c = tid + k * 256;
+    if (c < H) out[c] += acc[k];
+  }
+}
 template <typename T>
 __global__ void embed_bwd_wpe_kernel(const T* __restrict__ dx, float* __restrict__ dwpe, int B, int S, int H, int accumulate) {
   constexpr int VN = Vec<T>::N;
@@ -955,11 +1005,31 @@ __global__ void embed_bwd_wpe_kernel(const T* __restrict__ dx, float* __restrict
 #pragma unroll
   for (int k = 0; k < VN; ++k) o[k] = accumulate ? o[k] + acc[k] : acc[k];
 }
-int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, int V, const int32_t* tok, int64_t tok_ld, const void* dx, float* dwte, float* dwpe, int accumulate) {
+template <typename T>
+static int embed_bwd_wte_ordered(hipStream_t s, const int32_t* tok, int64_t tok_ld, const T* dx, float* dwte, int64_t tokens, int S, int H, int V) {
+  if (H > 32 * 256) return poplar_fail(POPLAR_ERR_UNIMPLEMENTED, "ordered embedding gradient: hidden %d above %d", H, 32 * 256);
+  if (tokens > 0x7fffffff) return poplar_fail(POPLAR_ERR_INVALID, "too many tokens for one launch");
+  const dim3 grid((unsigned)tokens), block(256);
+#define ORDERED(C) hipLaunchKernelGGL((embed_bwd_wte_ordered_kernel<T, C>), grid, block, 0, s, tok, tok_ld, dx, dwte, tokens, S, H, V)
+  const int cols = (H + 255) / 256;
+  if (cols <= 1) ORDERED(1);
+  else if (cols <= 2) ORDERED(2);
+  else if (cols <= 4) ORDERED(4);
+  else if (cols <= 8) ORDERED(8);
+  else if (cols <= 16) ORDERED(16);
+  else ORDERED(32);
+#undef ORDERED
+  POPLAR_LAUNCH_CHECK();
+  return POPLAR_OK;
+}
+
+int embed_bwd(hipStream_t s, int dtype, int B, int S, int H, int V, const int32_t* tok, int64_t tok_ld, const void* dx, float* dwte, float* dwpe, int accumulate,
+              int ordered) {
   int64_t tokens = (int64_t)B * S;
   if (tokens == 0) return POPLAR_OK;
   DISPATCH_DTYPE(dtype, {
-    hipLaunchKernelGGL(embed_bwd_wte_kernel<T>, dim3(grid_for(tokens * H, 256)), dim3(256), 0, s, tok, tok_ld, (const T*)dx, dwte, tokens, S, H, V);
+    if (ordered) POPLAR_TRY(embed_bwd_wte_ordered<T>(s, tok, tok_ld, (const T*)dx, dwte, tokens, S, H, V));
+    else hipLaunchKernelGGL(embed_bwd_wte_kernel<T>, dim3(grid_for(tokens * H, 256)), dim3(256), 0, s, tok, tok_ld, (const T*)dx, dwte, tokens, S, H, V);
     POPLAR_LAUNCH_CHECK();
     if (dwpe) {
       hipLaunchKernelGGL(embed_bwd_wpe_kernel<T>, dim3((unsigned)cdiv((int64_t)S * H / Vec<T>::N, 256)), dim3(256), 0, s, (const T*)dx, dwpe, B, S, H, accumulate);

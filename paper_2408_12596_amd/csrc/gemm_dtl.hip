@@ -99,6 +99,10 @@ struct StridedImage {
     return (uint32_t)(((int64_t)krow * ld + r0 + (col >= R * 2 ? 0 : col / 2)) * 2);
   }
   __device__ static uint32_t k_step(int64_t ld) { return (uint32_t)(DTL_BK * ld * 2); }
+  // INVARIANT for the caller: a fragment returned here may feed an MFMA only after an s_waitcnt lgkmcnt(0) that
+  // follows this call (slice() begins with one), and a fragment that is read but never used must be named as an input
+  // of an empty asm statement after such a wait (the kernel does so for the last K step's reads), or the compiler may
+  // hand its registers to something else while the read is still in flight.
   // The transposing reads are written as assembly: the compiler orders the builtin form after every
   // global -> LDS load in flight (it cannot tell the stage being filled from the one being read), which
   // would serialise the pipeline.  The price: the compiler does not see these reads complete either, so
@@ -484,6 +488,10 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
         // 16 lanes: lane j16 addresses image row (j16 >> 2) of a 4 x 16 block at element 4 (j16 & 3) and receives element
         // j16 of the four rows, i.e. C[row mb*16 + j16][four consecutive columns]; two reads give eight columns.
         // All reads of a 16-row block are issued before the one wait.
+        // INVARIANT (the compiler does not see these reads complete): every register pair written by issue() is
+        // named as an in/out operand of the empty statement after the matching s_waitcnt below, which both keeps the
+        // pair reserved until the data has landed and orders every use behind the wait; issue(mb + 1) runs only when
+        // block mb + 1 exists, so no read is left without such a statement.
         const int64_t mrow = m0 + wm + (r * IC * 32) + j16;
         bf16* orow = outp + mrow * ldo + (n0 + wn + grp * 8);
         constexpr int NMB = IC * 2;
@@ -717,7 +725,7 @@ static double dtl_plan(const GemmArgs* a, int n, bool plain, int* pick_out, int*
     for (int i = 0; i < n; ++i) t += cdiv(a[i].M, tc.bm) * cdiv(a[i].N, tc.bn);
     static const int cand[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16};
     for (int sp : cand) {
-      if (sp > 1 && (!plain || ksteps / sp < 8)) break;
+      if (sp > 1 && (!plain || ksteps / sp < 8 || a[0].no_atomics)) break;
       const double rounds = ceil((double)(t * sp) / tc.slots);
       // two 128x128 blocks that really share a CU slow each other down a little more
       // (measured; likewise the 64x64 blocks as a CU fills up: four to a CU they cost almost twice the lone block's

@@ -344,7 +344,7 @@ int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a) {
   // split K only for plain float-output GEMMs (weight gradients) that leave CUs idle
   int splits = 1;
   const bool plain = a.c_float && !a.bias && !a.residual && a.act == ACT_NONE;
-  if (plain && tiles < 384) {
+  if (plain && tiles < 384 && !a.no_atomics) {
     splits = (int)std::min<int64_t>(cdiv(768, tiles), cdiv(a.K, 512));
     if (splits < 1) splits = 1;
   }

@@ -37,7 +37,9 @@ struct LaunchTimer {
     return POPLAR_OK;
   }
 };
-static int gemm(poplar_ctx* ctx, const GemmArgs& a) {
+static int gemm(poplar_ctx* ctx, const GemmArgs& a0) {
+  GemmArgs a = a0;
+  a.no_atomics = ctx->cfg.deterministic;
   LaunchTimer t{ctx};
   POPLAR_TRY(t.begin(KIND_GEMM, 2.0 * (double)a.M * (double)a.N * (double)a.K));
   if (ctx->cfg.dtype == POPLAR_BF16) {
@@ -63,7 +65,7 @@ static int gemm_group(poplar_ctx* ctx, const GemmArgs* a, int n) {
     LaunchTimer t{ctx};
     POPLAR_TRY(t.begin(KIND_GEMM, flops));
     GemmArgs b[4];
-    for (int i = 0; i < n; ++i) b[i] = a[i];
+    for (int i = 0; i < n; ++i) { b[i] = a[i]; b[i].no_atomics = ctx->cfg.deterministic; }
     b[0].ev_start = t.tl.a; b[0].ev_stop = t.tl.b;
     const int r = gemm_bf16_dtl_group(ctx->stream, b, n);
     if (r == POPLAR_OK) return t.done();
@@ -436,7 +438,8 @@ extern "C" int poplar_embed_bwd(poplar_ctx* ctx, int32_t B, const int32_t* token
   const poplar_model_cfg& c = ctx->cfg;
   if (!tokens || !dx || !dwte) return poplar_fail(POPLAR_ERR_INVALID, "null device pointer");
   if (c.arch == POPLAR_ARCH_GPT && !dwpe) return poplar_fail(POPLAR_ERR_INVALID, "GPT needs dwpe");
-  return embed_bwd(ctx->stream, c.dtype, B, c.seq, c.hidden, c.vocab, tokens, c.seq, dx, dwte, c.arch == POPLAR_ARCH_GPT ? dwpe : nullptr, accumulate);
+  return embed_bwd(ctx->stream, c.dtype, B, c.seq, c.hidden, c.vocab, tokens, c.seq, dx, dwte, c.arch == POPLAR_ARCH_GPT ? dwpe : nullptr, accumulate,
+                   c.deterministic);
 }
 
 // ---- head + loss -----------------------------------------------------------

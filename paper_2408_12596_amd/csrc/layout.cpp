@@ -32,6 +32,7 @@ int validate_cfg(const poplar_model_cfg* c) {
   if (c->zero_stage < 0 || c->zero_stage > 3) return poplar_fail(POPLAR_ERR_INVALID, "zero_stage %d outside 0..3", c->zero_stage);
   if (c->cap_bytes < 0) return poplar_fail(POPLAR_ERR_INVALID, "negative cap_bytes");
   if (c->checkpoint != 0 && c->checkpoint != 1) return poplar_fail(POPLAR_ERR_INVALID, "checkpoint must be 0 or 1, got %d", c->checkpoint);
+  if (c->deterministic != 0 && c->deterministic != 1) return poplar_fail(POPLAR_ERR_INVALID, "deterministic must be 0 or 1, got %d", c->deterministic);
   return POPLAR_OK;
 }
 

@@ -359,7 +359,7 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
       // stage 0/1 GPT: the head already wrote dwte, the embedding adds to it; everywhere else start from zero
       // (an accumulating pass at stage 0/1 adds to the earlier micro-steps' gradient instead)
       if (stage >= 2 || (llama && !acc)) POPLAR_TRY(fill_zero(s, ge, (int64_t)c.vocab * H * 4));
-      POPLAR_TRY(embed_bwd(s, c.dtype, B, c.seq, (int)H, c.vocab, tokens, tok_ld, dx_cur, ge, llama ? nullptr : ge + mo.wpe, stage < 2 ? acc : 0));
+      POPLAR_TRY(embed_bwd(s, c.dtype, B, c.seq, (int)H, c.vocab, tokens, tok_ld, dx_cur, ge, llama ? nullptr : ge + mo.wpe, stage < 2 ? acc : 0, c.deterministic));
       POPLAR_TRY(reduce_unit(ge, 0, u.emb_hi));
     }
     POPLAR_TRY(ev.mark(&e_bwd_end));

@@ -26,9 +26,10 @@ MODELS = {
 class Rank:
     """Device state of one simulated rank, built from the same flat fp32 vector the oracle sees."""
 
-    def __init__(self, model, dtype, stage, world, rank, max_batch, cap_bytes=0, seed=0):
+    def __init__(self, model, dtype, stage, world, rank, max_batch, cap_bytes=0, seed=0, deterministic=False):
         self.model, self.dtype, self.stage = model, dtype, stage
-        self.cfg = pb.make_cfg(**model, dtype=dtype, world=world, rank=rank, zero_stage=stage, cap_bytes=cap_bytes)
+        self.cfg = pb.make_cfg(**model, dtype=dtype, world=world, rank=rank, zero_stage=stage, cap_bytes=cap_bytes,
+                               deterministic=deterministic)
         self.ctx = pb.Context(self.cfg)
         self.spec = otr.model_spec(model)
         self.flat = synth.init_params(self.spec, seed=seed, jitter=True)
@@ -235,6 +236,38 @@ def test_accum_step_of_one_micro_batch_is_profile_step():
     assert torch.equal(a.master, b.master) and torch.equal(a.m, b.m) and torch.equal(a.v, b.v)
     assert torch.equal(a.grads[V * H:], b.grads[V * H:])
     assert rel_l2(to_np(a.grads[:V * H]), to_np(b.grads[:V * H])) <= 1e-6
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("arch", ["gpt", "llama"])
+def test_deterministic_step_repeats_bit_for_bit(arch, dtype):
+    """cfg.deterministic: the embedding-matrix gradient is summed in sequence order and no contraction is split over
+    atomics, so the whole gradient, wte included, repeats bit for bit, equals the accumulation path's, and is still
+    the oracle's gradient."""
+    model, B = dict(MODELS[arch], V=37), 4        # a small vocabulary: every id occurs many times
+    a = Rank(model, dtype, 0, 1, 0, max_batch=B, deterministic=True)
+    b = Rank(model, dtype, 0, 1, 0, max_batch=B, deterministic=True)
+    c = Rank(model, dtype, 0, 1, 0, max_batch=B, deterministic=True)
+    pa = a.ctx.profile_step(0, B)
+    pb_ = b.ctx.profile_step(0, B)
+    c.ctx.accum_step(0, [B], B)
+    sync()
+    assert torch.equal(a.grads, b.grads) and torch.equal(a.grads, c.grads) and torch.equal(a.master, b.master)
+    assert pa["loss"] == pb_["loss"]
+    loss, grad, _ = otr.model_fwd_bwd(model, quantize(a.flat, dtype), a.tok[:B], a.tgt[:B], 1.0 / (B * model["S"]))
+    table, _ = otr.offsets(a.spec)
+    got = to_np(a.grads)
+    for name, (off, shape) in table.items():
+        k = int(np.prod(shape))
+        assert rel_l2(got[off:off + k], grad[off:off + k]) <= TOL[dtype], name
+    # ids outside the vocabulary embed as zero and get no gradient, in this path too
+    d = Rank(model, dtype, 0, 1, 0, max_batch=B, deterministic=True)
+    bad = d.tokens.clone()
+    bad[0, 3], bad[1, 5] = -7, model["V"] + 2
+    d.ctx.bind_state(d.params, d.master, d.m, d.v, d.grads, bad, B, d.ws, d.wsb, d.loss, adam_t=1)
+    pd = d.ctx.profile_step(0, B)
+    sync()
+    assert np.isfinite(pd["loss"]) and torch.isfinite(d.grads).all()
 
 
 def test_allocation_is_executable_on_two_unequal_devices():

@@ -286,3 +286,73 @@ def test_state_sized_for_a_shard_cannot_run_stage_0():
         ctx.bind_state(fake, fake, fake, fake, fake, fake, 4, fake, 0, fake, own_shard=fake, master_len=ln, grads_len=P, own_len=0)
     with pytest.raises(pb.PoplarError):
         ctx.set_sampling(0, 0)
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers():
+    """layout.cpp and analysis.cpp rebuilt for the host with ASan + UBSan (any finding aborts the driver) and fed the
+    kinds of input the library gets, valid and invalid: the sanitized build must agree with the library to the last bit."""
+    import subprocess
+    from paper_2408_12596_amd import build as pbuild
+    exe = pbuild.build_host_sanitized()
+    rng = np.random.default_rng(99)
+    lines, expect = [], []
+
+    def curve_text(c):
+        return f"{c[2]} {len(c[0])} " + " ".join(f"{b} {t!r}" for b, t in zip(c[0], c[1]))
+    for P, N, r in [(10, 4, 3), (0, 3, 0), (124439808, 8, 7), (10, 4, 4)] + [(int(rng.integers(0, 10**12)), int(rng.integers(1, 65)), 0) for _ in range(30)]:
+        lines.append(f"shard {P} {N} {r}")
+        try:
+            expect.append("0 " + " ".join(str(v) for v in pb.shard_range(P, N, r)))
+        except pb.PoplarError as e:
+            expect.append(f"{e.status} 0 0 0")
+    for cfg in CFGS:
+        c = pb.make_cfg(**cfg)
+        lines.append(f"count {c.arch} {c.n_layer} {c.hidden} {c.n_head} {c.ffn} {c.seq} {c.vocab} {c.dtype}")
+        expect.append(f"0 {pb.model_param_count(c)} {pb.layer_param_count(c)}")
+        for layer, tid in ((0, pb.T_WQKV), (cfg["L"] - 1, pb.T_W2), (0, pb.T_GF), (cfg["L"], pb.T_G1), (0, pb.T_BQKV)):
+            lines.append(f"offset {c.arch} {c.n_layer} {c.hidden} {c.n_head} {c.ffn} {c.seq} {c.vocab} {c.dtype} {layer} {tid}")
+            try:
+                expect.append("0 " + " ".join(str(v) for v in pb.param_offset(c, layer, tid)))
+            except pb.PoplarError as e:
+                expect.append(f"{e.status} 0 0 0")
+    for _ in range(40):
+        P, world, stage = int(rng.integers(0, 10**10)), int(rng.integers(1, 65)), int(rng.integers(0, 4))
+        bw = float(rng.uniform(1e9, 2e12))
+        lines.append(f"comm {P} {world} {stage} 2.0 4.0 {bw!r}")
+        m = pb.comm_model(P, world, stage, 2.0, 4.0, bw)
+        expect.append("0 " + " ".join(repr(float(m[k])) for k in ("micro_bytes", "step_bytes", "total_micro_elements", "t_micro", "t_step")))
+    import json
+    with open(os.path.join(ROOT, "tests", "golden", "alloc_dip_cases.json")) as f:
+        dips = [(c["batches"], c["times"], c["mbs"]) for c in json.load(f)["cases"]]
+    for c in dips + [random_curve(rng) for _ in range(60)] + [([4], [2.0], 6)]:
+        lines.append("curve " + curve_text(c))
+        expect.append("0 " + " ".join(repr(float(v)) for v in pb.speed_curve(*c)))
+    for stage in range(4):
+        for _ in range(40):
+            n = int(rng.integers(1, 7))
+            curves = [random_curve(rng) for _ in range(n)] if rng.random() < 0.9 else [dips[0], dips[1]]
+            n = len(curves)
+            gbs, tc = int(rng.integers(1, 400)), float(rng.choice([0.0, 0.01, 0.5, 20.0]))
+            lines.append(f"alloc {stage} {gbs} {tc!r} 0.95 {n} " + " ".join(curve_text(c) for c in curves))
+            a = pb.allocate(stage, gbs, curves, tc)
+            expect.append("0 " + " ".join(f"{a['gmbs'][i]} {a['b'][i]} {a['gas'][i]} {a['lbs'][i]}" for i in range(n))
+                          + f" {a['T']!r} {a['t']!r} {a['T_steps']!r}")
+    lines.append("alloc 1 8 0.0 0.95 1 0 0")                 # no device can run a sample
+    lines.append("alloc 7 8 0.0 0.95 1 2 2 1 1.0 2 1.5")     # no such stage
+    lines.append("curve 3 2 1 0.0 2 1.0")                    # a zero time
+    expect += [None, None, None]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=1", UBSAN_OPTIONS="halt_on_error=1")
+    env.pop("LD_PRELOAD", None)   # the sanitizer runtime must come first in the process
+    r = subprocess.run([exe], input="\n".join(lines) + "\n", capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
+    got = r.stdout.strip().split("\n")
+    assert len(got) == len(lines)
+    for line, g, e in zip(lines, got, expect):
+        if e is None:
+            assert g.split()[0] == str(pb.ERR_INVALID), (line, g)
+        else:
+            gt, et = g.split(), e.split()
+            assert gt[0] == et[0], (line, g, e)
+            if et[0] == "0":
+                assert [float(x) for x in gt] == [float(x) for x in et], (line, g, e)
