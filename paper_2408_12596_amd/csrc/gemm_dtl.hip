@@ -843,6 +843,33 @@ static int dtl_group_impl(hipStream_t s, const GemmArgs* a, int n, bool may_cut,
       }
     }
   }
+  // A forward or input-gradient product (one problem, 256x256 tiles, rows = tokens) whose last round would be partly
+  // empty is cut along N: the tile columns that fill whole rounds run as they are, the remaining columns as a problem
+  // of their own, on whatever tile shape fills the chip best for them (8192 x 11008: 1376 tiles = 5.4 rounds become
+  // five whole rounds and 384 blocks of 128 x 128, two to a CU).  Taken for products without a second matrix operand
+  // (residual, GeLU factor): the bias is indexed by column and moves with the cut.
+  if (may_cut && n == 1 && a[0].layout != GEMM_TN && pick == 0 && splits == 1 && !a[0].residual && !a[0].aux) {
+    const GemmArgs& g = a[0];
+    const int64_t tm = cdiv(g.M, 256), tn = cdiv(g.N, 256), tiles = tm * tn, rest = tiles % 256;
+    if (tiles > 256 && rest != 0 && rest % tm == 0 && rest / tm < tn) {
+      const int64_t keep = (tn - rest / tm) * 256;         // columns of the main part
+      const int64_t es_c = g.c_float ? 4 : 2;
+      GemmArgs h = g, t = g;
+      h.N = keep;
+      t.N = g.N - keep;
+      t.B = g.layout == GEMM_NT ? (const void*)((const bf16*)g.B + keep * g.ldb) : (const void*)((const bf16*)g.B + keep);
+      t.C = (char*)g.C + keep * es_c;
+      if (g.bias) t.bias = (const bf16*)g.bias + keep;
+      h.ev_stop = nullptr; t.ev_start = nullptr;
+      int pk, sp;
+      const double cut = dtl_plan(&h, 1, plain, &pk, &sp) + dtl_plan(&t, 1, plain, &pk, &sp);
+      DtlGemmParams probe;
+      if (cut < 0.96 * best && dtl_prepare(h, probe) == POPLAR_OK && dtl_prepare(t, probe) == POPLAR_OK) {
+        POPLAR_TRY(dtl_group_impl(s, &h, 1, false));
+        return dtl_group_impl(s, &t, 1, false);
+      }
+    }
+  }
   const int BM = cfgs[pick].bm, BN = cfgs[pick].bn;
   const int k_per_split = (int)round_up(cdiv(K, splits), DTL_BK);
   splits = (int)cdiv(K, k_per_split);

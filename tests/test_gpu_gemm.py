@@ -99,6 +99,10 @@ WHOLE = [
     (pb.GEMM_NT, 26624, 8192, 2048, False), (pb.GEMM_NN, 26624, 2048, 8192, False), (pb.GEMM_TN, 8192, 2048, 26624, True),
     (pb.GEMM_TN, 2048, 6144, 26624, True),
     (pb.GEMM_NT, 8192, 22016, 4096, False), (pb.GEMM_TN, 4096, 11008, 8192, True),
+    # 1376 tiles: the launcher cuts the partial sixth round off along N and runs it on smaller tiles
+    (pb.GEMM_NN, 8192, 11008, 4096, False), (pb.GEMM_NT, 8192, 11008, 4096, True),
+    # 688 tiles of a lone weight gradient: cut along M, the rest split over K
+    (pb.GEMM_TN, 11008, 4096, 8192, True),
 ]
 
 
