@@ -28,19 +28,32 @@ HEADLINE = dict(arch="llama", L=32, H=4096, nh=32, F=11008, S=2048, V=32000)
 HEADLINE_WORLD, HEADLINE_STAGE, HEADLINE_SWEEP = 16, 3, (1, 2, 4)
 MID = dict(arch="gpt", L=24, H=2048, nh=16, F=8192, S=2048, V=50257)
 MID_WORLD, MID_STAGE, MID_SWEEP, MID_ODD = 4, 2, (1, 2, 4, 8), (3, 5, 7, 13)
+WORKLOADS = {   # name -> (model, simulated world, ZeRO stage, local-batch sweep, description)
+    "llama7b": (HEADLINE, HEADLINE_WORLD, HEADLINE_STAGE, HEADLINE_SWEEP,
+                "Llama-7B-shaped decoder (32 layers, hidden 4096, 32 heads of 128, SwiGLU MLP 11008, RMSNorm, RoPE, seq 2048, vocab 32000), "
+                "bf16 compute, fp32 master; ZeRO-3 step of rank 0 of a simulated world of 16: per-layer parameter gather, fwd + bwd with the "
+                "local gradient reduce, Adam on the 1/16 shard"),
+    "gpt1p3b": (MID, MID_WORLD, MID_STAGE, MID_SWEEP,
+                "~1.3B GPT decoder (24 layers, hidden 2048, 16 heads of 128, MLP 8192 GeLU, seq 2048, vocab 50257), bf16 compute, fp32 master; "
+                "ZeRO-2 step of rank 0 of a simulated world of 4: fwd + bwd with the local gradient reduce, Adam on the 1/4 shard"),
+    "gpt2small": (WORKLOAD, WORLD, STAGE, SWEEP,
+                  "GPT-2-small-shaped decoder (12 layers, hidden 768, 12 heads of 64, MLP 3072 GeLU, seq 1024, vocab 50257), bf16 compute, "
+                  "fp32 master; ZeRO-1 step of rank 0 of a simulated world of 8: fwd + bwd, Adam on the 1/8 shard"),
+}
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # Bytes that cross the L2 per GEMM launch of the headline step, averaged over its launches: rocprofv3 counters
 # FETCH_SIZE and WRITE_SIZE, scaled by the factors a copy of known size gives, summarised under profiles/.
-# None while no counters have been taken for the GEMM kernel as it stands.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = None
+# Per kernel launch (355 per step: a weight-gradient group or a product whose partial last round is cut off is two).
+# Valid for the GEMM kernel as profiled; set to None when that kernel changes until the counters are taken again.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 1617e6
 # Events ride on the GEMM launches of every GEMM_EVENTS_EVERY-th timed step (the first, the sixth, ...): an attached
 # pair of events costs about 4.5 us per launch, 0.5 ms on a step's 111 launches, and the headline number should
 # carry as little of the instrument as the measurement allows.
 GEMM_EVENTS_EVERY = 5
 
 
-def cpu_baseline(model):
+def cpu_baseline(model, n):
     """The oracle as it stands, timed on this host, on a bounded sample of the headline workload: forward +
     backward of the headline's local batch (4 samples) through ONE decoder layer of the model's shape (fp64 NumPy;
     10 TFLOP at the Llama-7B shape, 10-30 s).  The whole step is 32 such layers plus embedding, head and optimizer,
@@ -57,7 +70,6 @@ def cpu_baseline(model):
     spec = [(f"l0.{n}", s) for n, s in otr.layer_spec(model["arch"], H, model["F"])]
     flat = synth.init_params(spec, seed=0).astype(np.float64)
     p = {k[3:]: v for k, v in otr.unpack(flat, spec).items()}
-    n = max(HEADLINE_SWEEP)
     x = synth.activations((n, S, H), seed=1).astype(np.float64)
     dy = synth.activations((n, S, H), seed=2).astype(np.float64)
     t0 = time.perf_counter()
@@ -297,7 +309,7 @@ def kernel_rooflines(ctx, torch, stage, B):
     _, g = timed_steps(ctx, torch, stage, B, 2, 0, 1)
     _, a = timed_steps(ctx, torch, stage, B, 2, 0, 2)
     tg, ta = float(np.mean([p["t_gemm"] for p in g])), float(np.mean([p["t_attn"] for p in a]))
-    out = {"gemm": {"achieved": g[0]["gemm_flops"] / tg / 1e12, "launches_per_step": g[0]["n_gemm"], "ms_per_step": tg * 1e3},
+    out = {"gemm": {"achieved": g[0]["gemm_flops"] / tg / 1e12, "launches_per_step": g[0]["n_gemm_kernels"], "ms_per_step": tg * 1e3},
            "attention": {"achieved": a[0]["attn_flops"] / ta / 1e12, "launches_per_step": a[0]["n_attn"], "ms_per_step": ta * 1e3}}
     for v in out.values():
         v.update(unit="TFLOP/s", peak=PEAK_BF16_TFLOPS, frac=v["achieved"] / PEAK_BF16_TFLOPS)
@@ -360,10 +372,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--batch", type=int, default=max(HEADLINE_SWEEP), help="local batch of the headline number")
+    ap.add_argument("--batch", type=int, default=0, help="local batch of the headline number (default: the top of the workload's sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true", help="the headline configuration's timed steps and rooflines only "
                     "(no sweeps, no sub-records, no CPU leg): the short run the rocprofv3 summaries under profiles/ are taken from")
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="llama7b", help="which configuration takes the headline's place "
+                    "(default: the Llama-7B shape; the others exist so that the profiler can be pointed at them with --headline-only)")
     ap.add_argument("--curve-report", action="store_true", help="add the dense-sweep / spline / Algorithm 2 report (GPT-2-small) to the line")
     ap.add_argument("--layer-report", action="store_true", help="add one-layer timings at the larger configurations' shapes")
     ap.add_argument("--clock-report", action="store_true", help="add GEMM rates on zero, one and normal operands with the shader "
@@ -377,9 +391,9 @@ def main():
     from paper_2408_12596_amd import binding as pb
 
     pb.lib()   # fails loudly if the HIP library has not been built
-    model, world, stage = HEADLINE, HEADLINE_WORLD, HEADLINE_STAGE
-    B = args.batch
-    r = DeviceRank(pb, torch, model, world, stage, max(max(HEADLINE_SWEEP), B))
+    model, world, stage, sweep, label = WORKLOADS[args.workload]
+    B = args.batch if args.batch else max(sweep)
+    r = DeviceRank(pb, torch, model, world, stage, max(max(sweep), B))
     ctx = r.ctx
     # the timed steps carry events on the GEMM launches of every fifth step (the roofline kernel, measured live in the
     # timed region on the launch stream); the attention kernels are timed in further steps afterwards
@@ -387,7 +401,7 @@ def main():
     mean = lambda k: float(np.mean([p[k] for p in profs]))
     flops = profs[0]["flops"]
     evp = profs[::GEMM_EVENTS_EVERY]
-    t_gemm, f_gemm, n_gemm = float(np.mean([p["t_gemm"] for p in evp])), evp[0]["gemm_flops"], evp[0]["n_gemm"]
+    t_gemm, f_gemm, n_gemm = float(np.mean([p["t_gemm"] for p in evp])), evp[0]["gemm_flops"], evp[0]["n_gemm_kernels"]
     gemm_tflops = f_gemm / t_gemm / 1e12 if t_gemm > 0 else 0.0
     _, aprofs = timed_steps(ctx, torch, stage, B, 2, 0, 2)
     t_attn, f_attn = float(np.mean([p["t_attn"] for p in aprofs])), aprofs[0]["attn_flops"]
@@ -395,10 +409,7 @@ def main():
         "metric": "samples/sec", "value": B / dt, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "Llama-7B-shaped decoder (32 layers, hidden 4096, 32 heads of 128, SwiGLU MLP 11008, RMSNorm, RoPE, seq 2048, "
-                               "vocab 32000), bf16 compute, fp32 master; ZeRO-3 step of rank 0 of a simulated world of 16: per-layer parameter "
-                               "gather, fwd + bwd with the local gradient reduce, Adam on the 1/16 shard",
-                   "local_batch": B, "zero_stage": stage, "world": world, "params": r.P, "shard_elems": r.valid},
+        "config": {"workload": label, "local_batch": B, "zero_stage": stage, "world": world, "params": r.P, "shard_elems": r.valid},
         "tflops": flops / dt / 1e12,
         "frac_mfma_peak_step": flops / dt / 1e12 / PEAK_BF16_TFLOPS,
         "samples_per_s_time_consumed": B / mean("t_consumed"),
@@ -406,26 +417,25 @@ def main():
                                   t_gemm=t_gemm * 1e3, t_attn=t_attn * 1e3),
         "roofline": {"bound": "mfma", "kernel": "gemm_dtl_kernel (all GEMM launches of the step)", "achieved": gemm_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if B == max(HEADLINE_SWEEP) else None, "traffic_unit": "bytes per launch",
-                     "launches_per_step": n_gemm, "avg_launch_ms": t_gemm / max(n_gemm, 1) * 1e3,
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "llama7b" and B == max(HEADLINE_SWEEP)) else None,
+                     "traffic_unit": "bytes between the L2 caches and memory per GEMM kernel launch",
+                     "launches_per_step": n_gemm, "timed_spans_per_step": evp[0]["n_gemm"], "avg_launch_ms": t_gemm / max(n_gemm, 1) * 1e3,
                      "timed_steps_with_events": len(evp), "flop_per_launch": f_gemm / max(n_gemm, 1)},
         "attention": {"achieved": f_attn / t_attn / 1e12 if t_attn > 0 else 0.0, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS,
                       "frac": (f_attn / t_attn / 1e12 / PEAK_BF16_TFLOPS) if t_attn > 0 else 0.0, "head_dim": model["H"] // model["nh"],
                       "ms_per_step": t_attn * 1e3},
-        "hbm_kernels": rank_hbm_figures(r.P, r.emb, r.valid, stage, {k: mean(k) for k in ("t_adam", "t_gather_fwd", "t_gather_bwd", "t_reduce_bwd")}, False),
+        "hbm_kernels": rank_hbm_figures(r.P, r.emb, r.valid, stage, {k: mean(k) for k in ("t_adam", "t_gather_fwd", "t_gather_bwd", "t_reduce_bwd")}, model["arch"] == "gpt"),
         "loss": profs[-1]["loss"],
         "device": device_info(pb, torch),
     }
     if not args.headline_only:
-        out["sweep"] = sweep_rows(r, torch, stage, HEADLINE_SWEEP)
+        out["sweep"] = sweep_rows(r, torch, stage, sweep)
     del r, ctx
     torch.cuda.empty_cache()
-    if not args.headline_only:
-        mid = sub_record(pb, torch, "~1.3B GPT decoder (24 layers, hidden 2048, 16 heads of 128, MLP 8192 GeLU, seq 2048, vocab 50257), "
-                         "ZeRO-2 on a 1/4 shard", MID, MID_WORLD, MID_STAGE, MID_SWEEP, MID_ODD)
+    if not args.headline_only and args.workload == "llama7b":
+        mid = sub_record(pb, torch, WORKLOADS["gpt1p3b"][4], MID, MID_WORLD, MID_STAGE, MID_SWEEP, MID_ODD)
         mid["allocation_stress"] = allocation_stress(pb, torch, MID, MID_WORLD, 40 * 2**30)
-        small = sub_record(pb, torch, "GPT-2-small-shaped decoder (12 layers, hidden 768, 12 heads of 64, MLP 3072 GeLU, seq 1024, vocab 50257), "
-                           "ZeRO-1 on a 1/8 shard", WORKLOAD, WORLD, STAGE, SWEEP)
+        small = sub_record(pb, torch, WORKLOADS["gpt2small"][4], WORKLOAD, WORLD, STAGE, SWEEP)
         out["sub_records"] = {"gpt_1p3b_zero2": mid, "gpt2_small_zero1": small}
     if args.curve_report or args.clock_report:
         rs = DeviceRank(pb, torch, WORKLOAD, WORLD, STAGE, max(SWEEP))
@@ -437,7 +447,7 @@ def main():
     if args.layer_report:
         out["layer_report"] = layer_report(pb, torch)
     if not args.no_cpu_baseline and not args.headline_only:
-        out["cpu_baseline"] = cpu_baseline(model)
+        out["cpu_baseline"] = cpu_baseline(model, max(sweep))
     print(json.dumps(out))
 
 

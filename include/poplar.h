@@ -291,6 +291,8 @@ typedef struct poplar_profile {
   double t_attn, attn_flops;    /* same for the attention kernels: 2 S^2 H fwd, 5 S^2 H bwd per sample (causal) */
   int32_t n_gemm, n_attn;       /* launches counted */
   int64_t measured_bytes;       /* with memory hooks: what bytes_now() returned while the step's workspace was held; else 0 */
+  int32_t n_gemm_kernels;       /* GEMM kernels inside the n_gemm timed spans (a grouped launch whose partial last round is cut
+                                   off, or a product cut along N, is one span and two kernels) */
 } poplar_profile;
 
 /* What the current HIP device reports: compute units, the peak engine clock in

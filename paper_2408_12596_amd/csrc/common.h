@@ -27,7 +27,10 @@ int poplar_fail(int code, const char* fmt, ...);
 #define POPLAR_LAUNCH_CHECK() POPLAR_CHECK_HIP(hipGetLastError())
 
 enum LaunchKind { KIND_GEMM = 0, KIND_ATTN = 1, KIND_COUNT = 2 };
-struct TimedLaunch { int kind; hipEvent_t a, b; double flops; };
+struct TimedLaunch { int kind; hipEvent_t a, b; double flops; int kernels; };
+// GEMM kernels launched by this thread so far (every tile kernel of every GEMM path; not the zero fills and adds
+// around them): a timed span reads it before and after to know how many kernels it covered
+extern thread_local int64_t poplar_gemm_kernel_launches;
 
 struct poplar_ctx {
   poplar_model_cfg cfg;

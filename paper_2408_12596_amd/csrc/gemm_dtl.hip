@@ -642,6 +642,7 @@ __global__ void __launch_bounds__(256) splitk_add_kernel(AddGroup g) {
 template <int WM, int WN, int TM, int TN, int EPI>
 static void launch_dtl(hipStream_t s, int layout, dim3 grid, const DtlGroupParams& gp, hipEvent_t e0, hipEvent_t e1) {
   dim3 block(64 * WM * WN);
+  poplar_gemm_kernel_launches += 1;
   // with events the launch itself carries them: they receive the kernel's own start and end
   switch (layout) {
     case GEMM_NT: hipExtLaunchKernelGGL((gemm_dtl_kernel<GEMM_NT, WM, WN, TM, TN, EPI>), grid, block, 0, s, e0, e1, 0, gp); break;

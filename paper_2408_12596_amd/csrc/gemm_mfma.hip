@@ -361,6 +361,7 @@ int gemm_bf16_mfma(hipStream_t s, const GemmArgs& a) {
     }
   }
   dim3 grid((unsigned)tiles, (unsigned)splits);
+  poplar_gemm_kernel_launches += 1;
   if (p.atomic) {
     if (big) launch_tiles<4, 2, true>(s, a.layout, grid, p);
     else launch_tiles<2, 2, true>(s, a.layout, grid, p);

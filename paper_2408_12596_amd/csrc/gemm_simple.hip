@@ -67,6 +67,7 @@ __global__ void __launch_bounds__(256) gemm_simple_kernel(const T* __restrict__ 
 }
 
 int gemm_simple(hipStream_t s, int dtype, const GemmArgs& a) {
+  poplar_gemm_kernel_launches += 1;
   if (a.M == 0 || a.N == 0) return POPLAR_OK;
   SimpleGemmParams p;
   p.M = a.M; p.N = a.N; p.K = a.K;

@@ -21,19 +21,24 @@ struct LaunchTimer {
   poplar_ctx* ctx;
   bool on;
   TimedLaunch tl;
+  int64_t launched0 = 0;
   // hands out the two events, unrecorded
   int begin(int kind, double flops) {
     on = ((ctx->kernel_timing >> kind) & 1) && ctx->in_step;
     tl.a = nullptr; tl.b = nullptr;
     if (!on) return POPLAR_OK;
     tl.kind = kind; tl.flops = flops;
+    launched0 = poplar_gemm_kernel_launches;
     POPLAR_TRY(ctx_take(ctx, &tl.a));
     return ctx_take(ctx, &tl.b);
   }
   int record_start() { return on ? (hipEventRecord(tl.a, ctx->stream) == hipSuccess ? POPLAR_OK : poplar_fail(POPLAR_ERR_HIP, "hipEventRecord")) : POPLAR_OK; }
   int record_stop() { return on ? (hipEventRecord(tl.b, ctx->stream) == hipSuccess ? POPLAR_OK : poplar_fail(POPLAR_ERR_HIP, "hipEventRecord")) : POPLAR_OK; }
   int done() {
-    if (on) ctx->launches.push_back(tl);
+    if (on) {
+      tl.kernels = (int)(poplar_gemm_kernel_launches - launched0);
+      ctx->launches.push_back(tl);
+    }
     return POPLAR_OK;
   }
 };

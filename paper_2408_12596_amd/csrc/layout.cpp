@@ -5,6 +5,7 @@
 #include <string.h>
 
 static thread_local char g_err[512] = "";
+thread_local int64_t poplar_gemm_kernel_launches = 0;
 
 int poplar_fail(int code, const char* fmt, ...) {
   va_list ap;

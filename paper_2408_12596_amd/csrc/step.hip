@@ -396,7 +396,7 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   out->loss = loss_host;
   for (const TimedLaunch& tl : ctx->launches) {
     POPLAR_CHECK_HIP(hipEventElapsedTime(&ms, tl.a, tl.b));
-    if (tl.kind == KIND_GEMM) { out->t_gemm += ms * 1e-3; out->gemm_flops += tl.flops; out->n_gemm += 1; }
+    if (tl.kind == KIND_GEMM) { out->t_gemm += ms * 1e-3; out->gemm_flops += tl.flops; out->n_gemm += 1; out->n_gemm_kernels += tl.kernels; }
     else { out->t_attn += ms * 1e-3; out->attn_flops += tl.flops; out->n_attn += 1; }
   }
   return POPLAR_OK;
@@ -536,7 +536,7 @@ extern "C" int poplar_accum_step(poplar_ctx* ctx, int32_t stage, int32_t n_micro
     tot.t_fwd += pr.t_fwd; tot.t_bwd += pr.t_bwd; tot.t_gather_fwd += pr.t_gather_fwd; tot.t_gather_bwd += pr.t_gather_bwd;
     tot.t_reduce_bwd += pr.t_reduce_bwd; tot.t_consumed += pr.t_consumed; tot.flops += pr.flops; tot.loss += pr.loss;
     tot.t_gemm += pr.t_gemm; tot.gemm_flops += pr.gemm_flops; tot.t_attn += pr.t_attn; tot.attn_flops += pr.attn_flops;
-    tot.n_gemm += pr.n_gemm; tot.n_attn += pr.n_attn;
+    tot.n_gemm += pr.n_gemm; tot.n_attn += pr.n_attn; tot.n_gemm_kernels += pr.n_gemm_kernels;
     if (pr.accounted_bytes > tot.accounted_bytes) tot.accounted_bytes = pr.accounted_bytes;
     if (ms.optimizer) tot.t_adam = pr.t_adam;
   }

@@ -567,10 +567,11 @@ def test_kernel_timing_selects_and_counts_the_launches():
         if sel & 1:
             # forward 4, backward 4 input gradients + the weight gradients as one grouped launch or four; head 3
             assert p["n_gemm"] in (L * 9 + 3, L * 12 + 3)
+            assert p["n_gemm"] <= p["n_gemm_kernels"] <= 2 * p["n_gemm"]   # a span holds one kernel, or two when it is cut
             assert p["gemm_flops"] == pytest.approx(gemm_flop, rel=1e-12)
             assert 0.0 < p["t_gemm"] < p["t_fwd"] + p["t_bwd"]
         else:
-            assert p["n_gemm"] == 0 and p["t_gemm"] == 0.0
+            assert p["n_gemm"] == 0 and p["n_gemm_kernels"] == 0 and p["t_gemm"] == 0.0
         if sel & 2:
             assert p["n_attn"] == 2 * L
             assert p["attn_flops"] == pytest.approx(attn_flop, rel=1e-12)
