@@ -1,7 +1,7 @@
 """Benchmark: one rank's ZeRO training step on one MI355X, through libpoplar's C ABI.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--headline-only]
-                    [--curve-report] [--layer-report] [--model-report] [--clock-report]
+                    [--workload llama7b|gpt1p3b|gpt2small] [--curve-report] [--layer-report] [--clock-report]
 
 Headline: the Llama-7B-shaped configuration (32 layers, hidden 4096, SwiGLU 11008, seq 2048, vocab 32000) at
 ZeRO-3 on a 1/16 shard, the largest configuration that fits one GPU.  A step is poplar_profile_step(3, B):
