@@ -347,7 +347,10 @@ int poplar_set_mem_hooks(poplar_ctx* ctx, const poplar_mem_hooks* hooks);
  * reduce per unit, (stage 3) parameter gather per layer in both passes, Adam
  * on the shard.  Synchronises the stream.  t_consumed follows Section "Time
  * Consumed Estimation": stage 0/1 t_fwd + t_bwd; stage 2 t_fwd + t_bwd -
- * t_reduce_bwd; stage 3 additionally minus both gathers.  Returns
+ * t_reduce_bwd; stage 3 additionally minus both gathers (the three are sums
+ * of the stand-in kernels' own durations, start to end, taken by events that
+ * ride on their launches; a unit that does not meet the shard launches
+ * nothing and adds nothing).  Returns
  * POPLAR_ERR_OOM, with nothing launched and the state untouched, when the
  * accounted bytes exceed cfg.cap_bytes (the "find OOM error" of Algorithm 1)
  * or the bound workspace is too small. */

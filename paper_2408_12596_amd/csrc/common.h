@@ -146,8 +146,11 @@ int xent_fwd_bwd(hipStream_t s, int dtype, int64_t T, int V, int64_t ld, void* l
                  float loss_scale, float* loss, float* row_loss);
 int adam_shard(hipStream_t s, int lowp_dtype, float* p, float* m, float* v, const float* g, void* p_lowp, int64_t n,
                int step_t, float lr, float b1, float b2, float eps);
-int zero2_reduce_local(hipStream_t s, float* gshard, const float* g_unit, int64_t unit_lo, int64_t unit_hi, int64_t shard_off, int64_t shard_len);
-int zero3_gather_local(hipStream_t s, int dtype, void* out, const void* own, const void* peers, int64_t lo, int64_t hi, int64_t shard_off, int64_t shard_len);
+// ev_start / ev_stop: optional events carried by the launches (kernel start / kernel end); *launched: whether anything ran
+int zero2_reduce_local(hipStream_t s, float* gshard, const float* g_unit, int64_t unit_lo, int64_t unit_hi, int64_t shard_off, int64_t shard_len,
+                       hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, int* launched = nullptr);
+int zero3_gather_local(hipStream_t s, int dtype, void* out, const void* own, const void* peers, int64_t lo, int64_t hi, int64_t shard_off, int64_t shard_len,
+                       hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, int* launched = nullptr);
 int fill_zero(hipStream_t s, void* p, int64_t bytes);
 int fill_zero_2d(hipStream_t s, void* p, int64_t rows, int64_t cols, int64_t ld);   // rows x cols 32-bit words, row stride ld words
 int cast_f32_to_lowp(hipStream_t s, int dtype, const float* in, void* out, int64_t n);

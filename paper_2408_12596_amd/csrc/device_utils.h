@@ -119,6 +119,41 @@ __device__ inline float gelu_tanh_grad_fast(float h) {
   return __builtin_fmaf(h * du2 * s, 1.0f - s, s);
 }
 
+// Row accesses through a buffer descriptor.  The descriptor spans `bytes` bytes at p; a lane whose byte offset lies
+// at or beyond that reads zeros and writes nothing, and the instruction is issued all the same.  The row kernels
+// below rely on both halves of that: no lane needs a branch around its loads and stores (a row tail reads as zeros),
+// and every pass over a row issues the same number of memory instructions whatever the row length, so that the
+// compiler can count exactly how many newer ones may stay in flight when it waits for an older one (the counter is
+// in order): a row fetched one step ahead stays in flight while the current one is worked on and stored.  A branch
+// around a load or store (even one that is always taken) makes that count a guess, and the guess is zero; a branch
+// between a load and its first use lets the compiler sink the load down to the use.  So the row loops below are
+// single blocks that handle rows in pairs, a missing second row being a descriptor of zero bytes.
+// AUX: 0 = cached, 2 = non-temporal.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ inline __amdgpu_buffer_rsrc_t span_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+template <typename T, int AUX = 0>
+__device__ inline void span_load(Vec<T>& v, __amdgpu_buffer_rsrc_t rs, uint32_t byte_off) {
+  v.raw = __builtin_bit_cast(decltype(v.raw), __builtin_amdgcn_raw_buffer_load_b128(rs, (int)byte_off, 0, AUX));
+}
+template <typename T, int AUX = 0>
+__device__ inline void span_store(const Vec<T>& v, __amdgpu_buffer_rsrc_t rs, uint32_t byte_off) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v.raw), rs, (int)byte_off, 0, AUX);
+}
+// one value stored by the lane with in_range_lane_off == 0 only: the others point past the descriptor's 4 or 8 bytes
+__device__ inline void span_store_f1(float a, __amdgpu_buffer_rsrc_t rs, uint32_t lane_off) {
+  __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(a), rs, (int)lane_off, 0, 0);
+}
+__device__ inline void span_store_f2(float a, float b, __amdgpu_buffer_rsrc_t rs, uint32_t lane_off) {
+  u32x2 t = {__float_as_uint(a), __float_as_uint(b)};
+  __builtin_amdgcn_raw_buffer_store_b64(t, rs, (int)lane_off, 0, 0);
+}
+// Barrier of the block for LDS traffic only: waits for this wave's LDS operations and meets the others.  Unlike
+// __syncthreads() it carries no fence over global memory, which would wait for every load and store in flight.
+__device__ inline void block_sync_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // streaming (non-temporal) 16-byte / 8-byte accesses: index i counts vectors
 typedef float nt_f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t nt_u2 __attribute__((ext_vector_type(2)));

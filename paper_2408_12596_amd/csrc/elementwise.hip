@@ -173,8 +173,12 @@ __global__ void axpy_scalar_kernel(float* __restrict__ dst, const float* __restr
   for (; i < n; i += stride) dst[i] += src[i];
 }
 
+// ev_start / ev_stop (both or neither): events that ride on the launches themselves and receive the first kernel's
+// start and the last kernel's end, so that a timed span holds the kernels and nothing else.  *launched tells the
+// caller whether anything ran (an empty intersection launches nothing and leaves the events untouched).
 int zero2_reduce_local(hipStream_t s, float* gshard, const float* g_unit, int64_t unit_lo, int64_t unit_hi,
-                       int64_t shard_off, int64_t shard_len) {
+                       int64_t shard_off, int64_t shard_len, hipEvent_t ev_start, hipEvent_t ev_stop, int* launched) {
+  if (launched) *launched = 0;
   int64_t lo = unit_lo > shard_off ? unit_lo : shard_off;
   int64_t hi = unit_hi < shard_off + shard_len ? unit_hi : shard_off + shard_len;
   if (hi <= lo) return POPLAR_OK;
@@ -182,14 +186,17 @@ int zero2_reduce_local(hipStream_t s, float* gshard, const float* g_unit, int64_
   const float* src = g_unit + (lo - unit_lo);
   int64_t n = hi - lo;
   int64_t n4 = (aligned16(dst) && aligned16(src)) ? n / 4 : 0;
+  const bool tail = n4 * 4 < n;
   if (n4 > 0) {
-    hipLaunchKernelGGL(axpy_vec_kernel, dim3(grid_for(n4, 256)), dim3(256), 0, s, dst, src, n4);
+    hipExtLaunchKernelGGL(axpy_vec_kernel, dim3(grid_for(n4, 256)), dim3(256), 0, s, ev_start, tail ? nullptr : ev_stop, 0, dst, src, n4);
     POPLAR_LAUNCH_CHECK();
   }
-  if (n4 * 4 < n) {
-    hipLaunchKernelGGL(axpy_scalar_kernel, dim3(grid_for(n - n4 * 4, 256)), dim3(256), 0, s, dst, src, n4 * 4, n);
+  if (tail) {
+    hipExtLaunchKernelGGL(axpy_scalar_kernel, dim3(grid_for(n - n4 * 4, 256)), dim3(256), 0, s, n4 > 0 ? nullptr : ev_start, ev_stop, 0,
+                          dst, src, n4 * 4, n);
     POPLAR_LAUNCH_CHECK();
   }
+  if (launched) *launched = 1;
   return POPLAR_OK;
 }
 
@@ -207,7 +214,8 @@ __global__ void gather_kernel(W* __restrict__ out, const W* __restrict__ own, co
 }
 
 int zero3_gather_local(hipStream_t s, int dtype, void* out, const void* own, const void* peers, int64_t lo, int64_t hi,
-                       int64_t shard_off, int64_t shard_len) {
+                       int64_t shard_off, int64_t shard_len, hipEvent_t ev_start, hipEvent_t ev_stop, int* launched) {
+  if (launched) *launched = 0;
   if (hi <= lo) return POPLAR_OK;
   const int64_t es = elt_size(dtype);
   const int64_t per = 16 / es;  // elements per 16-byte word
@@ -215,16 +223,17 @@ int zero3_gather_local(hipStream_t s, int dtype, void* out, const void* own, con
   bool vec = aligned16(out) && aligned16(own) && aligned16(peers) && lo % per == 0 && n % per == 0 &&
              shard_off % per == 0 && shard_len % per == 0;
   if (vec) {
-    hipLaunchKernelGGL(gather_kernel<uint4>, dim3(grid_for(n / per, 256)), dim3(256), 0, s, (uint4*)out, (const uint4*)own,
-                       (const uint4*)peers, lo / per, n / per, shard_off / per, (shard_off + shard_len) / per);
+    hipExtLaunchKernelGGL(gather_kernel<uint4>, dim3(grid_for(n / per, 256)), dim3(256), 0, s, ev_start, ev_stop, 0, (uint4*)out, (const uint4*)own,
+                          (const uint4*)peers, lo / per, n / per, shard_off / per, (shard_off + shard_len) / per);
   } else if (es == 2) {
-    hipLaunchKernelGGL(gather_kernel<uint16_t>, dim3(grid_for(n, 256)), dim3(256), 0, s, (uint16_t*)out, (const uint16_t*)own,
-                       (const uint16_t*)peers, lo, n, shard_off, shard_off + shard_len);
+    hipExtLaunchKernelGGL(gather_kernel<uint16_t>, dim3(grid_for(n, 256)), dim3(256), 0, s, ev_start, ev_stop, 0, (uint16_t*)out, (const uint16_t*)own,
+                          (const uint16_t*)peers, lo, n, shard_off, shard_off + shard_len);
   } else {
-    hipLaunchKernelGGL(gather_kernel<uint32_t>, dim3(grid_for(n, 256)), dim3(256), 0, s, (uint32_t*)out, (const uint32_t*)own,
-                       (const uint32_t*)peers, lo, n, shard_off, shard_off + shard_len);
+    hipExtLaunchKernelGGL(gather_kernel<uint32_t>, dim3(grid_for(n, 256)), dim3(256), 0, s, ev_start, ev_stop, 0, (uint32_t*)out, (const uint32_t*)own,
+                          (const uint32_t*)peers, lo, n, shard_off, shard_off + shard_len);
   }
   POPLAR_LAUNCH_CHECK();
+  if (launched) *launched = 1;
   return POPLAR_OK;
 }
 
@@ -232,10 +241,114 @@ int zero3_gather_local(hipStream_t s, int dtype, void* out, const void* own, con
 // LayerNorm / RMSNorm.  One wavefront per row, the row held in registers
 // (NV 16-byte vectors per lane), so x is read from HBM once.
 // stats: float [T, 2] = (mean, rstd); RMSNorm stores mean = 0.
+//
+// A wave walks rows wave, wave + nwaves, ... with the row after the current one already requested: two register
+// sets take turns inside a loop body that handles two rows and has no branch in it (a row that does not exist is a
+// descriptor of zero bytes: its loads return zeros, its stores go nowhere), every load and store goes through a row
+// descriptor and is issued unconditionally (see span_rsrc), and before the loop a row's worth of stores is issued to
+// nowhere, so that the loop is entered with the same operations in flight as it is re-entered with.  The waits the
+// compiler then places let the next row's loads and the previous row's stores stay in flight.
 // ---------------------------------------------------------------------------
 template <typename T, int NV, bool RMS>
 __global__ void __launch_bounds__(256) norm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ g, const T* __restrict__ b,
                                                         T* __restrict__ y, float* __restrict__ stats, int64_t rows, int H) {
+  constexpr int VN = Vec<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  if (wave >= rows) return;
+  const uint32_t row_bytes = (uint32_t)H * sizeof(T);
+  const float inv_h = 1.0f / (float)H;
+  Vec<T> gam[NV], bet[NV];
+  {
+    const __amdgpu_buffer_rsrc_t rg = span_rsrc(g, row_bytes), rb = span_rsrc(RMS ? g : b, row_bytes);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      span_load<T>(gam[i], rg, (uint32_t)(i * 64 + lane) * 16);
+      if (!RMS) span_load<T>(bet[i], rb, (uint32_t)(i * 64 + lane) * 16);
+    }
+  }
+  // row r if it exists, else nothing: the address stays inside the tensor either way
+  auto fetch = [&](Vec<T> (&q)[NV], int64_t r) __attribute__((always_inline)) {
+    const bool have = r < rows;
+    const __amdgpu_buffer_rsrc_t rs = span_rsrc(x + (have ? r : 0) * H, have ? row_bytes : 0u);
+    __builtin_amdgcn_sched_barrier(0);   // the loads go out here, in this order: not after the arithmetic they are meant to overlap
+#pragma unroll
+    for (int i = 0; i < NV; ++i) span_load<T>(q[i], rs, (uint32_t)(i * 64 + lane) * 16);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto work = [&](Vec<T> (&q)[NV], int64_t r) __attribute__((always_inline)) {
+    const bool have = r < rows;
+    float f[NV][VN];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      q[i].unpack(f[i]);   // lanes past the row's end hold zeros
+#pragma unroll
+      for (int k = 0; k < VN; ++k) sum += RMS ? f[i][k] * f[i][k] : f[i][k];
+    }
+    sum = wave_sum(sum);
+    float mean = 0.f, var;
+    if (RMS) {
+      var = sum * inv_h;
+    } else {
+      mean = sum * inv_h;
+      float sq = 0.f;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const bool in = (i * 64 + lane) * VN < H;
+#pragma unroll
+        for (int k = 0; k < VN; ++k) { const float d = in ? f[i][k] - mean : 0.f; sq += d * d; }
+      }
+      var = wave_sum(sq) * inv_h;
+    }
+    const float rstd = 1.0f / sqrtf(var + 1e-5f);
+    span_store_f2(mean, rstd, span_rsrc(stats + 2 * (have ? r : 0), have ? 8u : 0u), (uint32_t)lane * 8);
+    const __amdgpu_buffer_rsrc_t ry = span_rsrc(y + (have ? r : 0) * H, have ? row_bytes : 0u);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      float gg[VN], bb[VN], o[VN];
+      gam[i].unpack(gg);
+      if (!RMS) bet[i].unpack(bb);
+#pragma unroll
+      for (int k = 0; k < VN; ++k) o[k] = (f[i][k] - mean) * rstd * gg[k] + (RMS ? 0.f : bb[k]);
+      Vec<T> v; v.pack(o);
+      span_store<T>(v, ry, (uint32_t)(i * 64 + lane) * 16);
+    }
+  };
+  Vec<T> qa[NV], qb[NV];
+  // rows r and r + nwaves; qa holds row r on entry and row r + 2 nwaves on exit
+  auto pair = [&](int64_t r) __attribute__((always_inline)) {
+    fetch(qb, r + nwaves);
+    work(qa, r);
+    fetch(qa, r + 2 * nwaves);
+    work(qb, r + nwaves);
+  };
+  int64_t r = wave;
+  fetch(qa, r);
+  {
+    // as many stores as work() issues, through a descriptor of zero bytes: they go nowhere, and the loop is entered
+    // with the same sequence of operations behind qa's loads as it is re-entered with
+    const __amdgpu_buffer_rsrc_t none = span_rsrc(y, 0u);
+    Vec<T> z; float zf[VN];
+#pragma unroll
+    for (int k = 0; k < VN; ++k) zf[k] = 0.f;
+    z.pack(zf);
+    span_store_f2(0.f, 0.f, none, 0u);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) span_store<T>(z, none, (uint32_t)i * 16);   // distinct offsets: identical stores would be merged
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  do {
+    pair(r);
+    r += 2 * nwaves;
+  } while (r < rows);
+}
+
+// Rows too long for two register sets (NV = 16): one row at a time.
+template <typename T, int NV, bool RMS>
+__global__ void __launch_bounds__(256) norm_fwd_long_kernel(const T* __restrict__ x, const T* __restrict__ g, const T* __restrict__ b,
+                                                             T* __restrict__ y, float* __restrict__ stats, int64_t rows, int H) {
   constexpr int VN = Vec<T>::N;
   const int lane = threadIdx.x & 63;
   const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -288,18 +401,29 @@ __global__ void __launch_bounds__(256) norm_fwd_kernel(const T* __restrict__ x, 
   }
 }
 
+// Waves per CU that keep about 96 KB of rows in flight (two rows per wave), in blocks of four waves over 256 CUs,
+// but never fewer than two rows per wave's walk where the rows allow it.
+static int norm_fwd_blocks(int64_t rows, int64_t row_bytes) {
+  int64_t per_cu = cdiv(96 * 1024, 2 * row_bytes * 4);   // blocks per CU
+  if (per_cu < 1) per_cu = 1;
+  if (per_cu > 6) per_cu = 6;
+  int64_t blocks = per_cu * 256;
+  if (blocks > cdiv(rows, 8)) blocks = cdiv(rows, 8);
+  return (int)(blocks < 1 ? 1 : blocks);
+}
+
 template <typename T, bool RMS>
 static int norm_fwd_launch(hipStream_t s, int64_t rows, int H, const T* x, const T* g, const T* b, T* y, float* stats) {
   constexpr int VN = Vec<T>::N;
   int need = (int)cdiv(H, 64 * VN);
-  int grid = grid_for(rows, 4);
+  int grid = norm_fwd_blocks(rows, (int64_t)H * sizeof(T));
 #define NORM_FWD_CASE(NVV) \
   hipLaunchKernelGGL((norm_fwd_kernel<T, NVV, RMS>), dim3(grid), dim3(256), 0, s, x, g, b, y, stats, rows, H)
   if (need <= 1) NORM_FWD_CASE(1);
   else if (need <= 2) NORM_FWD_CASE(2);
   else if (need <= 4) NORM_FWD_CASE(4);
   else if (need <= 8) NORM_FWD_CASE(8);
-  else if (need <= 16) NORM_FWD_CASE(16);
+  else if (need <= 16) hipLaunchKernelGGL((norm_fwd_long_kernel<T, 16, RMS>), dim3(grid_for(rows, 4)), dim3(256), 0, s, x, g, b, y, stats, rows, H);
   else return poplar_fail(POPLAR_ERR_INVALID, "hidden %d too large for the norm kernel", H);
 #undef NORM_FWD_CASE
   POPLAR_LAUNCH_CHECK();
@@ -320,6 +444,9 @@ int layernorm_fwd(hipStream_t s, int dtype, int64_t T_, int H, const void* x, co
 // and keeps per-column partial sums of dy*xhat (dgamma) and dy (dbeta) in
 // registers; the four waves of a block are added through LDS and the block
 // writes one row of `partials` [nblocks, 2, H].
+// The row loop is built like the forward kernel's: rows in pairs, two register sets, every access through a row
+// descriptor (a row that does not exist, and a residual gradient that is not given, are descriptors of zero bytes
+// and read as zeros, which add nothing to any sum).
 template <typename T, int NV, bool RMS>
 __global__ void __launch_bounds__(256) norm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, const T* __restrict__ g,
                                                         const float* __restrict__ stats, const T* __restrict__ dres,
@@ -327,71 +454,93 @@ __global__ void __launch_bounds__(256) norm_bwd_kernel(const T* __restrict__ dy,
   constexpr int VN = Vec<T>::N;
   const int lane = threadIdx.x & 63;
   const int wv = threadIdx.x >> 6;
-  const int64_t wave = (int64_t)blockIdx.x * 4 + wv;
+  const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + wv));
   const int64_t nwaves = (int64_t)gridDim.x * 4;
+  const uint32_t row_bytes = (uint32_t)H * sizeof(T);
   float accg[NV][VN], accb[NV][VN], gam[NV][VN];
-#pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    int c = (i * 64 + lane) * VN;
-#pragma unroll
-    for (int k = 0; k < VN; ++k) { accg[i][k] = 0.f; accb[i][k] = 0.f; gam[i][k] = 0.f; }
-    if (c < H) { Vec<T> v; v.load(g + c); v.unpack(gam[i]); }
-  }
-  // The row after the current one is fetched before the current one is worked on: a wave has a handful of
-  // rows, each 1-3 KB, and would otherwise sit through two memory round trips per row.
-  struct RowRaw { Vec<T> x[NV], dy[NV], rs[NV]; float mean, rstd; };
-  auto fetch = [&](int64_t r, RowRaw& q) {
+  {
+    const __amdgpu_buffer_rsrc_t rg = span_rsrc(g, row_bytes);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int c = (i * 64 + lane) * VN;
-      if (c < H) {
-        q.x[i].load(x + r * H + c);
-        q.dy[i].load(dy + r * H + c);
-        if (dres) q.rs[i].load(dres + r * H + c);
-      }
+      Vec<T> v;
+      span_load<T>(v, rg, (uint32_t)(i * 64 + lane) * 16);
+      v.unpack(gam[i]);
+#pragma unroll
+      for (int k = 0; k < VN; ++k) { accg[i][k] = 0.f; accb[i][k] = 0.f; }
     }
-    q.mean = stats[2 * r]; q.rstd = stats[2 * r + 1];
+  }
+  struct RowRaw { Vec<T> x[NV], dy[NV], rs[NV]; float mean, rstd; };
+  auto fetch = [&](RowRaw& q, int64_t r) __attribute__((always_inline)) {
+    const bool have = r < rows;
+    const int64_t rr = have ? r : 0;
+    const __amdgpu_buffer_rsrc_t rx = span_rsrc(x + rr * H, have ? row_bytes : 0u), rd = span_rsrc(dy + rr * H, have ? row_bytes : 0u),
+                                 rs = span_rsrc(dres ? dres + rr * H : x, have && dres ? row_bytes : 0u);
+    q.mean = stats[2 * rr]; q.rstd = stats[2 * rr + 1];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const uint32_t off = (uint32_t)(i * 64 + lane) * 16;
+      span_load<T>(q.x[i], rx, off);
+      span_load<T>(q.dy[i], rd, off);
+      span_load<T>(q.rs[i], rs, off);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   };
-  RowRaw cur, nxt;
-  if (wave < rows) fetch(wave, cur);
-  for (int64_t r = wave; r < rows; r += nwaves) {
-    if (r + nwaves < rows) fetch(r + nwaves, nxt);
+  auto work = [&](RowRaw& cur, int64_t r) __attribute__((always_inline)) {
+    const bool have = r < rows;
     const float mean = cur.mean, rstd = cur.rstd;
     float xh[NV][VN], dxh[NV][VN];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      int c = (i * 64 + lane) * VN;
-      if (c < H) {
-        float xv[VN], dv[VN];
-        cur.x[i].unpack(xv);
-        cur.dy[i].unpack(dv);
+      float xv[VN], dv[VN];
+      cur.x[i].unpack(xv);
+      cur.dy[i].unpack(dv);
 #pragma unroll
-        for (int k = 0; k < VN; ++k) {
-          xh[i][k] = (xv[k] - mean) * rstd;
-          dxh[i][k] = dv[k] * gam[i][k];
-          accg[i][k] += dv[k] * xh[i][k];
-          accb[i][k] += dv[k];
-          s1 += dxh[i][k];
-          s2 += dxh[i][k] * xh[i][k];
-        }
+      for (int k = 0; k < VN; ++k) {
+        xh[i][k] = (xv[k] - mean) * rstd;
+        dxh[i][k] = dv[k] * gam[i][k];
+        accg[i][k] += dv[k] * xh[i][k];
+        accb[i][k] += dv[k];
+        s1 += dxh[i][k];
+        s2 += dxh[i][k] * xh[i][k];
       }
     }
     s1 = RMS ? 0.f : wave_sum(s1) / H;
     s2 = wave_sum(s2) / H;
+    const __amdgpu_buffer_rsrc_t ro = span_rsrc(dx + (have ? r : 0) * H, have ? row_bytes : 0u);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      int c = (i * 64 + lane) * VN;
-      if (c < H) {
-        float o[VN], rs[VN];
-        Vec<T> v;
-        if (dres) cur.rs[i].unpack(rs);
+      float o[VN], rs[VN];
+      cur.rs[i].unpack(rs);
 #pragma unroll
-        for (int k = 0; k < VN; ++k) o[k] = rstd * (dxh[i][k] - s1 - xh[i][k] * s2) + (dres ? rs[k] : 0.f);
-        v.pack(o); v.store(dx + r * H + c);
-      }
+      for (int k = 0; k < VN; ++k) o[k] = rstd * (dxh[i][k] - s1 - xh[i][k] * s2) + rs[k];
+      Vec<T> v; v.pack(o);
+      span_store<T>(v, ro, (uint32_t)(i * 64 + lane) * 16);
     }
-    cur = nxt;
+  };
+  if (wave < rows) {
+    RowRaw qa, qb;
+    int64_t r = wave;
+    fetch(qa, r);
+    {
+      // a row's worth of stores to nowhere: the loop is entered with the operations in flight it is re-entered with
+      const __amdgpu_buffer_rsrc_t none = span_rsrc(dx, 0u);
+      Vec<T> z; float zf[VN];
+#pragma unroll
+      for (int k = 0; k < VN; ++k) zf[k] = 0.f;
+      z.pack(zf);
+#pragma unroll
+      for (int i = 0; i < NV; ++i) span_store<T>(z, none, (uint32_t)i * 16);   // distinct offsets: identical stores would be merged
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    do {
+      fetch(qb, r + nwaves);
+      work(qa, r);
+      fetch(qa, r + 2 * nwaves);
+      work(qb, r + nwaves);
+      r += 2 * nwaves;
+    } while (r < rows);
   }
   // block reduction of the per-wave column sums
   extern __shared__ float lds[];  // [4][2][H]
@@ -421,87 +570,99 @@ __global__ void __launch_bounds__(256) norm_bwd_wide_kernel(const T* __restrict_
                                                              const float* __restrict__ stats, const T* __restrict__ dres,
                                                              T* __restrict__ dx, float* __restrict__ partials, int64_t rows, int H) {
   constexpr int VN = Vec<T>::N;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int wv = threadIdx.x >> 6;
+  const uint32_t row_bytes = (uint32_t)H * sizeof(T);
   float accg[NVW][VN], accb[NVW][VN], gam[NVW][VN];
-#pragma unroll
-  for (int i = 0; i < NVW; ++i) {
-    const int c = (i * 256 + threadIdx.x) * VN;
-#pragma unroll
-    for (int k = 0; k < VN; ++k) { accg[i][k] = 0.f; accb[i][k] = 0.f; gam[i][k] = 0.f; }
-    if (c < H) { Vec<T> v; v.load(g + c); v.unpack(gam[i]); }
-  }
-  struct RowRaw { Vec<T> x[NVW], dy[NVW], rs[NVW]; float mean, rstd; };
-  auto fetch = [&](int64_t r, RowRaw& q) {
+  {
+    const __amdgpu_buffer_rsrc_t rg = span_rsrc(g, row_bytes);
 #pragma unroll
     for (int i = 0; i < NVW; ++i) {
-      const int c = (i * 256 + threadIdx.x) * VN;
-      if (c < H) {
-        q.x[i].load(x + r * H + c);
-        q.dy[i].load(dy + r * H + c);
-        if (dres) q.rs[i].load(dres + r * H + c);
-      }
+      Vec<T> v;
+      span_load<T>(v, rg, (uint32_t)(i * 256 + threadIdx.x) * 16);
+      v.unpack(gam[i]);
+#pragma unroll
+      for (int k = 0; k < VN; ++k) { accg[i][k] = 0.f; accb[i][k] = 0.f; }
     }
-    q.mean = stats[2 * r]; q.rstd = stats[2 * r + 1];
-  };
-  // PF rows are in flight per block: one row's arithmetic is far shorter than a memory round trip
-  constexpr int PF = NVW == 1 ? 4 : NVW == 2 ? 3 : 2;
+  }
+  struct RowRaw { Vec<T> x[NVW], dy[NVW], rs[NVW]; float mean, rstd; };
   __shared__ float red[2][2][4];
-  RowRaw q[PF];
-  const int64_t r0 = blockIdx.x, step = gridDim.x;
+  const int64_t step = gridDim.x;
+  auto fetch = [&](RowRaw& q, int64_t r) __attribute__((always_inline)) {
+    const bool have = r < rows;
+    const int64_t rr = have ? r : 0;
+    const __amdgpu_buffer_rsrc_t rx = span_rsrc(x + rr * H, have ? row_bytes : 0u), rd = span_rsrc(dy + rr * H, have ? row_bytes : 0u),
+                                 rs = span_rsrc(dres ? dres + rr * H : x, have && dres ? row_bytes : 0u);
+    q.mean = stats[2 * rr]; q.rstd = stats[2 * rr + 1];
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int j = 0; j < PF; ++j)
-    if (r0 + j * step < rows) fetch(r0 + j * step, q[j]);
-  int par = 0;
-  for (int64_t rb = r0; rb < rows; rb += PF * step) {
+    for (int i = 0; i < NVW; ++i) {
+      const uint32_t off = (uint32_t)(i * 256 + threadIdx.x) * 16;
+      span_load<T>(q.x[i], rx, off);
+      span_load<T>(q.dy[i], rd, off);
+      span_load<T>(q.rs[i], rs, off);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // par: which of the two LDS slots this row uses; a wave cannot be two rows ahead of another (one barrier per row),
+  // so the slots of a parity are free again when it writes them
+  auto work = [&](RowRaw& cur, int64_t r, int par) __attribute__((always_inline)) {
+    const bool have = r < rows;
+    const float mean = cur.mean, rstd = cur.rstd;
+    float xh[NVW][VN], dxh[NVW][VN];
+    float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int j = 0; j < PF; ++j) {
-      const int64_t r = rb + j * step;
-      if (r < rows) {   // uniform over the block
-        RowRaw& cur = q[j];
-        const float mean = cur.mean, rstd = cur.rstd;
-        float xh[NVW][VN], dxh[NVW][VN], rs[NVW][VN];
-        float s1 = 0.f, s2 = 0.f;
+    for (int i = 0; i < NVW; ++i) {
+      float xv[VN], dv[VN];
+      cur.x[i].unpack(xv);
+      cur.dy[i].unpack(dv);
 #pragma unroll
-        for (int i = 0; i < NVW; ++i) {
-          const int c = (i * 256 + threadIdx.x) * VN;
-          if (c < H) {
-            float xv[VN], dv[VN];
-            cur.x[i].unpack(xv);
-            cur.dy[i].unpack(dv);
-            if (dres) cur.rs[i].unpack(rs[i]);
-#pragma unroll
-            for (int k = 0; k < VN; ++k) {
-              xh[i][k] = (xv[k] - mean) * rstd;
-              dxh[i][k] = dv[k] * gam[i][k];
-              accg[i][k] += dv[k] * xh[i][k];
-              if (!RMS) accb[i][k] += dv[k];
-              s1 += dxh[i][k];
-              s2 += dxh[i][k] * xh[i][k];
-            }
-          }
-        }
-        // the buffer is free again: fetch the row PF steps ahead before waiting on anything
-        if (r + PF * step < rows) fetch(r + PF * step, q[j]);
-        s1 = RMS ? 0.f : wave_sum(s1);
-        s2 = wave_sum(s2);
-        if (lane == 0) { red[par][0][wv] = s1; red[par][1][wv] = s2; }
-        __syncthreads();   // a wave cannot be two rows ahead of another: the slots of a parity are free again when it writes them
-        s1 = (red[par][0][0] + red[par][0][1] + red[par][0][2] + red[par][0][3]) / H;
-        s2 = (red[par][1][0] + red[par][1][1] + red[par][1][2] + red[par][1][3]) / H;
-        par ^= 1;
-#pragma unroll
-        for (int i = 0; i < NVW; ++i) {
-          const int c = (i * 256 + threadIdx.x) * VN;
-          if (c < H) {
-            float o[VN];
-            Vec<T> v;
-#pragma unroll
-            for (int k = 0; k < VN; ++k) o[k] = rstd * (dxh[i][k] - s1 - xh[i][k] * s2) + (dres ? rs[i][k] : 0.f);
-            v.pack(o); v.store(dx + r * H + c);
-          }
-        }
+      for (int k = 0; k < VN; ++k) {
+        xh[i][k] = (xv[k] - mean) * rstd;
+        dxh[i][k] = dv[k] * gam[i][k];
+        accg[i][k] += dv[k] * xh[i][k];
+        if (!RMS) accb[i][k] += dv[k];
+        s1 += dxh[i][k];
+        s2 += dxh[i][k] * xh[i][k];
       }
     }
+    s1 = RMS ? 0.f : wave_sum(s1);
+    s2 = wave_sum(s2);
+    red[par][0][wv] = s1; red[par][1][wv] = s2;   // every lane of the wave writes the same two values: no branch in the row loop
+    block_sync_lds();
+    s1 = (red[par][0][0] + red[par][0][1] + red[par][0][2] + red[par][0][3]) / H;
+    s2 = (red[par][1][0] + red[par][1][1] + red[par][1][2] + red[par][1][3]) / H;
+    const __amdgpu_buffer_rsrc_t ro = span_rsrc(dx + (have ? r : 0) * H, have ? row_bytes : 0u);
+#pragma unroll
+    for (int i = 0; i < NVW; ++i) {
+      float o[VN], rs[VN];
+      cur.rs[i].unpack(rs);
+#pragma unroll
+      for (int k = 0; k < VN; ++k) o[k] = rstd * (dxh[i][k] - s1 - xh[i][k] * s2) + rs[k];
+      Vec<T> v; v.pack(o);
+      span_store<T>(v, ro, (uint32_t)(i * 256 + threadIdx.x) * 16);
+    }
+  };
+  if ((int64_t)blockIdx.x < rows) {
+    RowRaw qa, qb;
+    int64_t r = blockIdx.x;
+    fetch(qa, r);
+    {
+      const __amdgpu_buffer_rsrc_t none = span_rsrc(dx, 0u);
+      Vec<T> z; float zf[VN];
+#pragma unroll
+      for (int k = 0; k < VN; ++k) zf[k] = 0.f;
+      z.pack(zf);
+#pragma unroll
+      for (int i = 0; i < NVW; ++i) span_store<T>(z, none, (uint32_t)i * 16);   // distinct offsets: identical stores would be merged
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    do {
+      fetch(qb, r + step);
+      work(qa, r, 0);
+      fetch(qa, r + 2 * step);
+      work(qb, r + step, 1);
+      r += 2 * step;
+    } while (r < rows);
   }
   float* outp = partials + (int64_t)blockIdx.x * 2 * H;
 #pragma unroll
@@ -1108,116 +1269,137 @@ __global__ void __launch_bounds__(256) xent_kernel(T* __restrict__ logits, int64
 // The same operation with each row held in registers between the two passes, so that the logits cross the
 // memory system once in each direction (the two-pass kernel above reads them twice: a row of 100 KB times the
 // rows in flight is far beyond the L2).  One block of 1024 threads per CU walks rows blockIdx.x, + gridDim.x, ...;
-// a thread owns vectors tid, tid + 1024, ... of the row (at most NV).  The next row's loads are issued before
-// the block-wide reduction of the current one and stay in flight through its second pass.
+// a thread owns vectors tid, tid + 1024, ... of the row: exactly NV of them, so that only the last can hold columns
+// past V (the launcher checks (NV - 1) * 1024 vectors <= V columns).  The row loop is built like the norm kernels':
+// rows in pairs in a body without a branch, two register sets, all accesses through row descriptors, so that the
+// next row's loads and the previous row's stores stay in flight while a row is worked on.  For that reason a row
+// without a prediction is not skipped: its sums are formed and its gradient is scaled by zero.
 template <typename T, int NV>
 __global__ void __launch_bounds__(1024) xent_row_kernel(T* __restrict__ logits, int64_t ld, int V, int64_t rows,
                                                          const int32_t* __restrict__ targets, int64_t tgt_ld, int S,
                                                          float loss_scale, float* __restrict__ row_loss) {
   constexpr int VN = Vec<T>::N;
-  const int nvec = (int)(ld / VN);
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  __shared__ float smx[2][16], ssum[2][16], stl[2];
-  Vec<T> cur[NV], nxt[NV];
-  auto fetch = [&](Vec<T>* dst, int64_t t) __attribute__((always_inline)) {
-    const T* row = logits + t * ld;
+  constexpr float L2E = 1.4426950408889634f;
+  const int wv = threadIdx.x >> 6;
+  const uint32_t row_bytes = (uint32_t)ld * sizeof(T);
+  __shared__ float smx[2][16], ssum[2][16], stl[2], junk[64];
+  const int64_t step = gridDim.x;
+  auto fetch = [&](Vec<T> (&q)[NV], int64_t t) __attribute__((always_inline)) {
+    const bool have = t < rows;
+    const __amdgpu_buffer_rsrc_t rs = span_rsrc(logits + (have ? t : 0) * ld, have ? row_bytes : 0u);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) span_load<T, 2>(q[j], rs, (uint32_t)(threadIdx.x + j * 1024) * 16);   // streamed once in each direction: non-temporal
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto work = [&](Vec<T> (&q)[NV], int64_t t, int par) __attribute__((always_inline)) {
+    const bool have = t < rows;
+    const int64_t tt = have ? t : 0;
+    const uint32_t ts = (uint32_t)tt / (uint32_t)S;   // rows fit 32 bits (the launcher checks): a 64-bit division would bring a branch into the loop
+    int tgt = targets[(int64_t)ts * tgt_ld + ((uint32_t)tt - ts * (uint32_t)S)];
+    if (tgt >= V || !have) tgt = -1;   // a class that does not exist is treated like a position without a prediction
+    const int tv = tgt >= 0 ? tgt / VN : -1;
+    // columns past V in the row's last vector (and whole vectors past the row's end, which read as zeros) count as
+    // minus infinity: they drop out of the maximum and the sum and come out of the last pass as zeros
+    {
+      float f[VN];
+      q[NV - 1].unpack(f);
+      const int c0 = (int)(threadIdx.x + (NV - 1) * 1024) * VN;
+#pragma unroll
+      for (int k = 0; k < VN; ++k) f[k] = c0 + k < V ? f[k] : -INFINITY;
+      q[NV - 1].pack(f);
+    }
+    // this thread's share of max and sum; exponentials in the base-2 domain (one fma + v_exp_f32 each); the vector
+    // that holds the target logit is kept aside on the way
+    float mx = -INFINITY, sum = 0.f;
+    Vec<T> hit = q[0];
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-      const int i = threadIdx.x + j * 1024;
-      // streamed once in each direction: non-temporal accesses
-      if (i < nvec) dst[j].raw = __builtin_bit_cast(decltype(dst[j].raw), __builtin_nontemporal_load(reinterpret_cast<const nt_f4*>(row + (int64_t)i * VN)));
-    }
-  };
-  int64_t t = blockIdx.x;
-  if (t < rows) fetch(cur, t);
-  for (int par = 0; t < rows; t += gridDim.x, par ^= 1) {
-    T* row = logits + t * ld;
-    int tgt = targets[(t / S) * tgt_ld + (t % S)];
-    if (tgt >= V) tgt = -1;   // a class that does not exist is treated like a position without a prediction, never read
-    // this thread's share of max and sum; exponentials in the base-2 domain (one fma + v_exp_f32 each); only a
-    // row's last vectors can hold padding columns, the others skip the column test
-    constexpr float L2E = 1.4426950408889634f;
-    float mx = -INFINITY, sum = 0.f;
-    if (tgt >= 0) {
+      float f[VN];
+      q[j].unpack(f);
 #pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        const int i = threadIdx.x + j * 1024;
-        if (i < nvec) {
-          float f[VN];
-          cur[j].unpack(f);
-          if (i * VN + VN <= V) {
-#pragma unroll
-            for (int k = 0; k < VN; ++k) mx = fmaxf(mx, f[k]);
-          } else {
-#pragma unroll
-            for (int k = 0; k < VN; ++k) if (i * VN + k < V) mx = fmaxf(mx, f[k]);
-          }
-        }
-      }
-      const float m2 = mx * L2E;
-#pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        const int i = threadIdx.x + j * 1024;
-        if (i < nvec) {
-          float f[VN];
-          cur[j].unpack(f);
-          if (i * VN + VN <= V) {
-#pragma unroll
-            for (int k = 0; k < VN; ++k) sum += __builtin_amdgcn_exp2f(fmaf(f[k], L2E, -m2));
-          } else {
-#pragma unroll
-            for (int k = 0; k < VN; ++k) if (i * VN + k < V) sum += __builtin_amdgcn_exp2f(fmaf(f[k], L2E, -m2));
-          }
-        }
+      for (int k = 0; k < VN; ++k) mx = fmaxf(mx, f[k]);
+      if (j > 0) {
+        const bool mine = (int)(threadIdx.x + j * 1024) == tv;
+        hit.raw.x = mine ? q[j].raw.x : hit.raw.x; hit.raw.y = mine ? q[j].raw.y : hit.raw.y;
+        hit.raw.z = mine ? q[j].raw.z : hit.raw.z; hit.raw.w = mine ? q[j].raw.w : hit.raw.w;
       }
     }
-    const int64_t tn = t + gridDim.x;
-    if (tn < rows) fetch(nxt, tn);
+    const float m2 = mx * L2E;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      float f[VN];
+      q[j].unpack(f);
+#pragma unroll
+      for (int k = 0; k < VN; ++k) sum += __builtin_amdgcn_exp2f(fmaf(f[k], L2E, -m2));
+    }
     const float wm = wave_max(mx);
     sum = (mx == -INFINITY) ? 0.f : sum * __expf(mx - wm);
     sum = wave_sum(sum);
-    if (lane == 0) { smx[par][wv] = wm; ssum[par][wv] = sum; }
-    // the target logit is read (and has arrived) before the barrier, its owner overwrites it after
-    if (threadIdx.x == 0) stl[par] = tgt >= 0 ? to_float<T>(row[tgt]) : 0.f;
-    __syncthreads();   // one barrier per row: the LDS slots alternate, a wave two rows ahead is impossible
-    float lse = 0.f;
-    if (tgt >= 0) {
-      float bm = -INFINITY;
+    smx[par][wv] = wm; ssum[par][wv] = sum;   // every lane writes the same two values: no branch in the row loop
+    float own_tl; bool is_owner;
+    {
+      // the thread whose vectors include the target's puts the logit where thread 0 finds it; the others write aside
+      float f[VN];
+      hit.unpack(f);
+      float tl = f[0];
 #pragma unroll
-      for (int w = 0; w < 16; ++w) bm = fmaxf(bm, smx[par][w]);
-      float bs = 0.f;
-#pragma unroll
-      for (int w = 0; w < 16; ++w) bs += (smx[par][w] == -INFINITY) ? 0.f : ssum[par][w] * __expf(smx[par][w] - bm);
-      lse = bm + logf(bs);
+      for (int k = 1; k < VN; ++k) tl = (tgt % VN) == k ? f[k] : tl;
+      const bool owner = tv >= 0 && (tv & 1023) == (int)threadIdx.x;
+      float* dst = owner ? &stl[par] : &junk[threadIdx.x & 63];
+      *dst = tl;
+      own_tl = tl; is_owner = owner;
     }
-    if (threadIdx.x == 0) row_loss[t] = tgt >= 0 ? lse - stl[par] : 0.f;
+    block_sync_lds();   // one barrier per row: the LDS slots alternate, a wave two rows ahead is impossible
+    float bm = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) bm = fmaxf(bm, smx[par][w]);
+    float bs = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) bs += (smx[par][w] == -INFINITY) ? 0.f : ssum[par][w] * __expf(smx[par][w] - bm);
+    const float lse = bm + logf(bs);
+    span_store_f1((lse - stl[par]) * (tgt >= 0 ? 1.f : 0.f), span_rsrc(row_loss + tt, have ? 4u : 0u), (uint32_t)threadIdx.x * 4);
     const float l2 = lse * L2E;
     const float scale = tgt >= 0 ? loss_scale : 0.f;   // a row without a prediction gets zeros
-    const int tv = tgt >= 0 ? tgt / VN : -1;
+    const __amdgpu_buffer_rsrc_t ro = span_rsrc(logits + tt * ld, have ? row_bytes : 0u);
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-      const int i = threadIdx.x + j * 1024;
-      if (i < nvec) {
-        float f[VN];
-        cur[j].unpack(f);
-        if (i * VN + VN <= V) {
+      float f[VN];
+      q[j].unpack(f);
 #pragma unroll
-          for (int k = 0; k < VN; ++k) f[k] = __builtin_amdgcn_exp2f(fmaf(f[k], L2E, -l2)) * scale;
-        } else {
-#pragma unroll
-          for (int k = 0; k < VN; ++k) f[k] = i * VN + k < V ? __builtin_amdgcn_exp2f(fmaf(f[k], L2E, -l2)) * scale : 0.f;
-        }
-        if (i == tv) {
-#pragma unroll
-          for (int k = 0; k < VN; ++k) if (k == tgt % VN) f[k] -= scale;
-        }
-        Vec<T> o; o.pack(f);
-        __builtin_nontemporal_store(__builtin_bit_cast(nt_f4, o.raw), reinterpret_cast<nt_f4*>(row + (int64_t)i * VN));
-      }
+      for (int k = 0; k < VN; ++k) f[k] = __builtin_amdgcn_exp2f(fmaf(f[k], L2E, -l2)) * scale;
+      Vec<T> o; o.pack(f);
+      span_store<T, 2>(o, ro, (uint32_t)(threadIdx.x + j * 1024) * 16);
     }
+    // the target's entry is softmax - 1: its owner stores that one value again, after the vector that holds it (same
+    // thread, same address: in order), formed in float and rounded once; every other lane's offset points past the row
+    const T fix = from_float<T>(__builtin_amdgcn_exp2f(fmaf(own_tl, L2E, -l2)) * scale - scale);
+    static_assert(sizeof(T) == 2, "one 16-bit store");
+    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, fix), ro, (int)(is_owner ? (uint32_t)tgt * 2u : row_bytes), 0, 2);
+  };
+  Vec<T> qa[NV], qb[NV];
+  int64_t t = blockIdx.x;   // the launcher starts no more blocks than there are rows
+  fetch(qa, t);
+  {
+    // a row's worth of stores to nowhere: the loop is entered with the operations in flight it is re-entered with
+    const __amdgpu_buffer_rsrc_t none = span_rsrc(logits, 0u);
+    Vec<T> z; float zf[VN];
 #pragma unroll
-    for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
+    for (int k = 0; k < VN; ++k) zf[k] = 0.f;
+    z.pack(zf);
+    span_store_f1(0.f, none, 0u);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) span_store<T, 2>(z, none, (uint32_t)j * 16);   // distinct offsets: identical stores would be merged
+    __builtin_amdgcn_raw_buffer_store_b16((short)0, none, 0, 0, 2);
+    __builtin_amdgcn_sched_barrier(0);
   }
+  do {
+    fetch(qb, t + step);
+    work(qa, t, 0);
+    fetch(qa, t + 2 * step);
+    work(qb, t + step, 1);
+    t += 2 * step;
+  } while (t < rows);
 }
 
 __global__ void __launch_bounds__(1024) loss_sum_kernel(const float* __restrict__ row_loss, int64_t n, float scale, float* __restrict__ loss) {
@@ -1247,7 +1429,8 @@ int xent_fwd_bwd(hipStream_t s, int dtype, int64_t T_, int V, int64_t ld, void* 
   const int VN = dtype == POPLAR_BF16 ? 8 : 4;
   if (ld % VN || ld < V) return poplar_fail(POPLAR_ERR_INVALID, "logit row stride %lld invalid for V=%d", (long long)ld, V);
   const int64_t nvec = ld / VN;
-  if (dtype == POPLAR_BF16 && nvec <= 8 * 1024) {
+  const int nv = (int)cdiv(nvec, 1024);
+  if (dtype == POPLAR_BF16 && nv <= 8 && (int64_t)(nv - 1) * 1024 * VN <= V && T_ < (1ll << 31)) {
     static int cus = 0;   // one block per CU (1024 threads with the row in registers fill it)
     if (!cus) {
       int dev = 0;
@@ -1255,10 +1438,13 @@ int xent_fwd_bwd(hipStream_t s, int dtype, int64_t T_, int V, int64_t ld, void* 
       POPLAR_CHECK_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     }
     const dim3 grid((unsigned)std::min<int64_t>(T_, cus));
-    if (nvec <= 4 * 1024)
-      hipLaunchKernelGGL((xent_row_kernel<bf16, 4>), grid, dim3(1024), 0, s, (bf16*)logits, ld, V, T_, targets, tgt_ld, S, loss_scale, row_loss);
-    else
-      hipLaunchKernelGGL((xent_row_kernel<bf16, 8>), grid, dim3(1024), 0, s, (bf16*)logits, ld, V, T_, targets, tgt_ld, S, loss_scale, row_loss);
+#define XENT_ROW_CASE(NVV) \
+  case NVV: hipLaunchKernelGGL((xent_row_kernel<bf16, NVV>), grid, dim3(1024), 0, s, (bf16*)logits, ld, V, T_, targets, tgt_ld, S, loss_scale, row_loss); break
+    switch (nv) {
+      XENT_ROW_CASE(1); XENT_ROW_CASE(2); XENT_ROW_CASE(3); XENT_ROW_CASE(4);
+      XENT_ROW_CASE(5); XENT_ROW_CASE(6); XENT_ROW_CASE(7); XENT_ROW_CASE(8);
+    }
+#undef XENT_ROW_CASE
   } else {
     DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(xent_kernel<T>, dim3((unsigned)T_), dim3(256), 0, s, (T*)logits, ld, V, targets, tgt_ld, S, loss_scale, row_loss));
   }

@@ -277,11 +277,13 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   // gathers flat range [lo, hi) into the staging buffer first
   auto params_at = [&](int64_t lo, int64_t hi, char* dst, std::vector<Span>& spans, const void** p) -> int {
     if (stage < 3) { *p = (const char*)st.params + lo * es; return POPLAR_OK; }
+    // the span's two events ride on the launch: kernel start to kernel end, no packet between kernels
     Span sn;
-    POPLAR_TRY(ev.mark(&sn.a));
-    POPLAR_TRY(zero3_gather_local(s, c.dtype, dst, st.own_shard, st.params, lo, hi, sh_off, sh_len));
-    POPLAR_TRY(ev.mark(&sn.b));
-    spans.push_back(sn);
+    int launched = 0;
+    POPLAR_TRY(ctx_take(ctx, &sn.a));
+    POPLAR_TRY(ctx_take(ctx, &sn.b));
+    POPLAR_TRY(zero3_gather_local(s, c.dtype, dst, st.own_shard, st.params, lo, hi, sh_off, sh_len, sn.a, sn.b, &launched));
+    if (launched) spans.push_back(sn);
     *p = dst;
     return POPLAR_OK;
   };
@@ -290,10 +292,11 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   auto reduce_unit = [&](const float* g_unit, int64_t lo, int64_t hi) -> int {
     if (stage < 2) return POPLAR_OK;
     Span sn;
-    POPLAR_TRY(ev.mark(&sn.a));
-    POPLAR_TRY(zero2_reduce_local(s, st.grads, g_unit, lo, hi, sh_off, sh_len));
-    POPLAR_TRY(ev.mark(&sn.b));
-    sp_red.push_back(sn);
+    int launched = 0;
+    POPLAR_TRY(ctx_take(ctx, &sn.a));
+    POPLAR_TRY(ctx_take(ctx, &sn.b));
+    POPLAR_TRY(zero2_reduce_local(s, st.grads, g_unit, lo, hi, sh_off, sh_len, sn.a, sn.b, &launched));
+    if (launched) sp_red.push_back(sn);   // a unit outside the shard moves nothing: no span
     return POPLAR_OK;
   };
 
