@@ -31,6 +31,7 @@
 // max / sum / rescale of a query inside one lane (plus one exchange between the
 // two lane halves).  dK/dV works on S = Q K^T (lane = key).
 #include <hip/hip_ext.h>
+#include <type_traits>
 #include "device_utils.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -43,6 +44,8 @@ typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 #define LOG2E 1.4426950408889634f
+// LDS stages of the two backward kernels: three at either head dim (48 or 96-102 KB of the CU's 160)
+#define FA_BWD_STAGES 3
 #define FA_OOB 0xfffffff0u
 
 __device__ inline bf16x8 as_frag(uint4 v) { return *reinterpret_cast<bf16x8*>(&v); }
@@ -151,6 +154,40 @@ __device__ inline void fa_wait_lds() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// Four floats from LDS, written as assembly for the same reason as the transposing reads: the statistics tile is
+// filled by direct loads, and the compiler would wait for every such load in flight (the next tile's) before a read
+// of it that it can see.  Same invariant: used only after a later fa_wait_lds(), and always used.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+__device__ inline floatx4 lds_read_f4(const float* p) {
+  floatx4 v;
+  const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(a));
+  return v;
+}
+
+// Two chains of MFMAs over the D/16 k-slices of two LDS tiles (rows `row` of each, as A operands) against two sets of
+// B fragments held in registers: acc0 += A0 B0^T, acc1 += A1 B1^T.  The A fragments are requested AHEAD MFMAs ahead of
+// their use (three is where the gain ends; one costs 15 %) and the order is pinned: left to itself the compiler issues each read right before its MFMA (it keeps the
+// register count down), and every MFMA then waits out an LDS round trip.
+template <int D, int AHEAD = 3>
+__device__ inline void mfma_two_chains(floatx16& acc0, floatx16& acc1, const char* lds0, const char* lds1, int row, int g,
+                                       const bf16x8* b0, const bf16x8* b1) {
+  typedef Rows64<D> Img;
+  constexpr int N = D / 8;
+  auto frag = [&](int n) { return (n & 1) ? Img::frag(lds1, row, n >> 1, g) : Img::frag(lds0, row, n >> 1, g); };
+  bf16x8 fa[AHEAD + 1];
+#pragma unroll
+  for (int n = 0; n < AHEAD; ++n) fa[n] = frag(n);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int n = 0; n < N; ++n) {
+    if (n + AHEAD < N) fa[(n + AHEAD) % (AHEAD + 1)] = frag(n + AHEAD);
+    if (n & 1) acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[n % (AHEAD + 1)], b1[n >> 1], acc1, 0, 0, 0);
+    else acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[n % (AHEAD + 1)], b0[n >> 1], acc0, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 // B fragments of one row of a [*, ld] matrix kept in registers: D/16 slices
 template <int D>
 __device__ inline void load_row_frags(bf16x8* f, const bf16* __restrict__ p, int64_t ld, int row, int rlim, int g) {
@@ -189,6 +226,15 @@ __device__ inline uint32_t records_from(int64_t rows_total, int64_t row0, int64_
   return bytes < (int64_t)FA_OOB ? (uint32_t)bytes : FA_OOB;
 }
 
+// Block id -> (sequence and head, tile): tile by tile over all heads, `t` counting a head's tiles in the order they
+// should start (the callers put the longest first, so that the grid ends on its shortest blocks).  Orders that keep
+// the blocks of a few heads together on an XCD, so that its L2 serves their shared K / V (or Q / dO) tiles, were
+// measured and are slower at every group size: the blocks that run at one time then differ in length.
+__device__ inline void fa_block_map(int bid, int heads, int tiles, int* head, int* t) {
+  *head = bid % heads;
+  *t = bid / heads;
+}
+
 // =============================================================================
 // forward
 // =============================================================================
@@ -202,9 +248,10 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const b
   const int64_t ld = 3 * (int64_t)H;
   const int qtiles = (S + 127) / 128;
   // longest blocks first over the whole grid (late query tiles see the most keys): the last blocks to start are the shortest
-  const int qt = qtiles - 1 - (int)(blockIdx.x / ((int64_t)B * nh));
-  const int h = (int)(blockIdx.x % nh);
-  const int b = (int)((blockIdx.x / nh) % B);
+  int bh, tq;
+  fa_block_map((int)blockIdx.x, B * nh, qtiles, &bh, &tq);
+  const int qt = qtiles - 1 - tq;   // late query tiles see the most keys
+  const int h = bh % nh, b = bh / nh;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, g = lane >> 5;
   const int q0 = qt * 128;
@@ -245,7 +292,9 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const b
     // this wave's part of the current tile has landed (loads complete in order; with three stages the next tile's may be pending)
     if (NS == 3 && kv0 + 64 < kv_end) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
     else __builtin_amdgcn_s_waitcnt(0x0f70);
-    __syncthreads();
+    // every wave's part of the tile has landed and its LDS reads of the stage that is filled next have returned; no
+    // fence over global memory, which would wait for the tile that is meant to stay in flight
+    block_sync_lds();
     char* cur = lds + sc * 2 * Img::BYTES;
     if (kv0 + 64 * (NS - 1) < kv_end) issue(lds + (sc == 0 ? NS - 1 : sc - 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + NS - 1) * tile_step);
     const char* k_lds = cur;
@@ -336,19 +385,20 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const b
 // backward, dQ: block = 128 queries, loop over key tiles (S^T form, lane = query)
 // =============================================================================
 template <int D>
-__global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
+__global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
                                                             const bf16* __restrict__ dout, const float* __restrict__ lse,
                                                             float* __restrict__ delta, bf16* __restrict__ dqkv, int B, int S, int nh,
                                                             int causal, float scale) {
   typedef Rows64<D> Img;
-  constexpr int NS = D == 64 ? 3 : 2;   // LDS stages: tiles t+1 .. t+NS-1 are in flight while tile t is used
+  constexpr int NS = D == 64 ? 3 : 2;     // LDS stages: tiles t+1 .. t+NS-1 are in flight while tile t is used
   __shared__ __attribute__((aligned(1024))) char lds[NS * 2 * Img::BYTES];   // [stage][K | V]
   const int H = nh * D;
   const int64_t ld = 3 * (int64_t)H;
   const int qtiles = (S + 127) / 128;
-  const int qt = qtiles - 1 - (int)(blockIdx.x / ((int64_t)B * nh));   // longest blocks first over the whole grid
-  const int h = (int)(blockIdx.x % nh);
-  const int b = (int)((blockIdx.x / nh) % B);
+  int bh, tq;
+  fa_block_map((int)blockIdx.x, B * nh, qtiles, &bh, &tq);
+  const int qt = qtiles - 1 - tq;   // late query tiles see the most keys
+  const int h = bh % nh, b = bh / nh;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, g = lane >> 5;
   const int q0 = qt * 128;
@@ -357,15 +407,20 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(cons
   const uint32_t recs = records_from((int64_t)B * S, (int64_t)b * S, ld, D);
   const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc((void*)(base + H), 0, recs, 0x00020000);
   const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void*)(base + 2 * H), 0, recs, 0x00020000);
-  uint32_t off[Img::PER_WAVE];
-#pragma unroll
-  for (int i = 0; i < Img::PER_WAVE; ++i) off[i] = Img::lane_offset(wave + 4 * i, lane, ld);
+  // this lane's offset in the wave's first load of a tile; the wave's further loads lie whole rows further on (a
+  // multiple of 16 rows, which leaves the swizzle as it is).  One register instead of one per load: the sums are
+  // formed where they are used (the empty statement keeps the compiler from forming them once, before the loop, and
+  // holding or spilling them)
+  const uint32_t off0 = Img::lane_offset(wave, lane, ld);
+  const uint32_t load_step = (uint32_t)(4 * Img::RPL * ld * 2);
   const uint32_t tile_step = (uint32_t)(64 * ld * 2);
   auto issue = [&](char* st, uint32_t tile_off) {
+    uint32_t o = off0 + tile_off;
+    asm volatile("" : "+v"(o));
 #pragma unroll
     for (int i = 0; i < Img::PER_WAVE; ++i) {
-      fa_load_kib(rk, st + (wave + 4 * i) * 1024, off[i] + tile_off);
-      fa_load_kib(rv, st + Img::BYTES + (wave + 4 * i) * 1024, off[i] + tile_off);
+      fa_load_kib(rk, st + (wave + 4 * i) * 1024, o + i * load_step);
+      fa_load_kib(rv, st + Img::BYTES + (wave + 4 * i) * 1024, o + i * load_step);
     }
   };
 
@@ -401,30 +456,32 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(cons
   for (int kv0 = 0; kv0 < kv_end; kv0 += 64, sc = sc == NS - 1 ? 0 : sc + 1) {
     if (NS == 3 && kv0 + 64 < kv_end) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
     else __builtin_amdgcn_s_waitcnt(0x0f70);
-    __syncthreads();
+    // every wave's part of the tile has landed and its LDS reads of the stage that is filled next have returned; no
+    // fence over global memory, which would wait for the tile that is meant to stay in flight
+    block_sync_lds();
     char* cur = lds + sc * 2 * Img::BYTES;
     if (kv0 + 64 * (NS - 1) < kv_end) issue(lds + (sc == 0 ? NS - 1 : sc - 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + NS - 1) * tile_step);
     const char* k_lds = cur;
     const char* v_lds = cur + Img::BYTES;
     // K^T fragments of the first 32 keys: issued now, they return behind the MFMAs and the exponentials
-    bf16x8 kt[2][2][D / 32];
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-      for (int ct = 0; ct < D / 32; ++ct) kt[0][jj][ct] = Img::frag_tr(k_lds, trb[ct], jj);
-    __builtin_amdgcn_sched_barrier(0);
-    // 32 keys at a time, through to dQ: half the score registers of a whole-tile pass
+    bf16x8 kt[2][D / 32];   // K^T fragments of one half (two 16-key chunks)
+    // 32 keys at a time, through to dQ: half the score registers of a whole-tile pass.  A half's K^T fragments are
+    // requested at its start and return behind its MFMAs and exponentials; one set of registers for them and two LDS
+    // stages keep the kernel within 256 registers at head dim 128, which is worth more than either: the MFMAs then write
+    // ordinary registers (with more than 256 the compiler puts every MFMA result into accumulation registers and
+    // copies each score out and in around the vector arithmetic), and two blocks share a CU.
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int ct = 0; ct < D / 32; ++ct) kt[jj][ct] = Img::frag_tr(k_lds, trb[ct], 2 * u + jj);
+      __builtin_amdgcn_sched_barrier(0);
       floatx16 st, dpt;
       zero_acc(st);
       zero_acc(dpt);
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s) {
-        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(k_lds, u * 32 + lr, s, g), qf[s], st, 0, 0, 0);
-        dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(v_lds, u * 32 + lr, s, g), dof[s], dpt, 0, 0, 0);
-      }
+      mfma_two_chains<D, D == 64 ? 3 : 2>(st, dpt, k_lds, v_lds, u * 32 + lr, g, qf, dof);
       if ((causal && kv0 + 63 > q0 + wave * 32) || kv0 + 64 > S || q0 + 128 > S) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -442,19 +499,12 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 1) flash_bwd_dq_kernel(cons
       }
       // dQ^T += K^T dS^T
       fa_wait_lds();
-      if (u == 0) {
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-          for (int ct = 0; ct < D / 32; ++ct) kt[1][jj][ct] = Img::frag_tr(k_lds, trb[ct], 2 + jj);
-        __builtin_amdgcn_sched_barrier(0);
-      }
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const bf16x8 dsb = regs_to_frag(st, jj);
 #pragma unroll
         for (int ct = 0; ct < D / 32; ++ct)
-          dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt[u][jj][ct], dsb, dq[ct], 0, 0, 0);
+          dq[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt[jj][ct], dsb, dq[ct], 0, 0, 0);
       }
     }
   }
@@ -470,14 +520,14 @@ __global__ void __launch_bounds__(256, D == 64 ? 2 : 1) flash_bwd_dkv_kernel(con
                                                              bf16* __restrict__ dqkv, int B, int S, int nh, int causal, float scale) {
   typedef Rows64<D> Img;
   constexpr int STAGE = 2 * Img::BYTES + 2048;   // Q | dO | lse2 (first 256 bytes of a KiB) | delta (first 256 bytes of a KiB)
-  constexpr int NS = D == 64 ? 3 : 2;
+  constexpr int NS = FA_BWD_STAGES;
   __shared__ __attribute__((aligned(1024))) char lds[NS * STAGE];
   const int H = nh * D;
   const int64_t ld = 3 * (int64_t)H;
   // longest blocks first over the whole grid: with the causal mask early key tiles see the most queries
-  const int ktile = (int)(blockIdx.x / ((int64_t)B * nh));
-  const int h = (int)(blockIdx.x % nh);
-  const int b = (int)((blockIdx.x / nh) % B);
+  int bh, ktile;   // with the causal mask early key tiles see the most queries: they come first as they are
+  fa_block_map((int)blockIdx.x, B * nh, (S + 127) / 128, &bh, &ktile);
+  const int h = bh % nh, b = bh / nh;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, g = lane >> 5;
   const int kvb = ktile * 128;
@@ -530,7 +580,9 @@ __global__ void __launch_bounds__(256, D == 64 ? 2 : 1) flash_bwd_dkv_kernel(con
   for (int q0 = q_begin; q0 < S; q0 += 64, sc = sc == NS - 1 ? 0 : sc + 1) {
     if (NS == 3 && q0 + 64 < S) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
     else __builtin_amdgcn_s_waitcnt(0x0f70);
-    __syncthreads();
+    // every wave's part of the tile has landed and its LDS reads of the stage that is filled next have returned; no
+    // fence over global memory, which would wait for the tile that is meant to stay in flight
+    block_sync_lds();
     char* cur = lds + sc * STAGE;
     if (q0 + 64 * (NS - 1) < S) issue(lds + (sc == 0 ? NS - 1 : sc - 1) * STAGE, q0 + 64 * (NS - 1));
     const char* q_lds = cur;
@@ -554,34 +606,30 @@ __global__ void __launch_bounds__(256, D == 64 ? 2 : 1) flash_bwd_dkv_kernel(con
       floatx16 sm, dp;
       zero_acc(sm);
       zero_acc(dp);
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s) {
-        sm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(q_lds, u * 32 + lr, s, g), kf[s], sm, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(do_lds, u * 32 + lr, s, g), vf[s], dp, 0, 0, 0);
-      }
-      // statistics of this lane's 16 queries: four runs of four consecutive floats each, read whole before either
-      // path (a read inside the masked path's select would turn every element into a branch around an LDS access)
-      float4 l4[4], d4[4];
+      // statistics of this lane's 16 queries: four runs of four consecutive floats each, requested before the MFMAs
+      floatx4 l4[4], d4[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        l4[r] = *reinterpret_cast<const float4*>(lse_lds + u * 32 + r * 8 + g * 4);
-        d4[r] = *reinterpret_cast<const float4*>(delta_lds + u * 32 + r * 8 + g * 4);
+        l4[r] = lds_read_f4(lse_lds + u * 32 + r * 8 + g * 4);
+        d4[r] = lds_read_f4(delta_lds + u * 32 + r * 8 + g * 4);
       }
+      mfma_two_chains<D>(sm, dp, q_lds, do_lds, u * 32 + lr, g, kf, vf);
+      fa_wait_lds();   // the statistics (the transposed fragments too: all LDS reads return in order)
       if ((causal && q0 < kvb + wave * 32 + 31) || q0 + 64 > S || kvb + 128 > S) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int qq = q0 + u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
           const bool ok = qq < S && kv < S && (!causal || kv <= qq);
-          const float e = fast_exp2(__builtin_fmaf(sm[i], c2, -f4_at(l4[i >> 2], i & 3)));
+          const float e = fast_exp2(__builtin_fmaf(sm[i], c2, -l4[i >> 2][i & 3]));
           const float p = ok ? e : 0.f;
-          dp[i] = p * (dp[i] - f4_at(d4[i >> 2], i & 3));   // dS
+          dp[i] = p * (dp[i] - d4[i >> 2][i & 3]);   // dS
           sm[i] = p;                                          // P
         }
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const float p = fast_exp2(__builtin_fmaf(sm[i], c2, -f4_at(l4[i >> 2], i & 3)));
-          dp[i] = p * (dp[i] - f4_at(d4[i >> 2], i & 3));
+          const float p = fast_exp2(__builtin_fmaf(sm[i], c2, -l4[i >> 2][i & 3]));
+          dp[i] = p * (dp[i] - d4[i >> 2][i & 3]);
           sm[i] = p;
         }
       }

@@ -3,6 +3,7 @@
 // backward, column sums (bias gradients), SwiGLU, RoPE, embedding, and the
 // softmax cross-entropy.  All use 16-byte accesses per lane and 64-lane
 // wavefront reductions; math is float whatever the storage type.
+#include <hip/hip_ext.h>
 #include "device_utils.h"
 #include <algorithm>
 
