@@ -301,13 +301,10 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const b
     const char* v_lds = cur + Img::BYTES;
     // S^T tiles: rows = keys kv0 + u*32 + .., cols = this wave's queries
     floatx16 st[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      zero_acc(st[u]);
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s)
-        st[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Img::frag(k_lds, u * 32 + lr, s, g), qf[s], st[u], 0, 0, 0);
-    }
+    zero_acc(st[0]);
+    zero_acc(st[1]);
+    // keys 0-31 and 32-63 of the tile as two chains against the same Q fragments (32 rows further on the swizzle repeats)
+    mfma_two_chains<D, 3>(st[0], st[1], k_lds, k_lds + 32 * Img::ROWB, lr, g, qf, qf);
     // V^T fragments, PF 16-row chunks at a time: the first group is issued now and returns behind the
     // softmax arithmetic, each later group behind the MFMAs of the one before
     constexpr int PF = D == 64 ? 2 : 1;
