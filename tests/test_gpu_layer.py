@@ -147,8 +147,19 @@ def test_embedding_fwd_bwd(arch, dtype):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("arch,V", [("gpt", 211), ("llama", 256), ("gpt", 1031), ("llama", 20011), ("gpt", 50257), ("llama", 70001)])
 def test_head_loss_fwd_bwd(arch, V, dtype):
-    B, S, H = 2, 48, 128
-    cfg = pb.make_cfg(arch=arch, L=1, H=H, nh=2, F=128, S=S, V=V, dtype=dtype)
+    check_head_loss(arch, V, dtype, 2, 48, 128)
+
+
+# Row counts that make the row kernels (final norm forward / backward, loss) walk several rows per wave or block, with
+# an odd count so that the last pair of rows is half empty; hidden 128 takes the wave-per-row norm kernels, 1152 the
+# block-per-row backward; the vocabularies give the loss kernel 1, 2 and 3 vectors per thread.
+@pytest.mark.parametrize("arch,V,H", [("gpt", 1031, 128), ("llama", 9001, 128), ("gpt", 20011, 1152)])
+def test_head_loss_over_many_rows(arch, V, H):
+    check_head_loss(arch, V, "bf16", 5, 379, H)
+
+
+def check_head_loss(arch, V, dtype, B, S, H):
+    cfg = pb.make_cfg(arch=arch, L=1, H=H, nh=H // 64, F=128, S=S, V=V, dtype=dtype)
     ctx = pb.Context(cfg)
     rng = np.random.default_rng(1)
     x = synth.activations((B, S, H), seed=5)
