@@ -452,7 +452,9 @@ def test_sampling_runs_warmup_and_repeats_and_reports_the_median_run():
 
 
 def test_two_searches_give_the_same_allocation():
-    model, world, stage = MODELS["gpt"], 4, 1
+    # a step long enough to be bound by the GPU rather than by the host's launch rate: on the tiny parity model one
+    # step is a quarter of a millisecond of launches, and two medians of five can differ by half of that
+    model, world, stage = dict(arch="gpt", L=2, H=768, nh=12, F=3072, S=256, V=2000), 4, 1
     probe = pb.make_cfg(**model, dtype="bf16", world=world, zero_stage=stage)
     cap = pb.step_accounted_bytes(probe, stage, 12) + 100
     rk = Rank(model, "bf16", stage, world, 0, max_batch=16, cap_bytes=cap)
