@@ -147,6 +147,20 @@ struct Rows64 {
 // component c (a constant after unrolling) of a float4
 __device__ inline float f4_at(const float4& v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
 
+// at most N vector-memory operations of this wave still in flight (they complete in order)
+template <int N>
+__device__ inline void fa_wait_vm() {
+  static_assert(N >= 0 && N < 64, "the counter has six bits");
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
+// The current tile has landed for this wave: `later` tiles (0 .. 2) were requested after it, each with PER_TILE loads
+template <int PER_TILE>
+__device__ inline void fa_wait_tile(int later) {
+  if (later >= 2) fa_wait_vm<2 * PER_TILE>();
+  else if (later == 1) fa_wait_vm<PER_TILE>();
+  else fa_wait_vm<0>();
+}
+
 // all LDS reads issued so far have returned; nothing moves across
 __device__ inline void fa_wait_lds() {
   __builtin_amdgcn_sched_barrier(0);
@@ -238,15 +252,23 @@ __device__ inline void fa_block_map(int bid, int heads, int tiles, int* head, in
 // =============================================================================
 // forward
 // =============================================================================
+// A block is WAVES waves of 32 queries each that share every K / V tile.  Four at either head dim: at head dim 128 two
+// such blocks share a CU and its LDS, which leaves two stages each, and the kernel waits for its tile loads a third
+// of its time (measured by taking the loads out); eight waves on one set of tiles (half the loads per CU, LDS for four
+// stages) were measured and are no faster in the forward pass and 16 % slower in dQ: under the causal mask the waves
+// of a block have unequal work, and with one block per CU nothing fills the SIMDs of those that are done.
 template <int D>
 __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
                                                          int B, int S, int nh, int causal, float scale) {
   typedef Rows64<D> Img;
-  constexpr int NS = D == 64 ? 3 : 2;   // LDS stages: tiles t+1 .. t+NS-1 are in flight while tile t is used
+  constexpr int WAVES = 4;
+  constexpr int QB = 32 * WAVES;            // queries per block
+  constexpr int NS = D == 64 ? 3 : 2;       // LDS stages: tiles t+1 .. t+NS-2 are in flight while tile t is used, t+NS-1 is requested
+  constexpr int PW = Img::LOADS / WAVES;    // a wave's loads per K tile (and per V tile)
   __shared__ __attribute__((aligned(1024))) char lds[NS * 2 * Img::BYTES];   // [stage][K | V]
   const int H = nh * D;
   const int64_t ld = 3 * (int64_t)H;
-  const int qtiles = (S + 127) / 128;
+  const int qtiles = (S + QB - 1) / QB;
   // longest blocks first over the whole grid (late query tiles see the most keys): the last blocks to start are the shortest
   int bh, tq;
   fa_block_map((int)blockIdx.x, B * nh, qtiles, &bh, &tq);
@@ -254,22 +276,23 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const b
   const int h = bh % nh, b = bh / nh;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, g = lane >> 5;
-  const int q0 = qt * 128;
+  const int q0 = qt * QB;
   const int q = q0 + wave * 32 + lr;
   const bf16* base = qkv + (int64_t)b * S * ld + h * D;   // row 0 of this sequence, q columns of head h
   // K and V tiles of this head: rows past the sequence are the next sequence's (finite, masked) or out of range (zero)
   const uint32_t recs = records_from((int64_t)B * S, (int64_t)b * S, ld, D);
   const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc((void*)(base + H), 0, recs, 0x00020000);
   const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void*)(base + 2 * H), 0, recs, 0x00020000);
-  uint32_t off[Img::PER_WAVE];
-#pragma unroll
-  for (int i = 0; i < Img::PER_WAVE; ++i) off[i] = Img::lane_offset(wave + 4 * i, lane, ld);
+  // this lane's offset in the wave's first load of a tile; its further loads lie WAVES * RPL rows further on (a multiple
+  // of 16 rows, which leaves the swizzle as it is)
+  const uint32_t off0 = Img::lane_offset(wave, lane, ld);
+  const uint32_t load_step = (uint32_t)(WAVES * Img::RPL * ld * 2);
   const uint32_t tile_step = (uint32_t)(64 * ld * 2);
   auto issue = [&](char* st, uint32_t tile_off) {
 #pragma unroll
-    for (int i = 0; i < Img::PER_WAVE; ++i) {
-      fa_load_kib(rk, st + (wave + 4 * i) * 1024, off[i] + tile_off);
-      fa_load_kib(rv, st + Img::BYTES + (wave + 4 * i) * 1024, off[i] + tile_off);
+    for (int i = 0; i < PW; ++i) {
+      fa_load_kib(rk, st + (wave + WAVES * i) * 1024, off0 + i * load_step + tile_off);
+      fa_load_kib(rv, st + Img::BYTES + (wave + WAVES * i) * 1024, off0 + i * load_step + tile_off);
     }
   };
 
@@ -281,22 +304,23 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_fwd_kernel(const b
   for (int ct = 0; ct < D / 32; ++ct) { zero_acc(oacc[ct]); trb[ct] = Img::tr_base(ct, lane); }
   float m_run = -INFINITY, l_run = 0.f;
   const float c2 = scale * LOG2E;
-  const int kv_end = causal ? min(S, q0 + 128) : S;
+  const int kv_end = causal ? min(S, q0 + QB) : S;
   const int qw0 = q0 + wave * 32;
 
-  constexpr int NLD = 2 * Img::PER_WAVE;   // loads of this wave per tile
-  issue(lds, 0);
-  if (NS == 3 && 64 < kv_end) issue(lds + 2 * Img::BYTES, tile_step);
+#pragma unroll
+  for (int j = 0; j < NS - 1; ++j)
+    if (j * 64 < kv_end) issue(lds + j * 2 * Img::BYTES, (uint32_t)j * tile_step);
   int sc = 0;   // stage of the current tile
   for (int kv0 = 0; kv0 < kv_end; kv0 += 64, sc = sc == NS - 1 ? 0 : sc + 1) {
-    // this wave's part of the current tile has landed (loads complete in order; with three stages the next tile's may be pending)
-    if (NS == 3 && kv0 + 64 < kv_end) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
-    else __builtin_amdgcn_s_waitcnt(0x0f70);
+    // this wave's part of the current tile has landed (loads complete in order; those of up to NS - 2 later tiles may be pending)
+    fa_wait_tile<2 * PW>(min(NS - 2, (kv_end - kv0 + 63) / 64 - 1));
     // every wave's part of the tile has landed and its LDS reads of the stage that is filled next have returned; no
-    // fence over global memory, which would wait for the tile that is meant to stay in flight
+    // fence over global memory, which would wait for the tiles that are meant to stay in flight
     block_sync_lds();
     char* cur = lds + sc * 2 * Img::BYTES;
     if (kv0 + 64 * (NS - 1) < kv_end) issue(lds + (sc == 0 ? NS - 1 : sc - 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + NS - 1) * tile_step);
+    // a tile that lies wholly behind this wave's queries under the causal mask adds nothing: the wave only keeps step
+    if (causal && kv0 > qw0 + 31) continue;
     const char* k_lds = cur;
     const char* v_lds = cur + Img::BYTES;
     // S^T tiles: rows = keys kv0 + u*32 + .., cols = this wave's queries
@@ -387,18 +411,21 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_bwd_dq_kernel(cons
                                                             float* __restrict__ delta, bf16* __restrict__ dqkv, int B, int S, int nh,
                                                             int causal, float scale) {
   typedef Rows64<D> Img;
-  constexpr int NS = D == 64 ? 3 : 2;     // LDS stages: tiles t+1 .. t+NS-1 are in flight while tile t is used
+  constexpr int WAVES = 4;                  // waves of 32 queries that share every K / V tile (see the forward kernel)
+  constexpr int QB = 32 * WAVES;
+  constexpr int NS = D == 64 ? 3 : 2;       // LDS stages
+  constexpr int PW = Img::LOADS / WAVES;    // a wave's loads per K tile (and per V tile)
   __shared__ __attribute__((aligned(1024))) char lds[NS * 2 * Img::BYTES];   // [stage][K | V]
   const int H = nh * D;
   const int64_t ld = 3 * (int64_t)H;
-  const int qtiles = (S + 127) / 128;
+  const int qtiles = (S + QB - 1) / QB;
   int bh, tq;
   fa_block_map((int)blockIdx.x, B * nh, qtiles, &bh, &tq);
   const int qt = qtiles - 1 - tq;   // late query tiles see the most keys
   const int h = bh % nh, b = bh / nh;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, g = lane >> 5;
-  const int q0 = qt * 128;
+  const int q0 = qt * QB;
   const int q = q0 + wave * 32 + lr;
   const bf16* base = qkv + (int64_t)b * S * ld + h * D;
   const uint32_t recs = records_from((int64_t)B * S, (int64_t)b * S, ld, D);
@@ -409,15 +436,15 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_bwd_dq_kernel(cons
   // formed where they are used (the empty statement keeps the compiler from forming them once, before the loop, and
   // holding or spilling them)
   const uint32_t off0 = Img::lane_offset(wave, lane, ld);
-  const uint32_t load_step = (uint32_t)(4 * Img::RPL * ld * 2);
+  const uint32_t load_step = (uint32_t)(WAVES * Img::RPL * ld * 2);
   const uint32_t tile_step = (uint32_t)(64 * ld * 2);
   auto issue = [&](char* st, uint32_t tile_off) {
     uint32_t o = off0 + tile_off;
     asm volatile("" : "+v"(o));
 #pragma unroll
-    for (int i = 0; i < Img::PER_WAVE; ++i) {
-      fa_load_kib(rk, st + (wave + 4 * i) * 1024, o + i * load_step);
-      fa_load_kib(rv, st + Img::BYTES + (wave + 4 * i) * 1024, o + i * load_step);
+    for (int i = 0; i < PW; ++i) {
+      fa_load_kib(rk, st + (wave + WAVES * i) * 1024, o + i * load_step);
+      fa_load_kib(rv, st + Img::BYTES + (wave + WAVES * i) * 1024, o + i * load_step);
     }
   };
 
@@ -444,27 +471,28 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_bwd_dq_kernel(cons
   int2 trb[D / 32];
 #pragma unroll
   for (int ct = 0; ct < D / 32; ++ct) { zero_acc(dq[ct]); trb[ct] = Img::tr_base(ct, lane); }
-  const int kv_end = causal ? min(S, q0 + 128) : S;
+  const int kv_end = causal ? min(S, q0 + QB) : S;
 
-  constexpr int NLD = 2 * Img::PER_WAVE;   // loads of this wave per tile; stages as in the forward kernel
-  issue(lds, 0);
-  if (NS == 3 && 64 < kv_end) issue(lds + 2 * Img::BYTES, tile_step);
+#pragma unroll
+  for (int j = 0; j < NS - 1; ++j)
+    if (j * 64 < kv_end) issue(lds + j * 2 * Img::BYTES, (uint32_t)j * tile_step);
   int sc = 0;
   for (int kv0 = 0; kv0 < kv_end; kv0 += 64, sc = sc == NS - 1 ? 0 : sc + 1) {
-    if (NS == 3 && kv0 + 64 < kv_end) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
-    else __builtin_amdgcn_s_waitcnt(0x0f70);
+    fa_wait_tile<2 * PW>(min(NS - 2, (kv_end - kv0 + 63) / 64 - 1));
     // every wave's part of the tile has landed and its LDS reads of the stage that is filled next have returned; no
-    // fence over global memory, which would wait for the tile that is meant to stay in flight
+    // fence over global memory, which would wait for the tiles that are meant to stay in flight
     block_sync_lds();
     char* cur = lds + sc * 2 * Img::BYTES;
     if (kv0 + 64 * (NS - 1) < kv_end) issue(lds + (sc == 0 ? NS - 1 : sc - 1) * 2 * Img::BYTES, (uint32_t)(kv0 / 64 + NS - 1) * tile_step);
+    // a tile that lies wholly behind this wave's queries under the causal mask adds nothing: the wave only keeps step
+    if (causal && kv0 > q0 + wave * 32 + 31) continue;
     const char* k_lds = cur;
     const char* v_lds = cur + Img::BYTES;
     // K^T fragments of the first 32 keys: issued now, they return behind the MFMAs and the exponentials
     bf16x8 kt[2][D / 32];   // K^T fragments of one half (two 16-key chunks)
     // 32 keys at a time, through to dQ: half the score registers of a whole-tile pass.  A half's K^T fragments are
-    // requested at its start and return behind its MFMAs and exponentials; one set of registers for them and two LDS
-    // stages keep the kernel within 256 registers at head dim 128, which is worth more than either: the MFMAs then write
+    // requested at its start and return behind its MFMAs and exponentials; one set of registers for them keeps the
+    // kernel within 256 registers at head dim 128, which is worth more than the second set: the MFMAs then write
     // ordinary registers (with more than 256 the compiler puts every MFMA result into accumulation registers and
     // copies each score out and in around the vector arithmetic), and two blocks share a CU.
 #pragma unroll
@@ -479,7 +507,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) flash_bwd_dq_kernel(cons
       zero_acc(st);
       zero_acc(dpt);
       mfma_two_chains<D, D == 64 ? 3 : 2>(st, dpt, k_lds, v_lds, u * 32 + lr, g, qf, dof);
-      if ((causal && kv0 + 63 > q0 + wave * 32) || kv0 + 64 > S || q0 + 128 > S) {
+      if ((causal && kv0 + 63 > q0 + wave * 32) || kv0 + 64 > S || q0 + QB > S) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int kv = kv0 + u * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
