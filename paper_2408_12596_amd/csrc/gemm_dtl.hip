@@ -7,10 +7,10 @@
 //  * Tiles travel HBM/L2 -> LDS without passing through registers: each
 //    wavefront issues 16-byte-per-lane buffer loads whose 64 results land in
 //    one contiguous KiB of LDS (lane L at base + 16 L; measured on the device).
-//    The LDS image is swizzled (k-contiguous operands) or padded (k-strided
-//    operands, read with ds_read_b64_tr_b16), so the permutation is applied on
-//    the global side: every lane computes once which 16 bytes belong at its LDS
-//    position.  Rows past the matrix are out of the buffer's range and arrive
+//    The LDS image is swizzled, in 16-byte chunks for k-contiguous operands and
+//    in 64-byte granules for k-strided ones (read with ds_read_b64_tr_b16), and
+//    the permutation is applied on the global side: every lane computes once
+//    which 16 bytes belong at its LDS position.  Rows past the matrix are out of the buffer's range and arrive
 //    as zeros.
 //  * Two LDS stages, one barrier per K step of 64 (four k-slices of 16), no
 //    ds_write instructions at all.  The step is software-pipelined by hand: the
@@ -83,20 +83,25 @@ struct DirectImage {
   }
 };
 
-// k-strided operand: the tile as it lies in memory, 64 k-rows of R values, row stride R*2 + 64 bytes
+// k-strided operand: the tile as it lies in memory, 64 k-rows of R values (R * 2 bytes each, no padding); the 64-byte
+// granules of k-row r change places by XOR with swz(r), chosen so that four consecutive k-rows (what 32 lanes of a
+// transposing read address, 64 bytes of each) fall into four different quarters of the 64 banks: rows of 512 or 256
+// bytes all start at bank 0 (swz = r % 4), rows of 384 or 128 bytes alternate between banks 0 and 32 (swz = (r / 2) % 2).
+// The permutation is applied on the global side: a granule is 64 consecutive bytes of the row there, too.
 template <int R>
 struct StridedImage {
-  static constexpr int STRIDE = R * 2 + 64;
+  static constexpr int STRIDE = R * 2;
   static constexpr int BYTES = 64 * STRIDE;
   static constexpr int LOADS = BYTES / 1024;
   static constexpr int FRAG_READS = 2;
   static constexpr bool MANUAL_WAIT = true;
-  static_assert(BYTES % 1024 == 0, "image must be whole KiB");
+  static_assert(R % 64 == 0 && BYTES % 1024 == 0, "whole granule pairs, whole KiB");
+  __device__ static int swz(int krow) { return (STRIDE % 256 == 0) ? (krow & 3) : ((krow >> 1) & 1); }
   __device__ static uint32_t lane_offset(int idx, int lane, int64_t ld, int64_t r0) {
     const int pos = idx * 1024 + lane * 16;
-    const int krow = pos / STRIDE, col = pos % STRIDE;
-    // lanes that land in the padding fetch the row's first bytes again: never read back, no extra traffic
-    return (uint32_t)(((int64_t)krow * ld + r0 + (col >= R * 2 ? 0 : col / 2)) * 2);
+    const int krow = pos / STRIDE, within = pos % STRIDE;
+    const int col = (((within >> 6) ^ swz(krow)) << 5) + ((within & 63) >> 1);   // in values
+    return (uint32_t)(((int64_t)krow * ld + r0 + col) * 2);
   }
   __device__ static uint32_t k_step(int64_t ld) { return (uint32_t)(DTL_BK * ld * 2); }
   // INVARIANT for the caller: a fragment returned here may feed an MFMA only after an s_waitcnt lgkmcnt(0) that
@@ -108,8 +113,10 @@ struct StridedImage {
   // would serialise the pipeline.  The price: the compiler does not see these reads complete either, so
   // the kernel waits on lgkmcnt by hand before it uses a fragment (MANUAL_WAIT).
   __device__ static bf16x8 frag(const char* lds, int ro, int kk, int lane) {
+    // rows ro .. ro + 31 are one granule of every k-row; both reads take k-rows with the same remainder mod 4
     const int j = lane & 15, gi = (lane >> 4) & 1, lk = lane >> 5;
-    const char* q = lds + (kk * 16 + lk * 8 + (j >> 2)) * STRIDE + (ro + gi * 16 + 4 * (j & 3)) * 2;
+    const int krow = kk * 16 + lk * 8 + (j >> 2);
+    const char* q = lds + krow * STRIDE + (((ro >> 5) ^ swz(krow)) << 6) + gi * 32 + 8 * (j & 3);
     const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)q;
     intx2 lo, hi;
     asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
