@@ -43,7 +43,7 @@ struct DtlGemmParams {
   uint32_t a_records, b_records;   // bytes of A / B that may be read
   int c_float, act;
   float beta;
-  int tiles_m, tiles_n, k_per_split, flip;
+  int tiles_m, tiles_n, k_per_split;
   float* rowsum;        // TN only, may be null: rowsum[m] (+)= sum_k A(k, m)
   int rowsum_accumulate;
 };
@@ -167,23 +167,17 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
     if (i < gp.n && id >= gp.start[i]) pi = i;
   const DtlGemmParams& p = gp.g[pi];
   id -= gp.start[pi];
-  // p.flip: the same walk with the roles of tile rows and tile columns exchanged, so that the four-wide side of a
-  // patch lies along M.  Set for weight gradients with more tile rows than columns: their A operand is the wide
-  // activation gradient (leading dimension 12288 in the fused projection of a 4096-wide model), and with four of
-  // its panels in flight per XCD instead of eight that product ran 2.6 % faster; other shapes showed no difference.
-  const int walk_m = p.flip ? p.tiles_n : p.tiles_m, walk_n = p.flip ? p.tiles_m : p.tiles_n;
-  const int band = 8 * walk_n;
+  const int band = 8 * p.tiles_n;
   const int band_id = id / band;
-  const int rows_in_band = min(8, walk_m - band_id * 8);
+  const int rows_in_band = min(8, p.tiles_m - band_id * 8);
   const int in_band = id - band_id * band;
   // Order inside a band: the tiles that run on an XCD at one time (32 CUs, one or two blocks each) should share as
   // few operand panels as possible, i.e. form a near-square patch.  With many tile columns the row index runs
   // fastest (8 rows x 4-8 columns at a time); with up to 8 columns the column index does (whole tile rows: 4-9 rows x
   // all columns), which also keeps a row's tiles in the same round when a band is smaller than a round.
-  const bool n_fast = walk_n <= 8;
-  const int walk_i = band_id * 8 + (n_fast ? in_band / walk_n : in_band % rows_in_band);
-  const int walk_j = n_fast ? in_band % walk_n : in_band / rows_in_band;
-  const int tile_m = p.flip ? walk_j : walk_i, tile_n = p.flip ? walk_i : walk_j;
+  const bool n_fast = p.tiles_n <= 8;
+  const int tile_m = band_id * 8 + (n_fast ? in_band / p.tiles_n : in_band % rows_in_band);
+  const int tile_n = n_fast ? in_band % p.tiles_n : in_band / rows_in_band;
   const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
   const int64_t kbeg = (int64_t)blockIdx.y * p.k_per_split;
   const int64_t kend = min(p.K, kbeg + p.k_per_split);
@@ -893,7 +887,6 @@ static int dtl_group_impl(hipStream_t s, const GemmArgs* a, int n, bool may_cut,
     DtlGemmParams& p = gp.g[i];
     p.tiles_m = (int)cdiv(a[i].M, BM);
     p.tiles_n = (int)cdiv(a[i].N, BN);
-    p.flip = a[i].layout == GEMM_TN && p.tiles_m > p.tiles_n;
     p.k_per_split = k_per_split;
     gp.start[i] = (int)tiles;
     tiles += (int64_t)p.tiles_m * p.tiles_n;
