@@ -81,6 +81,16 @@ struct DirectImage {
     const int row = ro + (lane & 31);
     return *reinterpret_cast<const bf16x8*>(lds + row * 128 + (((kk * 2 + (lane >> 5)) ^ dtl_swz(row)) << 4));
   }
+  // The same read as assembly, for the kernel form whose stages the compiler cannot tell apart (it would wait for
+  // every tile load in flight before each read it can see).  The invariant of StridedImage::frag holds for it.
+  __device__ static bf16x8 frag_unseen(const char* lds, int ro, int kk, int lane) {
+    const int row = ro + (lane & 31);
+    const char* q = lds + row * 128 + (((kk * 2 + (lane >> 5)) ^ dtl_swz(row)) << 4);
+    const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)q;
+    intx4 f;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(f) : "v"(addr));
+    return __builtin_bit_cast(bf16x8, f);
+  }
 };
 
 // k-strided operand: the tile as it lies in memory, 64 k-rows of R values (R * 2 bytes each, no padding); the 64-byte
@@ -124,6 +134,7 @@ struct StridedImage {
     intx4 f = {lo[0], lo[1], hi[0], hi[1]};
     return __builtin_bit_cast(bf16x8, f);
   }
+  __device__ static bf16x8 frag_unseen(const char* lds, int ro, int kk, int lane) { return frag(lds, ro, kk, lane); }
 };
 
 // One 16-byte-per-lane load of a wavefront straight into the KiB of LDS at `dst`
@@ -152,6 +163,14 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
   // two separate arrays: the compiler can tell the stage being filled from the stage being read
   __shared__ __attribute__((aligned(1024))) char stage0[STAGE];
   __shared__ __attribute__((aligned(1024))) char stage1[STAGE];
+  // RING (256 x 256 tiles on eight waves: all 160 KB of LDS): a third slot for the B operand.  With two stages a
+  // tile's loads can only be issued once its stage is free, i.e. all behind the MFMAs of the last k-slice: eight
+  // loads per wave in a quarter of the step.  With the third slot B's loads of the tile after next go out behind
+  // the first two k-slices, while the tile that last held that slot is two steps gone, and only A's wait for the
+  // barrier.  The slots then rotate with period three against A's two, the compiler cannot tell which is being
+  // filled and which read, and every LDS read of the K loop is assembly (frag_unseen).
+  constexpr bool RING = NW == 8 && BM == 256 && BN == 256;
+  __shared__ __attribute__((aligned(1024))) char slot3[RING ? ImB::BYTES : 16];
 
   // XCD-aware renumbering over the tiles of the whole group (blocks are dealt round-robin to the 8 XCDs; each
   // XCD gets a contiguous run of tiles), then the problem the tile belongs to, then bands of 8 tile rows
@@ -204,15 +223,16 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
   for (int i = 0; i <= LB; ++i) offb[i] = ImB::lane_offset(min(wave + i * NW, ImB::LOADS - 1), lane, p.ldb, n0) + (uint32_t)(kbeg / DTL_BK) * stepb;
 
   // load number l (0 .. NL-1) of this wave's share of a tile into stage st
-  auto load_one = [&](char* st, int l) __attribute__((always_inline)) {
+  auto load_ab = [&](char* sta, char* stb, int l) __attribute__((always_inline)) {
     if (l < LA) {
-      load_kib_to_lds(rsrc_a, st + (wave + l * NW) * 1024, offa[l]);
+      load_kib_to_lds(rsrc_a, sta + (wave + l * NW) * 1024, offa[l]);
       offa[l] += stepa;
     } else {
-      load_kib_to_lds(rsrc_b, st + ImA::BYTES + (wave + (l - LA) * NW) * 1024, offb[l - LA]);
+      load_kib_to_lds(rsrc_b, stb + (wave + (l - LA) * NW) * 1024, offb[l - LA]);
       offb[l - LA] += stepb;
     }
   };
+  auto load_one = [&](char* st, int l) __attribute__((always_inline)) { load_ab(st, st + ImA::BYTES, l); };
   auto load_extra = [&](char* st) __attribute__((always_inline)) {
     if (XA && wave < XA) { load_kib_to_lds(rsrc_a, st + (wave + LA * NW) * 1024, offa[LA]); offa[LA] += stepa; }
     if (XB && wave < XB) { load_kib_to_lds(rsrc_b, st + ImA::BYTES + (wave + LB * NW) * 1024, offb[LB]); offb[LB] += stepb; }
@@ -271,17 +291,24 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
 
   // Fragments of k-slice kk of a stage; f = 0 .. TM+TN-1 in the order the MFMAs first need them
   bf16x8 fa[2][TM], fb[2][TN];
-  auto read_frag = [&](const char* st, int kk, int buf, int f) __attribute__((always_inline)) {
+  auto read_frag = [&](const char* sta, const char* stb, int kk, int buf, int f) __attribute__((always_inline)) {
     // order: a0, b0, b1 .., a1, a2 ..
-    if (f == 0) fa[buf][0] = ImA::frag(st, wm, kk, lane);
-    else if (f <= TN) fb[buf][f - 1] = ImB::frag(st + ImA::BYTES, wn + (f - 1) * 32, kk, lane);
-    else fa[buf][f - TN] = ImA::frag(st, wm + (f - TN) * 32, kk, lane);
+    if (RING) {
+      if (f == 0) fa[buf][0] = ImA::frag_unseen(sta, wm, kk, lane);
+      else if (f <= TN) fb[buf][f - 1] = ImB::frag_unseen(stb, wn + (f - 1) * 32, kk, lane);
+      else fa[buf][f - TN] = ImA::frag_unseen(sta, wm + (f - TN) * 32, kk, lane);
+    } else {
+      if (f == 0) fa[buf][0] = ImA::frag(sta, wm, kk, lane);
+      else if (f <= TN) fb[buf][f - 1] = ImB::frag(stb, wn + (f - 1) * 32, kk, lane);
+      else fa[buf][f - TN] = ImA::frag(sta, wm + (f - TN) * 32, kk, lane);
+    }
   };
   constexpr int NM = TM * TN, NF = TM + TN;
   // One k-slice: the NM MFMAs in source order, with the fragment reads of the next slice (from `rst`, slice rkk) and `nload` tile loads into `lst` dealt evenly between them.  The
   // fences keep the order as written: without them the reads drift together and the MFMAs wait on LDS.
-  auto slice = [&](int buf, const char* rst, int rkk, char* lst, int nload) __attribute__((always_inline)) {
-    if (ImA::MANUAL_WAIT || ImB::MANUAL_WAIT) {
+  // (tile loads: numbers l0 .. l0 + nload - 1 of the wave's share, A's into lsta, B's into lstb)
+  auto slice = [&](int buf, const char* rsta, const char* rstb, int rkk, char* lsta, char* lstb, int l0, int nload) __attribute__((always_inline)) {
+    if (RING || ImA::MANUAL_WAIT || ImB::MANUAL_WAIT) {
       __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this slice's fragments, read during the previous one
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -292,10 +319,10 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
 #pragma unroll
       for (int f = 0; f < NF; ++f)
-        if (f * (NM - SLACK) / NF == x) read_frag(rst, rkk, buf ^ 1, f);
+        if (f * (NM - SLACK) / NF == x) read_frag(rsta, rstb, rkk, buf ^ 1, f);
 #pragma unroll
       for (int l = 0; l < nload; ++l)
-        if (l * NM / nload == x) load_one(lst, l);
+        if (l * NM / nload == x) load_ab(lsta, lstb, l0 + l);
       __builtin_amdgcn_sched_barrier(0);
     }
     if (LAYOUT == GEMM_TN && do_rs) {
@@ -325,24 +352,48 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
   else __builtin_amdgcn_s_waitcnt(0x0f70);
   __syncthreads();
 #pragma unroll
-  for (int f = 0; f < NF; ++f) read_frag(stage0, 0, 0, f);
+  for (int f = 0; f < NF; ++f) read_frag(stage0, stage0 + ImA::BYTES, 0, 0, f);
   __builtin_amdgcn_sched_barrier(0);
-  int par = 0;
-  for (int i = 0; i < nsteps; ++i, par ^= 1) {
-    char* cur = par ? stage1 : stage0;
-    char* nxt = par ? stage0 : stage1;
-    slice(0, cur, 1, nullptr, 0);
-    slice(1, cur, 2, nullptr, 0);
-    slice(0, cur, 3, nullptr, 0);
-    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
-    __syncthreads();
-    // the last two steps have no tile to fetch: their loads zero-fill a stage nobody reads again, and the
-    // last step's fragment reads of the other stage are never used
-    const bool more = i + 2 < nsteps;
-    rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, more ? p.a_records : 0u, 0x00020000);
-    rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, more ? p.b_records : 0u, 0x00020000);
-    load_extra(cur);
-    slice(1, nxt, 0, cur, NL);
+  if (RING) {
+    static_assert(!RING || (XA == 0 && XB == 0 && LB >= 2 && LB <= 15), "whole loads per wave");
+    char *a_cur = stage0, *a_nxt = stage1;
+    char *b_cur = stage0 + ImA::BYTES, *b_nxt = stage1 + ImA::BYTES, *b_free = slot3;
+    for (int i = 0; i < nsteps; ++i) {
+      // the last two steps have no tile to fetch: their loads zero-fill slots nobody reads again
+      const bool more = i + 2 < nsteps;
+      rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, more ? p.b_records : 0u, 0x00020000);
+      slice(0, a_cur, b_cur, 1, nullptr, b_free, LA, LB / 2);
+      slice(1, a_cur, b_cur, 2, nullptr, b_free, LA + LB / 2, LB - LB / 2);
+      slice(0, a_cur, b_cur, 3, nullptr, nullptr, 0, 0);
+      // tile i+1 has landed for this wave (loads complete in order: only B's of tile i+2, just issued, may be on
+      // their way) and its LDS reads have returned; then every wave's.  A bare barrier: a fence over global memory
+      // would wait for the loads that are meant to stay in flight.
+      __builtin_amdgcn_s_waitcnt(0x0070 | LB);   // vmcnt(LB) lgkmcnt(0)
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, more ? p.a_records : 0u, 0x00020000);
+      slice(1, a_nxt, b_nxt, 0, a_cur, nullptr, 0, LA);
+      char* t = a_cur; a_cur = a_nxt; a_nxt = t;
+      t = b_cur; b_cur = b_nxt; b_nxt = b_free; b_free = t;
+    }
+  } else {
+    int par = 0;
+    for (int i = 0; i < nsteps; ++i, par ^= 1) {
+      char* cur = par ? stage1 : stage0;
+      char* nxt = par ? stage0 : stage1;
+      slice(0, cur, cur + ImA::BYTES, 1, nullptr, nullptr, 0, 0);
+      slice(1, cur, cur + ImA::BYTES, 2, nullptr, nullptr, 0, 0);
+      slice(0, cur, cur + ImA::BYTES, 3, nullptr, nullptr, 0, 0);
+      __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+      __syncthreads();
+      // the last two steps have no tile to fetch: their loads zero-fill a stage nobody reads again, and the
+      // last step's fragment reads of the other stage are never used
+      const bool more = i + 2 < nsteps;
+      rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, more ? p.a_records : 0u, 0x00020000);
+      rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, more ? p.b_records : 0u, 0x00020000);
+      load_extra(cur);
+      slice(1, nxt, nxt + ImA::BYTES, 0, cur, cur + ImA::BYTES, 0, NL);
+    }
   }
   // The zero fills must have landed before the stages are reused below.  The last step's fragment reads
   // must have landed too: the compiler does not know the assembly reads are in flight, their destination
