@@ -1,5 +1,5 @@
 // bf16 GEMM on the gfx950 matrix cores with global -> LDS direct loads
-// (buffer_load_dwordx4 ... lds) and a two-stage LDS pipeline.
+// (buffer_load_dwordx4 ... lds) and an LDS pipeline of 2 + 3 slots.
 //
 // Same math and operand layouts as gemm_mfma.hip (NT, NN, TN; float
 // accumulation; fused epilogues); this kernel is the one the large projections
@@ -12,14 +12,18 @@
 //    the permutation is applied on the global side: every lane computes once
 //    which 16 bytes belong at its LDS position.  Rows past the matrix are out of the buffer's range and arrive
 //    as zeros.
-//  * Two LDS stages, one barrier per K step of 64 (four k-slices of 16), no
-//    ds_write instructions at all.  The step is software-pipelined by hand: the
-//    barrier sits before the last k-slice, so that the loads of the tile after
-//    next are issued, one per MFMA, while that slice runs, and the first
-//    fragments of the next tile are read behind the same MFMAs.  Issued in one
-//    burst at the top of a step the loads hold every wavefront at the address
-//    unit's queue while the matrix cores idle (measured: 0.4 us of a 1.5 us
-//    step).  Scheduling fences keep MFMAs, LDS reads and loads in source order.
+//  * Two LDS slots for A tiles and three for B tiles, one barrier per K step of
+//    64 (four k-slices of 16), no ds_write instructions at all.  The step is
+//    software-pipelined by hand: the barrier sits before the last k-slice; B's
+//    loads of the tile after next are issued behind the MFMAs of the first two
+//    slices (into B's third slot), A's behind those of the last slice (into the
+//    slot the barrier has just freed), where the first fragments of the next
+//    tile are read as well.  Issued in one burst the loads hold every wavefront
+//    at the address unit's queue while the matrix cores idle (measured: 0.4 us
+//    of a 1.5 us step at the top of a step; with all of them behind the last
+//    slice, a fifth of the kernel's time).  Scheduling fences keep MFMAs, LDS
+//    reads and loads in source order; every LDS read is assembly, because the
+//    compiler cannot tell the slot being filled from the one being read.
 //  * 256x256 block tile on 8 wavefronts (2 x 4, each 128x64) for large
 //    problems, 256x192 (4 x 2, each 64x96) where that fills the CUs in whole
 //    rounds, 128x128 on 4 wavefronts (two blocks per CU) for small ones.
@@ -68,8 +72,6 @@ template <int R>
 struct DirectImage {
   static constexpr int BYTES = R * 128;
   static constexpr int LOADS = BYTES / 1024;
-  static constexpr int FRAG_READS = 1;
-  static constexpr bool MANUAL_WAIT = false;
   // byte offset (k = 0) of the 16 bytes that belong at LDS position idx*1024 + lane*16
   __device__ static uint32_t lane_offset(int idx, int lane, int64_t ld, int64_t r0) {
     const int row = idx * 8 + (lane >> 3);
@@ -77,13 +79,9 @@ struct DirectImage {
     return (uint32_t)(((r0 + row) * ld + c * 8) * 2);
   }
   __device__ static uint32_t k_step(int64_t ld) { return DTL_BK * 2; }   // bytes added per K step
+  // One 16-byte read per fragment, written as assembly like the transposing reads of StridedImage and for the same
+  // reason; the invariant stated there holds for it.
   __device__ static bf16x8 frag(const char* lds, int ro, int kk, int lane) {
-    const int row = ro + (lane & 31);
-    return *reinterpret_cast<const bf16x8*>(lds + row * 128 + (((kk * 2 + (lane >> 5)) ^ dtl_swz(row)) << 4));
-  }
-  // The same read as assembly, for the kernel form whose stages the compiler cannot tell apart (it would wait for
-  // every tile load in flight before each read it can see).  The invariant of StridedImage::frag holds for it.
-  __device__ static bf16x8 frag_unseen(const char* lds, int ro, int kk, int lane) {
     const int row = ro + (lane & 31);
     const char* q = lds + row * 128 + (((kk * 2 + (lane >> 5)) ^ dtl_swz(row)) << 4);
     const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)q;
@@ -103,8 +101,6 @@ struct StridedImage {
   static constexpr int STRIDE = R * 2;
   static constexpr int BYTES = 64 * STRIDE;
   static constexpr int LOADS = BYTES / 1024;
-  static constexpr int FRAG_READS = 2;
-  static constexpr bool MANUAL_WAIT = true;
   static_assert(R % 64 == 0 && BYTES % 1024 == 0, "whole granule pairs, whole KiB");
   __device__ static int swz(int krow) { return (STRIDE % 256 == 0) ? (krow & 3) : ((krow >> 1) & 1); }
   __device__ static uint32_t lane_offset(int idx, int lane, int64_t ld, int64_t r0) {
@@ -118,10 +114,10 @@ struct StridedImage {
   // follows this call (slice() begins with one), and a fragment that is read but never used must be named as an input
   // of an empty asm statement after such a wait (the kernel does so for the last K step's reads), or the compiler may
   // hand its registers to something else while the read is still in flight.
-  // The transposing reads are written as assembly: the compiler orders the builtin form after every
-  // global -> LDS load in flight (it cannot tell the stage being filled from the one being read), which
-  // would serialise the pipeline.  The price: the compiler does not see these reads complete either, so
-  // the kernel waits on lgkmcnt by hand before it uses a fragment (MANUAL_WAIT).
+  // The reads are written as assembly: the compiler orders the builtin form after every global -> LDS load in
+  // flight (the slots rotate, it cannot tell the one being filled from the one being read), which would serialise
+  // the pipeline.  The price: the compiler does not see these reads complete either, so the kernel waits on
+  // lgkmcnt by hand before it uses a fragment.
   __device__ static bf16x8 frag(const char* lds, int ro, int kk, int lane) {
     // rows ro .. ro + 31 are one granule of every k-row; both reads take k-rows with the same remainder mod 4
     const int j = lane & 15, gi = (lane >> 4) & 1, lk = lane >> 5;
@@ -134,7 +130,6 @@ struct StridedImage {
     intx4 f = {lo[0], lo[1], hi[0], hi[1]};
     return __builtin_bit_cast(bf16x8, f);
   }
-  __device__ static bf16x8 frag_unseen(const char* lds, int ro, int kk, int lane) { return frag(lds, ro, kk, lane); }
 };
 
 // One 16-byte-per-lane load of a wavefront straight into the KiB of LDS at `dst`
@@ -160,17 +155,17 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
   typedef typename ImageA<LAYOUT, BM>::type ImA;
   typedef typename ImageB<LAYOUT, BN>::type ImB;
   constexpr int STAGE = ImA::BYTES + ImB::BYTES;
-  // two separate arrays: the compiler can tell the stage being filled from the stage being read
+  // LDS: two slots for A tiles, three for B tiles (160 KB at 256 x 256, all there is; 136 KB at 256 x 192; 80 and 40
+  // KB for the shapes that run two and four blocks per CU).  With two slots a tile's loads can only go out once its
+  // slot is free, i.e. behind the MFMAs of the last k-slice: eight loads per wave in a quarter of the step, and the
+  // waves queue at the address unit while the matrix cores idle.  With its third slot B's loads of the tile after
+  // next go out behind the first two k-slices (the tile that last held that slot is two steps gone) with more than a
+  // step to land, and only A's wait for the barrier.  The slots rotate with period three against A's two, the
+  // compiler cannot tell which is being filled and which read, and every LDS read of the K loop is assembly.
+  // stage0 / stage1 (A slot + B slot each) double as the epilogue's staging memory.
   __shared__ __attribute__((aligned(1024))) char stage0[STAGE];
   __shared__ __attribute__((aligned(1024))) char stage1[STAGE];
-  // RING (256 x 256 tiles on eight waves: all 160 KB of LDS): a third slot for the B operand.  With two stages a
-  // tile's loads can only be issued once its stage is free, i.e. all behind the MFMAs of the last k-slice: eight
-  // loads per wave in a quarter of the step.  With the third slot B's loads of the tile after next go out behind
-  // the first two k-slices, while the tile that last held that slot is two steps gone, and only A's wait for the
-  // barrier.  The slots then rotate with period three against A's two, the compiler cannot tell which is being
-  // filled and which read, and every LDS read of the K loop is assembly (frag_unseen).
-  constexpr bool RING = NW == 8 && BM == 256 && BN == 256;
-  __shared__ __attribute__((aligned(1024))) char slot3[RING ? ImB::BYTES : 16];
+  __shared__ __attribute__((aligned(1024))) char slot3[ImB::BYTES];
 
   // XCD-aware renumbering over the tiles of the whole group (blocks are dealt round-robin to the 8 XCDs; each
   // XCD gets a contiguous run of tiles), then the problem the tile belongs to, then bands of 8 tile rows
@@ -211,18 +206,17 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
   __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, p.a_records, 0x00020000);
   __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, p.b_records, 0x00020000);
 
-  // Per-lane source offsets of this wave's loads: wave w takes KiB w, w + NW, ... of each image; when the
-  // KiB count is not a multiple of NW the first waves take one more (XA / XB).
+  // Per-lane source offsets of this wave's loads: wave w takes KiB w, w + NW, ... of each image
   constexpr int LA = ImA::LOADS / NW, LB = ImB::LOADS / NW, NL = LA + LB;
-  constexpr int XA = ImA::LOADS % NW, XB = ImB::LOADS % NW;
-  uint32_t offa[LA + 1], offb[LB + 1];
+  static_assert(ImA::LOADS % NW == 0 && ImB::LOADS % NW == 0 && LB >= 2 && LB <= 15, "whole loads per wave; B's in two parts; the wait's field");
+  uint32_t offa[LA], offb[LB];
   const uint32_t stepa = ImA::k_step(p.lda), stepb = ImB::k_step(p.ldb);
 #pragma unroll
-  for (int i = 0; i <= LA; ++i) offa[i] = ImA::lane_offset(min(wave + i * NW, ImA::LOADS - 1), lane, p.lda, m0) + (uint32_t)(kbeg / DTL_BK) * stepa;
+  for (int i = 0; i < LA; ++i) offa[i] = ImA::lane_offset(wave + i * NW, lane, p.lda, m0) + (uint32_t)(kbeg / DTL_BK) * stepa;
 #pragma unroll
-  for (int i = 0; i <= LB; ++i) offb[i] = ImB::lane_offset(min(wave + i * NW, ImB::LOADS - 1), lane, p.ldb, n0) + (uint32_t)(kbeg / DTL_BK) * stepb;
+  for (int i = 0; i < LB; ++i) offb[i] = ImB::lane_offset(wave + i * NW, lane, p.ldb, n0) + (uint32_t)(kbeg / DTL_BK) * stepb;
 
-  // load number l (0 .. NL-1) of this wave's share of a tile into stage st
+  // load number l (0 .. NL-1) of this wave's share of a tile: A's first (into slot sta), then B's (into slot stb)
   auto load_ab = [&](char* sta, char* stb, int l) __attribute__((always_inline)) {
     if (l < LA) {
       load_kib_to_lds(rsrc_a, sta + (wave + l * NW) * 1024, offa[l]);
@@ -232,15 +226,9 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
       offb[l - LA] += stepb;
     }
   };
-  auto load_one = [&](char* st, int l) __attribute__((always_inline)) { load_ab(st, st + ImA::BYTES, l); };
-  auto load_extra = [&](char* st) __attribute__((always_inline)) {
-    if (XA && wave < XA) { load_kib_to_lds(rsrc_a, st + (wave + LA * NW) * 1024, offa[LA]); offa[LA] += stepa; }
-    if (XB && wave < XB) { load_kib_to_lds(rsrc_b, st + ImA::BYTES + (wave + LB * NW) * 1024, offb[LB]); offb[LB] += stepb; }
-  };
   auto load_tile = [&](char* st) __attribute__((always_inline)) {
-    load_extra(st);
 #pragma unroll
-    for (int l = 0; l < NL; ++l) load_one(st, l);
+    for (int l = 0; l < NL; ++l) load_ab(st, st + ImA::BYTES, l);
   };
 
   // Second operand of the epilogue (the stashed gelu' factor for the backward of GeLU, or the residual; the launcher admits
@@ -293,25 +281,16 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
   bf16x8 fa[2][TM], fb[2][TN];
   auto read_frag = [&](const char* sta, const char* stb, int kk, int buf, int f) __attribute__((always_inline)) {
     // order: a0, b0, b1 .., a1, a2 ..
-    if (RING) {
-      if (f == 0) fa[buf][0] = ImA::frag_unseen(sta, wm, kk, lane);
-      else if (f <= TN) fb[buf][f - 1] = ImB::frag_unseen(stb, wn + (f - 1) * 32, kk, lane);
-      else fa[buf][f - TN] = ImA::frag_unseen(sta, wm + (f - TN) * 32, kk, lane);
-    } else {
-      if (f == 0) fa[buf][0] = ImA::frag(sta, wm, kk, lane);
-      else if (f <= TN) fb[buf][f - 1] = ImB::frag(stb, wn + (f - 1) * 32, kk, lane);
-      else fa[buf][f - TN] = ImA::frag(sta, wm + (f - TN) * 32, kk, lane);
-    }
+    if (f == 0) fa[buf][0] = ImA::frag(sta, wm, kk, lane);
+    else if (f <= TN) fb[buf][f - 1] = ImB::frag(stb, wn + (f - 1) * 32, kk, lane);
+    else fa[buf][f - TN] = ImA::frag(sta, wm + (f - TN) * 32, kk, lane);
   };
   constexpr int NM = TM * TN, NF = TM + TN;
-  // One k-slice: the NM MFMAs in source order, with the fragment reads of the next slice (from `rst`, slice rkk) and `nload` tile loads into `lst` dealt evenly between them.  The
-  // fences keep the order as written: without them the reads drift together and the MFMAs wait on LDS.
-  // (tile loads: numbers l0 .. l0 + nload - 1 of the wave's share, A's into lsta, B's into lstb)
+  // One k-slice: the NM MFMAs in source order, with the fragment reads of the next slice (slots rsta / rstb, slice rkk) and the tile loads number l0 .. l0 + nload - 1 of the wave's share
+  // (A's into slot lsta, B's into lstb) dealt evenly between them.  The fences keep the order as written: without them the reads drift together and the MFMAs wait on LDS.
   auto slice = [&](int buf, const char* rsta, const char* rstb, int rkk, char* lsta, char* lstb, int l0, int nload) __attribute__((always_inline)) {
-    if (RING || ImA::MANUAL_WAIT || ImB::MANUAL_WAIT) {
-      __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this slice's fragments, read during the previous one
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this slice's fragments, read during the previous one
+    __builtin_amdgcn_sched_barrier(0);
     constexpr int SLACK = NM >= 6 ? 2 : 1;   // MFMAs left after the last read is issued
 #pragma unroll
     for (int x = 0; x < NM; ++x) {
@@ -340,60 +319,41 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
     }
   };
 
-  // Software pipeline over K steps of 64 (four k-slices).  At the top of step i the fragments of slice 0
-  // are in registers and tile i+1 is in flight into the other stage.  Slices 0..2 run; then the wave
-  // waits for its own loads and for its last LDS reads, the barrier tells it that every wave has done
-  // so (tile i+1 complete, stage of tile i no longer read); slice 3 runs while the loads of tile i+2
-  // start into the freed stage and slice 0 of tile i+1 is read.
+  // Software pipeline over K steps of 64 (four k-slices).  At the top of step i the fragments of slice 0 are in
+  // registers and tile i+1 is in flight or landed.  Slices 0..2 run, B's loads of tile i+2 going out behind the first
+  // two; then the wave waits for its own loads of tile i+1 and for its last LDS reads, the barrier tells it that
+  // every wave has done so (tile i+1 complete, slots of tile i no longer read); slice 3 runs while A's loads of tile
+  // i+2 start into the freed A slot and slice 0 of tile i+1 is read.
   const int nsteps = (int)((kend - kbeg + DTL_BK - 1) / DTL_BK);
   load_tile(stage0);
   if (nsteps > 1) load_tile(stage1);
-  if (nsteps > 1) __builtin_amdgcn_s_waitcnt(0x0f70 | (NL & 15) | ((NL >> 4) << 14));   // vmcnt(NL): tile 0 landed (extras of tile 1 are older than its regular loads)
+  if (nsteps > 1) __builtin_amdgcn_s_waitcnt(0x0f70 | (NL & 15) | ((NL >> 4) << 14));   // vmcnt(NL): tile 0 landed, tile 1 may be on its way
   else __builtin_amdgcn_s_waitcnt(0x0f70);
-  __syncthreads();
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int f = 0; f < NF; ++f) read_frag(stage0, stage0 + ImA::BYTES, 0, 0, f);
   __builtin_amdgcn_sched_barrier(0);
-  if (RING) {
-    static_assert(!RING || (XA == 0 && XB == 0 && LB >= 2 && LB <= 15), "whole loads per wave");
-    char *a_cur = stage0, *a_nxt = stage1;
-    char *b_cur = stage0 + ImA::BYTES, *b_nxt = stage1 + ImA::BYTES, *b_free = slot3;
-    for (int i = 0; i < nsteps; ++i) {
-      // the last two steps have no tile to fetch: their loads zero-fill slots nobody reads again
-      const bool more = i + 2 < nsteps;
-      rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, more ? p.b_records : 0u, 0x00020000);
-      slice(0, a_cur, b_cur, 1, nullptr, b_free, LA, LB / 2);
-      slice(1, a_cur, b_cur, 2, nullptr, b_free, LA + LB / 2, LB - LB / 2);
-      slice(0, a_cur, b_cur, 3, nullptr, nullptr, 0, 0);
-      // tile i+1 has landed for this wave (loads complete in order: only B's of tile i+2, just issued, may be on
-      // their way) and its LDS reads have returned; then every wave's.  A bare barrier: a fence over global memory
-      // would wait for the loads that are meant to stay in flight.
-      __builtin_amdgcn_s_waitcnt(0x0070 | LB);   // vmcnt(LB) lgkmcnt(0)
-      __builtin_amdgcn_s_barrier();
-      __builtin_amdgcn_sched_barrier(0);
-      rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, more ? p.a_records : 0u, 0x00020000);
-      slice(1, a_nxt, b_nxt, 0, a_cur, nullptr, 0, LA);
-      char* t = a_cur; a_cur = a_nxt; a_nxt = t;
-      t = b_cur; b_cur = b_nxt; b_nxt = b_free; b_free = t;
-    }
-  } else {
-    int par = 0;
-    for (int i = 0; i < nsteps; ++i, par ^= 1) {
-      char* cur = par ? stage1 : stage0;
-      char* nxt = par ? stage0 : stage1;
-      slice(0, cur, cur + ImA::BYTES, 1, nullptr, nullptr, 0, 0);
-      slice(1, cur, cur + ImA::BYTES, 2, nullptr, nullptr, 0, 0);
-      slice(0, cur, cur + ImA::BYTES, 3, nullptr, nullptr, 0, 0);
-      __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
-      __syncthreads();
-      // the last two steps have no tile to fetch: their loads zero-fill a stage nobody reads again, and the
-      // last step's fragment reads of the other stage are never used
-      const bool more = i + 2 < nsteps;
-      rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, more ? p.a_records : 0u, 0x00020000);
-      rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, more ? p.b_records : 0u, 0x00020000);
-      load_extra(cur);
-      slice(1, nxt, nxt + ImA::BYTES, 0, cur, cur + ImA::BYTES, 0, NL);
-    }
+  char *a_cur = stage0, *a_nxt = stage1;
+  char *b_cur = stage0 + ImA::BYTES, *b_nxt = stage1 + ImA::BYTES, *b_free = slot3;
+  for (int i = 0; i < nsteps; ++i) {
+    // the last two steps have no tile to fetch: their loads zero-fill slots nobody reads again, and the last step's
+    // fragment reads of the next slots are never used
+    const bool more = i + 2 < nsteps;
+    rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)p.B, 0, more ? p.b_records : 0u, 0x00020000);
+    slice(0, a_cur, b_cur, 1, nullptr, b_free, LA, LB / 2);
+    slice(1, a_cur, b_cur, 2, nullptr, b_free, LA + LB / 2, LB - LB / 2);
+    slice(0, a_cur, b_cur, 3, nullptr, nullptr, 0, 0);
+    // Tile i+1 has landed for this wave (loads complete in order: only B's of tile i+2, just issued, may be on
+    // their way) and its LDS reads have returned; then every wave's.  A bare barrier: a fence over global memory
+    // would wait for the loads that are meant to stay in flight.
+    __builtin_amdgcn_s_waitcnt(0x0070 | LB);   // vmcnt(LB) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, more ? p.a_records : 0u, 0x00020000);
+    slice(1, a_nxt, b_nxt, 0, a_cur, nullptr, 0, LA);
+    char* t = a_cur; a_cur = a_nxt; a_nxt = t;
+    t = b_cur; b_cur = b_nxt; b_nxt = b_free; b_free = t;
   }
   // The zero fills must have landed before the stages are reused below.  The last step's fragment reads
   // must have landed too: the compiler does not know the assembly reads are in flight, their destination
