@@ -85,6 +85,18 @@ def test_gemm_ragged_mid_size_on_sampled_outputs(layout, M, N, K, c_float):
     check_sampled(layout, M, N, K, c_float)
 
 
+# contractions of one to four K steps at the sizes of RAGGED: the kernel's pipeline is three tiles deep (the first two
+# tiles are requested before the loop, the third inside its first step), so these are its start and its end with
+# nothing between
+SHORT_K = [(layout, M, N, K) for layout in (pb.GEMM_NT, pb.GEMM_NN, pb.GEMM_TN)
+           for (M, N) in ((3000, 2000), (5000, 3000), (16000, 2300)) for K in (64, 128, 192, 256)]
+
+
+@pytest.mark.parametrize("layout,M,N,K", SHORT_K)
+def test_gemm_short_contractions_on_sampled_outputs(layout, M, N, K):
+    check_sampled(layout, M, N, K, False)
+
+
 @pytest.mark.parametrize("layout,M,N,K", FULL)
 def test_gemm_full_size_on_sampled_outputs(layout, M, N, K):
     check_sampled(layout, M, N, K, True)
