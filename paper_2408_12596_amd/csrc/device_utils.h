@@ -154,6 +154,16 @@ __device__ inline void span_store_f2(float a, float b, __amdgpu_buffer_rsrc_t rs
 // __syncthreads() it carries no fence over global memory, which would wait for every load and store in flight.
 __device__ inline void block_sync_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// streaming (non-temporal) access to the 16 bytes of a Vec
+template <typename T>
+__device__ inline void vec_load_nt(Vec<T>& v, const T* p) {
+  v.raw = __builtin_bit_cast(decltype(v.raw), __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)));
+}
+template <typename T>
+__device__ inline void vec_store_nt(const Vec<T>& v, T* p) {
+  __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v.raw), reinterpret_cast<u32x4*>(p));
+}
+
 // streaming (non-temporal) 16-byte / 8-byte accesses: index i counts vectors
 typedef float nt_f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t nt_u2 __attribute__((ext_vector_type(2)));

@@ -6,6 +6,7 @@
 #include <hip/hip_ext.h>
 #include "device_utils.h"
 #include <algorithm>
+#include <type_traits>
 
 #define DISPATCH_DTYPE(dtype, ...)                                         \
   do {                                                                      \
@@ -890,53 +891,90 @@ int colsum(hipStream_t s, int dtype, int64_t T_, int64_t N, const void* x, int64
 // ---------------------------------------------------------------------------
 // SwiGLU on the fused [T, 2F] gate|up activation: g = silu(hg) * hu
 // ---------------------------------------------------------------------------
+// A block column owns 256 vectors of a row, a block row walks the rows two at a time (both rows' loads in flight
+// before either is worked on; four at a time measured the same); no index division anywhere; streaming accesses (the
+// forward kernel 95 -> 85 us on 8192 x 11008, 0.80 of the HBM rate; the backward kernel, five streams, stays at 0.72).  sigmoid(a) = 1 / (1 + 2^(-a log2 e)) with the hardware
+// exp2, and for bfloat16 outputs the hardware reciprocal (1 ulp; the quotient in float costs ten instructions a value).
 template <typename T>
-__global__ void swiglu_fwd_kernel(const T* __restrict__ hgu, T* __restrict__ g, int64_t rows, int F) {
-  constexpr int VN = Vec<T>::N;
-  const int64_t per_row = F / VN;
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (; i < rows * per_row; i += stride) {
-    int64_t r = i / per_row, c = (i % per_row) * VN;
-    float a[VN], b[VN], o[VN];
-    Vec<T> v; v.load(hgu + r * 2 * F + c); v.unpack(a);
-    v.load(hgu + r * 2 * F + F + c); v.unpack(b);
+__device__ inline float swiglu_sigmoid(float a) {
+  const float e = __builtin_amdgcn_exp2f(a * -1.4426950408889634f);
+  if (std::is_same<T, float>::value) return 1.0f / (1.0f + e);
+  return __builtin_amdgcn_rcpf(1.0f + e);
+}
+template <typename T>
+__global__ void __launch_bounds__(256) swiglu_fwd_kernel(const T* __restrict__ hgu, T* __restrict__ g, int64_t rows, int F) {
+  constexpr int VN = Vec<T>::N, R = 2;
+  const int c = (int)(blockIdx.x * 256 + threadIdx.x) * VN;
+  if (c >= F) return;
+  for (int64_t r0 = (int64_t)blockIdx.y * R; r0 < rows; r0 += (int64_t)gridDim.y * R) {
+    Vec<T> va[R], vb[R];
 #pragma unroll
-    for (int k = 0; k < VN; ++k) o[k] = a[k] / (1.0f + __expf(-a[k])) * b[k];
-    v.pack(o); v.store(g + r * F + c);
+    for (int u = 0; u < R; ++u)
+      if (r0 + u < rows) {
+        vec_load_nt(va[u], hgu + (r0 + u) * 2 * F + c);
+        vec_load_nt(vb[u], hgu + (r0 + u) * 2 * F + F + c);
+      }
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+      if (r0 + u < rows) {
+        float a[VN], b[VN], o[VN];
+        va[u].unpack(a);
+        vb[u].unpack(b);
+#pragma unroll
+        for (int k = 0; k < VN; ++k) o[k] = a[k] * swiglu_sigmoid<T>(a[k]) * b[k];
+        Vec<T> v;
+        v.pack(o);
+        vec_store_nt(v, g + (r0 + u) * F + c);
+      }
   }
 }
 template <typename T>
-__global__ void swiglu_bwd_kernel(const T* __restrict__ dg, const T* __restrict__ hgu, T* __restrict__ dhgu, int64_t rows, int F) {
-  constexpr int VN = Vec<T>::N;
-  const int64_t per_row = F / VN;
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (; i < rows * per_row; i += stride) {
-    int64_t r = i / per_row, c = (i % per_row) * VN;
-    float a[VN], b[VN], d[VN], oa[VN], ob[VN];
-    Vec<T> v; v.load(hgu + r * 2 * F + c); v.unpack(a);
-    v.load(hgu + r * 2 * F + F + c); v.unpack(b);
-    v.load(dg + r * F + c); v.unpack(d);
+__global__ void __launch_bounds__(256) swiglu_bwd_kernel(const T* __restrict__ dg, const T* __restrict__ hgu, T* __restrict__ dhgu, int64_t rows, int F) {
+  constexpr int VN = Vec<T>::N, R = 2;
+  const int c = (int)(blockIdx.x * 256 + threadIdx.x) * VN;
+  if (c >= F) return;
+  for (int64_t r0 = (int64_t)blockIdx.y * R; r0 < rows; r0 += (int64_t)gridDim.y * R) {
+    Vec<T> va[R], vb[R], vd[R];
 #pragma unroll
-    for (int k = 0; k < VN; ++k) {
-      float sg = 1.0f / (1.0f + __expf(-a[k]));
-      oa[k] = d[k] * b[k] * (sg + a[k] * sg * (1.0f - sg));
-      ob[k] = d[k] * a[k] * sg;
-    }
-    v.pack(oa); v.store(dhgu + r * 2 * F + c);
-    v.pack(ob); v.store(dhgu + r * 2 * F + F + c);
+    for (int u = 0; u < R; ++u)
+      if (r0 + u < rows) {
+        vec_load_nt(va[u], hgu + (r0 + u) * 2 * F + c);
+        vec_load_nt(vb[u], hgu + (r0 + u) * 2 * F + F + c);
+        vec_load_nt(vd[u], dg + (r0 + u) * F + c);
+      }
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+      if (r0 + u < rows) {
+        float a[VN], b[VN], d[VN], oa[VN], ob[VN];
+        va[u].unpack(a);
+        vb[u].unpack(b);
+        vd[u].unpack(d);
+#pragma unroll
+        for (int k = 0; k < VN; ++k) {
+          const float sg = swiglu_sigmoid<T>(a[k]);
+          oa[k] = d[k] * b[k] * (sg + a[k] * sg * (1.0f - sg));
+          ob[k] = d[k] * a[k] * sg;
+        }
+        Vec<T> v;
+        v.pack(oa);
+        vec_store_nt(v, dhgu + (r0 + u) * 2 * F + c);
+        v.pack(ob);
+        vec_store_nt(v, dhgu + (r0 + u) * 2 * F + F + c);
+      }
   }
+}
+static dim3 swiglu_grid(int64_t rows, int F, int vn) {
+  return dim3((unsigned)cdiv(F / vn, 256), (unsigned)std::min<int64_t>(cdiv(rows, 2), 65535));
 }
 int swiglu_fwd(hipStream_t s, int dtype, int64_t T_, int F, const void* hgu, void* g) {
   if (T_ == 0) return POPLAR_OK;
-  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(swiglu_fwd_kernel<T>, dim3(grid_for(T_ * F / Vec<T>::N, 256)), dim3(256), 0, s, (const T*)hgu, (T*)g, T_, F));
+  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(swiglu_fwd_kernel<T>, swiglu_grid(T_, F, Vec<T>::N), dim3(256), 0, s, (const T*)hgu, (T*)g, T_, F));
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }
 int swiglu_bwd(hipStream_t s, int dtype, int64_t T_, int F, const void* dg, const void* hgu, void* dhgu) {
   if (T_ == 0) return POPLAR_OK;
-  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(swiglu_bwd_kernel<T>, dim3(grid_for(T_ * F / Vec<T>::N, 256)), dim3(256), 0, s, (const T*)dg, (const T*)hgu, (T*)dhgu, T_, F));
+  DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(swiglu_bwd_kernel<T>, swiglu_grid(T_, F, Vec<T>::N), dim3(256), 0, s, (const T*)dg, (const T*)hgu, (T*)dhgu, T_, F));
   POPLAR_LAUNCH_CHECK();
   return POPLAR_OK;
 }
