@@ -46,7 +46,7 @@ PEAK_HBM_GBS = 8000.0
 # FETCH_SIZE and WRITE_SIZE, scaled by the factors a copy of known size gives, summarised under profiles/.
 # Per kernel launch (355 per step: a weight-gradient group or a product whose partial last round is cut off is two).
 # Valid for the GEMM kernel as profiled; set to None when that kernel changes until the counters are taken again.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 1607e6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 1606e6
 # Events ride on the GEMM launches of every GEMM_EVENTS_EVERY-th timed step (the first, the sixth, ...): an attached
 # pair of events costs about 4.5 us per launch, 0.5 ms on a step's 111 launches, and the headline number should
 # carry as little of the instrument as the measurement allows.
