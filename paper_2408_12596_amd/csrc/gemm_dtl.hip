@@ -304,7 +304,7 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) gemm_dtl_kernel(DtlGroupParam
         if (l * NM / nload == x) load_ab(lsta, lstb, l0 + l);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (LAYOUT == GEMM_TN && do_rs) {
+    if (LAYOUT == GEMM_TN && __builtin_expect(do_rs, 0)) {   // rare (the first column of tiles, models with biases): kept out of the MFMA stream's straight path
       typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
       const bf16x2_t one2 = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
 #pragma unroll
