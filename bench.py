@@ -279,8 +279,9 @@ def rank_hbm_figures(P_model, emb, shard_valid, stage, p, tied):
         gathered = 2 * P_model + (emb if tied else -emb)   # a tied head gathers the embedding matrix again in both passes
         out["gather"] = {"achieved": 4.0 * gathered / t / 1e9, "unit": "GB/s", "peak": PEAK_HBM_GBS, "bytes_per_elem": 4, "elems": gathered, "ms": t * 1e3}
     if stage >= 2:
-        out["local_reduce"] = {"achieved": 12.0 * shard_valid / p["t_reduce_bwd"] / 1e9, "unit": "GB/s", "peak": PEAK_HBM_GBS,
-                               "bytes_per_elem": 12, "elems": shard_valid, "ms": p["t_reduce_bwd"] * 1e3}
+        red = p["reduce_elems"]   # what the step's reduce launches moved: more than the shard where a tied embedding matrix lies in it
+        out["local_reduce"] = {"achieved": 12.0 * red / p["t_reduce_bwd"] / 1e9, "unit": "GB/s", "peak": PEAK_HBM_GBS,
+                               "bytes_per_elem": 12, "elems": red, "ms": p["t_reduce_bwd"] * 1e3}
     for v in out.values():
         v["frac"] = v["achieved"] / v["peak"]
     return out
@@ -424,7 +425,7 @@ def main():
         "attention": {"achieved": f_attn / t_attn / 1e12 if t_attn > 0 else 0.0, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS,
                       "frac": (f_attn / t_attn / 1e12 / PEAK_BF16_TFLOPS) if t_attn > 0 else 0.0, "head_dim": model["H"] // model["nh"],
                       "ms_per_step": t_attn * 1e3},
-        "hbm_kernels": rank_hbm_figures(r.P, r.emb, r.valid, stage, {k: mean(k) for k in ("t_adam", "t_gather_fwd", "t_gather_bwd", "t_reduce_bwd")}, model["arch"] == "gpt"),
+        "hbm_kernels": rank_hbm_figures(r.P, r.emb, r.valid, stage, dict({k: mean(k) for k in ("t_adam", "t_gather_fwd", "t_gather_bwd", "t_reduce_bwd")}, reduce_elems=profs[-1]["reduce_elems"]), model["arch"] == "gpt"),
         "loss": profs[-1]["loss"],
         "device": device_info(pb, torch),
     }

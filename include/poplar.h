@@ -293,6 +293,9 @@ typedef struct poplar_profile {
   int64_t measured_bytes;       /* with memory hooks: what bytes_now() returned while the step's workspace was held; else 0 */
   int32_t n_gemm_kernels;       /* GEMM kernels inside the n_gemm timed spans (a grouped launch whose partial last round is cut
                                    off, or a product cut along N, is one span and two kernels) */
+  int64_t reduce_elems;         /* stage 2/3: gradient elements the local reduces of the step added into the shard buffer (12 bytes
+                                   of memory traffic each).  More than the shard's length where a tied embedding matrix lies in the
+                                   shard: its head term and its embedding term are reduced one after the other. */
 } poplar_profile;
 
 /* What the current HIP device reports: compute units, the peak engine clock in

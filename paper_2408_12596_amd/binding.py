@@ -52,7 +52,7 @@ class Profile(C.Structure):
                 ("t_adam", C.c_double), ("t_consumed", C.c_double), ("accounted_bytes", C.c_int64),
                 ("flops", C.c_double), ("loss", C.c_float), ("t_gemm", C.c_double), ("gemm_flops", C.c_double),
                 ("t_attn", C.c_double), ("attn_flops", C.c_double), ("n_gemm", C.c_int32), ("n_attn", C.c_int32),
-                ("measured_bytes", C.c_int64), ("n_gemm_kernels", C.c_int32)]
+                ("measured_bytes", C.c_int64), ("n_gemm_kernels", C.c_int32), ("reduce_elems", C.c_int64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

@@ -271,6 +271,7 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
   struct StepScope { poplar_ctx* c; ~StepScope() { c->in_step = false; } } scope{ctx};
   EventCursor ev{ctx};
   std::vector<Span> sp_gf, sp_gb, sp_red;
+  int64_t red_elems = 0;   // elements the local reduces of this step add into the shard buffer
   hipEvent_t e_start, e_mid, e_bwd_end, e_adam_end;
 
   // parameter access: stages 0-2 read the resident compute copy; stage 3
@@ -296,7 +297,10 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
     POPLAR_TRY(ctx_take(ctx, &sn.a));
     POPLAR_TRY(ctx_take(ctx, &sn.b));
     POPLAR_TRY(zero2_reduce_local(s, st.grads, g_unit, lo, hi, sh_off, sh_len, sn.a, sn.b, &launched));
-    if (launched) sp_red.push_back(sn);   // a unit outside the shard moves nothing: no span
+    if (launched) {   // a unit outside the shard moves nothing: no span
+      sp_red.push_back(sn);
+      red_elems += std::min(hi, sh_off + sh_len) - std::max(lo, sh_off);
+    }
     return POPLAR_OK;
   };
 
@@ -390,6 +394,7 @@ static int run_step(poplar_ctx* ctx, int stage, int B, int forward_only, poplar_
     out->t_adam = ms * 1e-3;
     POPLAR_TRY(span_seconds(sp_gb, &out->t_gather_bwd));
     POPLAR_TRY(span_seconds(sp_red, &out->t_reduce_bwd));
+    out->reduce_elems = red_elems;
   }
   out->t_consumed = out->t_fwd + out->t_bwd;
   if (stage >= 2) out->t_consumed -= out->t_reduce_bwd;
@@ -539,7 +544,7 @@ extern "C" int poplar_accum_step(poplar_ctx* ctx, int32_t stage, int32_t n_micro
     tot.t_fwd += pr.t_fwd; tot.t_bwd += pr.t_bwd; tot.t_gather_fwd += pr.t_gather_fwd; tot.t_gather_bwd += pr.t_gather_bwd;
     tot.t_reduce_bwd += pr.t_reduce_bwd; tot.t_consumed += pr.t_consumed; tot.flops += pr.flops; tot.loss += pr.loss;
     tot.t_gemm += pr.t_gemm; tot.gemm_flops += pr.gemm_flops; tot.t_attn += pr.t_attn; tot.attn_flops += pr.attn_flops;
-    tot.n_gemm += pr.n_gemm; tot.n_attn += pr.n_attn; tot.n_gemm_kernels += pr.n_gemm_kernels;
+    tot.n_gemm += pr.n_gemm; tot.n_attn += pr.n_attn; tot.n_gemm_kernels += pr.n_gemm_kernels; tot.reduce_elems += pr.reduce_elems;
     if (pr.accounted_bytes > tot.accounted_bytes) tot.accounted_bytes = pr.accounted_bytes;
     if (ms.optimizer) tot.t_adam = pr.t_adam;
   }

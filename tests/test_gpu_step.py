@@ -551,6 +551,26 @@ def test_search_mbs_against_a_measuring_allocator(stage):
     assert rk2.ctx.profile_step(stage, 3)["measured_bytes"] == 0
 
 
+@pytest.mark.parametrize("rank", [0, 3])
+@pytest.mark.parametrize("stage", [1, 2, 3])
+@pytest.mark.parametrize("arch", ["gpt", "llama"])
+def test_profile_counts_the_elements_its_local_reduces_move(arch, stage, rank):
+    """reduce_elems: nothing below stage 2; at stages 2 and 3 every gradient element of the rank's shard once, and the
+    part of a tied embedding matrix that lies in the shard once more (its head term and its embedding term are
+    reduced one after the other: Appendix "Details about ZeRO", gradients leave for their owner as they are formed)."""
+    model, world, B = MODELS[arch], 4, 2
+    rk = Rank(model, "bf16", stage, world, rank, max_batch=2)
+    p = rk.ctx.profile_step(stage, B)
+    sync()
+    if stage < 2:
+        assert p["reduce_elems"] == 0 and p["t_reduce_bwd"] == 0.0
+        return
+    lo, hi = rk.off, min(rk.off + rk.len, rk.P)
+    tied = model["V"] * model["H"] if arch == "gpt" else 0      # the flat vector begins with the embedding matrix
+    assert p["reduce_elems"] == (hi - lo) + max(0, min(hi, tied) - lo)
+    assert p["t_reduce_bwd"] > 0.0
+
+
 def test_kernel_timing_selects_and_counts_the_launches():
     """Per-launch timing inside a profiled step: what is selected is counted with its algorithmic flop, the rest is not,
     and the summed kernel time fits inside the step's forward + backward time."""
